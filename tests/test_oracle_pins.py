@@ -1,0 +1,381 @@
+"""Pins for the float64 CPU oracle: closed forms, invariants, library routines
+and brute force -- nothing here compares the oracle with itself or with the
+GPU path."""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy.special import softmax as sp_softmax
+
+import oracle
+from oracle import Config, SCALE_ADAPTIVE, SCALE_FIXED
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rnd(seed, *shape):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+def harmonic(m):
+    return np.concatenate([[0.0], np.cumsum(1.0 / np.arange(1, m + 1))])
+
+
+# --------------------------------------------------------------- lambda ----
+def test_lambda_hand_values():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "lambda_values.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 4
+    for i, k, d, val in rows:
+        got = oracle.lam(int(i), int(k), int(d), floor=0.0)
+        assert abs(got - float(val)) < 5e-7, (i, k, d, got)
+
+
+def test_lambda_identities():
+    d, k = 128, 1000
+    assert oracle.lam(k, k, d, floor=0.0) == 0.0
+    assert oracle.lam(k // 2, k, d, floor=0.0) == 0.0            # clamped log
+    assert oracle.lam(k // 2, k, d, floor=-1.0) == pytest.approx(1 / math.sqrt(d), rel=1e-15)
+    # lambda = 1/sqrt(d) exactly where ln(c/k) = 1/2; c is an integer, so check
+    # the two integers that bracket k*sqrt(e)
+    c = k * math.sqrt(math.e)
+    lo, hi = oracle.lam(int(c), k, d, 0.0), oracle.lam(int(c) + 1, k, d, 0.0)
+    assert lo < 1 / math.sqrt(d) < hi
+    # entropy target: log c - lambda^2 d / 2 == log k  (the equation lambda solves)
+    for c_ in (1500, 4096, 32768):
+        lam = oracle.lam(c_, k, d, 0.0)
+        assert math.log(c_) - lam * lam * d / 2 == pytest.approx(math.log(k), rel=1e-13)
+    # floor
+    assert oracle.lam(1001, 1000, 64, floor=0.05) == 0.05
+
+
+# ------------------------------------------------- softmax rows / sums ----
+@pytest.mark.parametrize("mode", [SCALE_FIXED, SCALE_ADAPTIVE])
+def test_rows_sum_to_one_and_causal(mode):
+    b, hq, hk, n, d, r = 2, 4, 2, 96, 16, 20
+    Q, K = rnd(1, b, hq, n, d), rnd(2, b, hk, n, d)
+    cfg = Config(window=r, budget=24, recent=8, scale_mode=mode, fixed_scale=0.3,
+                 value_prior=False)
+    P = oracle.attention_rows(Q, K, cfg)
+    assert P.shape == (b, hq, r, n)
+    np.testing.assert_allclose(P.sum(-1), 1.0, atol=1e-12)
+    for ii in range(r):
+        i = n - r + ii
+        assert np.all(P[:, :, ii, i + 1:] == 0.0)
+        assert np.all(P[:, :, ii, :i + 1] > 0.0)
+
+
+def test_column_sums_total_rows():
+    b, hq, hk, n, d, r = 2, 6, 2, 80, 8, 17
+    Q, K, V = rnd(3, b, hq, n, d), rnd(4, b, hk, n, d), rnd(5, b, hk, n, d)
+    cfg = Config(window=r, budget=20, recent=4, value_prior=False)
+    S = oracle.prefill_scores(Q, K, V, cfg)
+    np.testing.assert_allclose(S.sum(-1), (hq // hk) * r, rtol=1e-12)
+    # scores equal the column sums of the written-out rows, summed per KV group
+    P = oracle.attention_rows(Q, K, cfg)
+    np.testing.assert_allclose(S, P.sum(2).reshape(b, hk, hq // hk, n).sum(2), rtol=1e-12)
+
+
+@pytest.mark.parametrize("r", [1, 5, 33, 64])
+def test_closed_form_at_scale_zero(r):
+    """scale 0 => a_ij = 1/(i+1) => S_j = G (H_n - H_max(j, n-r))."""
+    b, hq, hk, n, d = 1, 4, 2, 64, 8
+    Q, K, V = rnd(6, b, hq, n, d), rnd(7, b, hk, n, d), rnd(8, b, hk, n, d)
+    cfg = Config(window=r, budget=16, recent=4, scale_mode=SCALE_FIXED, fixed_scale=0.0,
+                 value_prior=False)
+    S = oracle.prefill_scores(Q, K, V, cfg)
+    H = harmonic(n)
+    j = np.arange(n)
+    want = (hq // hk) * (H[n] - H[np.maximum(j, n - r)])
+    np.testing.assert_allclose(S[0, 0], want, rtol=1e-13)
+    np.testing.assert_allclose(S[0, 1], want, rtol=1e-13)
+    if r == n:
+        # the paper's bias identity, exact here: S_{j+1} - S_j = -a_jj = -1/(j+1)
+        np.testing.assert_allclose(np.diff(S[0, 0]), -(hq // hk) / (j[:-1] + 1.0), rtol=1e-10)
+
+
+def _library_scores(Q, K, scales_by_row, rows):
+    """Independent route: masked logits -> scipy softmax -> column sum."""
+    b, hq, n, d = Q.shape
+    hk = K.shape[1]
+    G = hq // hk
+    out = np.zeros((b, hk, n))
+    for bi in range(b):
+        for h in range(hq):
+            W = Q[bi, h] @ K[bi, h // G].T                 # [n, n] raw dots
+            for i in rows:
+                x = scales_by_row[i] * W[i, :i + 1]
+                out[bi, h // G, :i + 1] += sp_softmax(x)
+    return out
+
+
+def test_reduces_to_accumulated_attention_score():
+    """window = n, scale 1/sqrt(d), no value prior: the plain accumulated score."""
+    b, hq, hk, n, d = 2, 4, 2, 70, 16
+    Q, K, V = rnd(9, b, hq, n, d), rnd(10, b, hk, n, d), rnd(11, b, hk, n, d)
+    cfg = Config(window=n, budget=16, recent=4, scale_mode=SCALE_FIXED,
+                 fixed_scale=1 / math.sqrt(d), value_prior=False)
+    S = oracle.prefill_scores(Q, K, V, cfg)
+    want = _library_scores(Q, K, {i: 1 / math.sqrt(d) for i in range(n)}, range(n))
+    np.testing.assert_allclose(S, want, rtol=1e-11)
+    # and via a dense masked softmax, a third route
+    for bi in range(b):
+        for h in range(hk):
+            acc = np.zeros(n)
+            for g in range(hq // hk):
+                W = (Q[bi, h * (hq // hk) + g] @ K[bi, h].T) / math.sqrt(d)
+                W = np.where(np.tril(np.ones((n, n), bool)), W, -np.inf)
+                acc += sp_softmax(W, axis=1).sum(0)
+            np.testing.assert_allclose(S[bi, h], acc, rtol=1e-11)
+
+
+def test_adaptive_windowed_matches_library_route():
+    b, hq, hk, n, d, r, B = 1, 4, 1, 300, 32, 24, 40
+    Q, K, V = rnd(12, b, hq, n, d), rnd(13, b, hk, n, d), rnd(14, b, hk, n, d)
+    cfg = Config(window=r, budget=B, recent=8, value_prior=False, lambda_floor=0.0)
+    S = oracle.prefill_scores(Q, K, V, cfg)
+    sc = {i: math.sqrt(2 * max(math.log((i + 1) / B), 0.0) / d) for i in range(n)}
+    want = _library_scores(Q, K, sc, range(n - r, n))
+    np.testing.assert_allclose(S, want, rtol=1e-11)
+
+
+def test_transposed_or_swapped_operands_would_fail():
+    """Q and K are not interchangeable: scoring with them swapped differs."""
+    b, h, n, d = 1, 1, 40, 8
+    Q, K, V = rnd(15, b, h, n, d), rnd(16, b, h, n, d), rnd(17, b, h, n, d)
+    cfg = Config(window=8, budget=10, recent=2, value_prior=False)
+    a = oracle.prefill_scores(Q, K, V, cfg)
+    bb = oracle.prefill_scores(K, Q, V, cfg)
+    assert np.abs(a - bb).max() > 1e-3
+
+
+# ---------------------------------------------- statistical (soft) pins ----
+def test_entropy_targets_on_gaussian_inputs():
+    """E[H] ~ log c - 1/2 under 1/sqrt(d) and ~ log k under the adaptive scale
+    (iid N(0,1) Q, K; loose band, the derivation swaps E log for log E)."""
+    b, h, n, d, r, k = 1, 24, 4096, 64, 8, 512
+    Q, K = rnd(18, b, h, n, d), rnd(19, b, h, n, d)
+
+    def mean_entropy(cfg):
+        P = oracle.attention_rows(Q, K, cfg)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            H = -(np.where(P > 0, P * np.log(P), 0.0)).sum(-1)
+        return H.mean()
+
+    std = mean_entropy(Config(window=r, budget=k, recent=4, scale_mode=SCALE_FIXED,
+                              fixed_scale=1 / math.sqrt(d)))
+    ada = mean_entropy(Config(window=r, budget=k, recent=4, lambda_floor=0.0))
+    assert abs(std - (math.log(n) - 0.5)) < 0.2
+    assert abs(ada - math.log(k)) < 0.25
+    assert ada < std  # the gain sharpens the rows
+
+
+def test_accumulated_score_bias_in_expectation():
+    """iid Gaussian, full accumulation: E[S_j] = H_n - H_j (each row's entries
+    are exchangeable), so the score decays with position."""
+    b, h, n, d = 1, 64, 128, 16
+    Q, K, V = rnd(20, b, h, n, d), rnd(21, b, h, n, d), rnd(22, b, h, n, d)
+    cfg = Config(window=n, budget=16, recent=4, scale_mode=SCALE_FIXED,
+                 fixed_scale=1 / math.sqrt(d), value_prior=False)
+    S = oracle.prefill_scores(Q, K, V, cfg)[0].mean(0)
+    Hn = harmonic(n)
+    want = Hn[n] - Hn[np.arange(n)]
+    # sampling error of a mean over 64 heads; compare coarse bins
+    for lo in range(0, n, 32):
+        assert S[lo:lo + 32].mean() == pytest.approx(want[lo:lo + 32].mean(), rel=0.08)
+    assert S[:32].mean() > S[32:64].mean() > S[64:96].mean() > S[96:].mean()
+
+
+# ------------------------------------------------------- value prior ----
+def test_value_prior_properties():
+    b, hk, n, d = 2, 3, 50, 8
+    V = rnd(23, b, hk, n, d)
+    for pool in (1, 3, 7):
+        g = oracle.value_prior(V, pool)
+        assert g.shape == (b, hk, n)
+        np.testing.assert_allclose(g.max(-1), 1.0, rtol=1e-15)
+        assert np.all(g > 0) and np.all(g <= 1)
+        np.testing.assert_allclose(oracle.value_prior(3.7 * V, pool), g, rtol=1e-12)
+    nu = (V ** 2).sum(-1)
+    np.testing.assert_allclose(oracle.value_prior(V, 1), nu / nu.max(-1, keepdims=True),
+                               rtol=1e-13)
+    # interior of the pool against numpy's convolution; edges against the
+    # truncated mean
+    pool, half = 7, 3
+    g = oracle.value_prior(V, pool)
+    for bi in range(b):
+        for h in range(hk):
+            gam = np.empty(n)
+            gam[half:n - half] = np.convolve(nu[bi, h], np.ones(pool) / pool, mode="valid")
+            for j in list(range(half)) + list(range(n - half, n)):
+                gam[j] = nu[bi, h, max(0, j - half):min(n, j + half + 1)].mean()
+            np.testing.assert_allclose(g[bi, h], gam / gam.max(), rtol=1e-12)
+
+
+def test_value_prior_equal_norm_rows_is_identity():
+    b, hq, hk, n, d = 1, 2, 2, 40, 8
+    Q, K, V = rnd(24, b, hq, n, d), rnd(25, b, hk, n, d), rnd(26, b, hk, n, d)
+    V /= np.linalg.norm(V, axis=-1, keepdims=True)
+    on = oracle.prefill_scores(Q, K, V, Config(8, 10, 2, value_prior=True, pool=5))
+    off = oracle.prefill_scores(Q, K, V, Config(8, 10, 2, value_prior=False))
+    np.testing.assert_allclose(on, off, rtol=1e-12)
+
+
+def test_value_prior_multiplies_scores():
+    b, hq, hk, n, d = 1, 2, 1, 40, 8
+    Q, K, V = rnd(27, b, hq, n, d), rnd(28, b, hk, n, d), rnd(29, b, hk, n, d)
+    on = oracle.prefill_scores(Q, K, V, Config(8, 10, 2, value_prior=True, pool=3))
+    off = oracle.prefill_scores(Q, K, V, Config(8, 10, 2, value_prior=False))
+    nu = (V ** 2).sum(-1)[0, 0]
+    gam = np.array([nu[max(0, j - 1):j + 2].mean() for j in range(n)])
+    np.testing.assert_allclose(on[0, 0], off[0, 0] * gam / gam.max(), rtol=1e-12)
+
+
+# -------------------------------------------------------------- GQA ----
+def test_gqa_equals_replicated_mha_summed_per_group():
+    b, hq, hk, n, d = 1, 8, 2, 60, 8
+    G = hq // hk
+    Q, K, V = rnd(30, b, hq, n, d), rnd(31, b, hk, n, d), rnd(32, b, hk, n, d)
+    cfg = Config(window=12, budget=20, recent=4, value_prior=False)
+    gqa = oracle.prefill_scores(Q, K, V, cfg)
+    mha = oracle.prefill_scores(Q, np.repeat(K, G, axis=1), np.repeat(V, G, axis=1), cfg)
+    np.testing.assert_allclose(gqa, mha.reshape(b, hk, G, n).sum(2), rtol=1e-12)
+
+
+# ------------------------------------------------------------ top-k ----
+def test_topk_brute_force_and_properties():
+    rng = np.random.default_rng(33)
+    for n, B, Br in [(50, 20, 6), (37, 37, 5), (64, 10, 10), (33, 9, 0), (16, 1, 0)]:
+        s = rng.random((3, 2, n))
+        idx = oracle.select_topk(s, B, Br)
+        assert idx.shape == (3, 2, B) and idx.dtype == np.int32
+        for p in np.ndindex(3, 2):
+            got = idx[p]
+            assert np.all(np.diff(got) > 0)                       # ascending, distinct
+            assert set(range(n - Br, n)) <= set(got.tolist())     # recents kept
+            cand = np.arange(n - Br)
+            order = sorted(cand, key=lambda j: (-s[p][j], j))     # full sort
+            want = sorted(order[:B - Br]) + list(range(n - Br, n))
+            assert got.tolist() == want
+            kept = [j for j in got if j < n - Br]
+            drop = [j for j in cand if j not in set(kept)]
+            if kept and drop:
+                assert s[p][kept].min() >= s[p][drop].max()
+
+
+def test_topk_exhaustive_subsets_maximise_kept_mass():
+    rng = np.random.default_rng(34)
+    m, Bs, Br = 11, 4, 2
+    s = rng.random(m + Br)
+    idx = oracle.select_topk(s, Bs + Br, Br)
+    chosen = tuple(j for j in idx if j < m)
+    best = max(itertools.combinations(range(m), Bs), key=lambda c: s[list(c)].sum())
+    assert chosen == best
+
+
+def test_topk_ties_keep_lower_index():
+    s = np.array([0.5, 0.9, 0.5, 0.5, 0.1, 0.5, 0.0, 0.0])
+    assert oracle.select_topk(s, 5, 2).tolist() == [0, 1, 2, 6, 7]
+    assert oracle.select_topk(np.zeros(9), 4, 1).tolist() == [0, 1, 2, 8]
+
+
+# -------------------------------------------------------- compaction ----
+def test_compaction_is_a_gather():
+    b, hk, n, d, B = 2, 3, 30, 4, 7
+    K, V = rnd(35, b, hk, n, d), rnd(36, b, hk, n, d)
+    S = np.random.default_rng(37).random((b, hk, n))
+    idx = oracle.select_topk(S, B, 2)
+    c = oracle.compact_kv(K, V, S, idx, slots=B + 3)
+    for p in np.ndindex(b, hk):
+        assert np.array_equal(c.K[p][:B], K[p][idx[p]])
+        assert np.array_equal(c.V[p][:B], V[p][idx[p]])
+        assert np.array_equal(c.F[p][:B], S[p][idx[p]])
+        assert np.array_equal(c.pos[p][:B], idx[p])
+        assert np.all(c.pos[p][B:] == -1) and np.all(c.F[p][B:] == 0)
+        assert c.free_slot[p] == B
+    # idempotent on the identity index list
+    ident = np.broadcast_to(np.arange(B, dtype=np.int32), (b, hk, B))
+    c2 = oracle.compact_kv(c.K[:, :, :B], c.V[:, :, :B], c.F[:, :, :B], ident, slots=B + 1)
+    assert np.array_equal(c2.K[:, :, :B], c.K[:, :, :B])
+
+
+# ------------------------------------------------------------ decode ----
+def _python_decode_sim(entries, q, k, v, c_t, B, Br, d, scale):
+    """Independent re-simulation on a dict keyed by token position."""
+    entries = dict(entries)
+    entries[c_t - 1] = [k.copy(), v.copy(), 0.0]
+    keys = sorted(entries)
+    outs = []
+    for g in range(q.shape[0]):
+        w = np.array([float(q[g] @ entries[p][0]) for p in keys])
+        po = sp_softmax(w / math.sqrt(d))
+        outs.append(sum(po[t] * entries[p][1] for t, p in enumerate(keys)))
+        ps = sp_softmax(scale * w)
+        for t, p in enumerate(keys):
+            entries[p][2] += ps[t]
+    protected = set(keys[len(keys) - Br:]) if Br else set()
+    cands = [p for p in keys if p not in protected]
+    victim = min(cands, key=lambda p: (entries[p][2], -p))
+    del entries[victim]
+    return entries, np.array(outs), victim
+
+
+@pytest.mark.parametrize("mode", [SCALE_FIXED, SCALE_ADAPTIVE])
+def test_decode_against_python_resimulation(mode):
+    b, hq, hk, d, n, B, Br = 2, 4, 2, 8, 40, 11, 3
+    G = hq // hk
+    Q, K, V = rnd(38, b, hq, n, d), rnd(39, b, hk, n, d), rnd(40, b, hk, n, d)
+    cfg = Config(window=6, budget=B, recent=Br, scale_mode=mode, fixed_scale=0.4,
+                 value_prior=True, pool=3)
+    S = oracle.prefill_scores(Q, K, V, cfg)
+    idx = oracle.select_topk(S, B, Br)
+    cache = oracle.compact_kv(K, V, S, idx, slots=B + 1)
+    sims = {p: {int(j): [K[p][j].copy(), V[p][j].copy(), float(S[p][j])] for j in idx[p]}
+            for p in np.ndindex(b, hk)}
+    rng = np.random.default_rng(41)
+    for step in range(8):
+        c_t = n + step + 1
+        q, k, v = rng.standard_normal((b, hq, d)), rng.standard_normal((b, hk, d)), \
+            rng.standard_normal((b, hk, d))
+        F_before = cache.F.copy()
+        pos_before = cache.pos.copy()
+        out = oracle.decode_step(cache, q, k, v, c_t, cfg)
+        scale = 0.4 if mode == SCALE_FIXED else oracle.lam(c_t, B, d, cfg.lambda_floor)
+        for p in np.ndindex(b, hk):
+            sims[p], o, victim = _python_decode_sim(
+                sims[p], q[p[0], p[1] * G:(p[1] + 1) * G], k[p], v[p], c_t, B, Br, d, scale)
+            np.testing.assert_allclose(out[p[0], p[1] * G:(p[1] + 1) * G], o, rtol=1e-11)
+            live = cache.pos[p] >= 0
+            assert live.sum() == B                              # constant cache size
+            got = {int(pp): float(f) for pp, f in zip(cache.pos[p][live], cache.F[p][live])}
+            want = {pp: e[2] for pp, e in sims[p].items()}
+            assert got.keys() == want.keys()
+            for pp in got:
+                assert got[pp] == pytest.approx(want[pp], rel=1e-11)
+            assert cache.pos[p][cache.free_slot[p]] == -1       # one eviction
+            assert victim not in got
+            # recents survive
+            assert set(range(c_t - Br, c_t)) <= set(got)
+            # the step distributes exactly G units of probability
+            Fb = F_before[p].copy()
+            Fb[pos_before[p] < 0] = 0.0                         # slot reused by the new token
+            total = (cache.F[p] - Fb).sum()
+            assert total == pytest.approx(G, rel=1e-11)
+
+
+def test_decode_output_is_textbook_attention():
+    b, hq, hk, d, B = 1, 2, 1, 16, 9
+    rng = np.random.default_rng(42)
+    Kc, Vc = rng.standard_normal((b, hk, B + 1, d)), rng.standard_normal((b, hk, B + 1, d))
+    cache = oracle.Cache(Kc.copy(), Vc.copy(), np.zeros((b, hk, B + 1)),
+                         np.concatenate([np.arange(B), [-1]]).astype(np.int32)[None, None].copy(),
+                         np.full((b, hk), B, np.int32))
+    q, k, v = rng.standard_normal((b, hq, d)), rng.standard_normal((b, hk, d)), \
+        rng.standard_normal((b, hk, d))
+    out = oracle.decode_step(cache, q, k, v, B + 1, Config(4, B, 2))
+    Kf, Vf = Kc[0, 0].copy(), Vc[0, 0].copy()
+    Kf[B], Vf[B] = k[0, 0], v[0, 0]
+    want = sp_softmax((q[0] @ Kf.T) / math.sqrt(d), axis=-1) @ Vf
+    np.testing.assert_allclose(out[0], want, rtol=1e-12)
