@@ -1,0 +1,188 @@
+/*
+ * aha.h -- C ABI of the AhaKV eviction hot path for AMD MI355X (gfx950).
+ *
+ * The four operations follow the paper's problem statement (Alg. 1): per
+ * layer, per head, Q, K, V in R^{n x d}; a total cache budget B made of a
+ * recent budget B_r and a selected budget B_s = B - B_r; an observation
+ * window of the r most recent query rows.
+ *
+ * General rules for every entry point
+ *   - All tensor arguments are DEVICE pointers owned by the caller.  The
+ *     library never allocates or frees device memory, never synchronises and
+ *     keeps no pointer after the call returns.  Scratch memory is the
+ *     caller's `workspace` (device memory, 256-byte aligned, at least
+ *     aha_workspace_bytes() bytes, contents arbitrary on entry and exit).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls only enqueue work on it.  Two calls that share a workspace or a
+ *     cache must be ordered by the caller (same stream, or events).
+ *   - Token positions are 0-indexed; query row i attends keys 0..i.
+ *   - Element strides (batch, head, token) are given in ELEMENTS; the
+ *     head_dim axis is contiguous.  Rows must be 16-byte aligned (base
+ *     pointers 16-byte aligned, strides multiples of 8 elements for bf16 and
+ *     4 for fp32).
+ *   - Return value: AHA_OK or a negative status.  All argument checks happen
+ *     on the host before anything is launched; on error nothing is enqueued.
+ *     aha_last_error() returns a thread-local, human readable reason.
+ *   - No C++ exception crosses this boundary.
+ */
+#ifndef AHA_H_
+#define AHA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    AHA_OK = 0,
+    AHA_ERR_INVALID_ARG = -1, /* a null pointer, an impossible size or stride */
+    AHA_ERR_UNSUPPORTED = -2, /* legal but not built: head_dim, dtype, sizes */
+    AHA_ERR_WORKSPACE = -3,   /* workspace null, misaligned or too small */
+    AHA_ERR_HIP = -4          /* the HIP runtime refused a launch */
+};
+
+enum { AHA_F32 = 0, AHA_BF16 = 1 };
+enum { AHA_SCALE_FIXED = 0, AHA_SCALE_ADAPTIVE = 1 };
+
+/*
+ * Problem description shared by the four operations.
+ *
+ *  window       r, the number of most recent query rows whose attention
+ *               rows are accumulated (Sec. 4.1, Recent Accumulation).
+ *               window == seq_len gives the plain accumulated attention
+ *               score (the H2O score of Sec. 4.1).
+ *  budget       B, total retained tokens per (batch, KV head); it is also k
+ *               in the adaptive scale.  1 <= budget <= seq_len.
+ *  recent       B_r, most recent tokens that are always retained;
+ *               0 <= recent <= budget.
+ *  scale_mode   AHA_SCALE_FIXED: softmax(fixed_scale * q.k).  1/sqrt(d)
+ *               gives the standard attention row.
+ *               AHA_SCALE_ADAPTIVE: step-gain softmax of Sec. 4.2 with
+ *               lambda_i = sqrt(2 ln(c_i / budget) / d), c_i = number of keys
+ *               the row normalises over, the logarithm clamped at 0 and the
+ *               result floored at lambda_floor (lambda_floor < 0 means
+ *               1/sqrt(d)).  lambda replaces 1/sqrt(d); it multiplies the raw
+ *               dot product in fp32.
+ *  value_prior  non-zero: scores are multiplied by gamma_bar of Sec. 4.3,
+ *               gamma = average pool over tokens (odd width pool_kernel,
+ *               stride 1, edge-truncated mean) of ||V_j||^2, divided by its
+ *               maximum over the sequence of that (batch, KV head).
+ *  n_q_heads    must be a multiple of n_kv_heads; the score of a KV head is
+ *               the sum over the query heads that share it.
+ */
+typedef struct aha_params {
+    int32_t batch;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;     /* 64 or 128 */
+    int32_t seq_len;      /* n (prefill) ; ignored by aha_decode_step */
+    int32_t window;       /* r, 1..seq_len */
+    int32_t budget;       /* B */
+    int32_t recent;       /* B_r */
+    int32_t dtype;        /* AHA_F32 | AHA_BF16: element type of Q, K, V, caches, out */
+    int32_t scale_mode;   /* AHA_SCALE_FIXED | AHA_SCALE_ADAPTIVE */
+    float fixed_scale;    /* >= 0 */
+    float lambda_floor;   /* see above */
+    int32_t value_prior;  /* 0 | 1 */
+    int32_t pool_kernel;  /* odd, 1..255 */
+    int64_t q_stride[3];  /* elements: batch, head, token (prefill Q) */
+    int64_t k_stride[3];  /* elements: batch, head, token (prefill K) */
+    int64_t v_stride[3];  /* elements: batch, head, token (prefill V) */
+} aha_params;
+
+/*
+ * Bytes of workspace that any of the calls below needs for `p` (the maximum
+ * over the four operations, a multiple of 256).
+ */
+int32_t aha_workspace_bytes(const aha_params *p, size_t *out_bytes);
+
+/*
+ * Prefill eviction scores (Alg. 1 Prefill, score lines; Sec. 4.1 - 4.3).
+ *
+ *   scores[b, h, j] = gamma_bar[b, h, j] *
+ *        sum_{g in group(h)} sum_{i = n-r}^{n-1} softmax_{j' <= i}(s_i * Q_i . K_j')_j
+ *
+ *  q       [batch, n_q_heads, seq_len, head_dim] by q_stride; only the last
+ *          `window` rows of each head are read.
+ *  k, v    [batch, n_kv_heads, seq_len, head_dim] by k_stride / v_stride.
+ *  scores  out, fp32, dense [batch, n_kv_heads, seq_len].
+ * The probability matrix is never written to memory: one pass over the keys
+ * finds each row's maximum and log-sum-exp, a second pass recomputes the
+ * logits and accumulates the column sums.
+ */
+int32_t aha_prefill_scores(const aha_params *p, const void *q, const void *k,
+                           const void *v, float *scores, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/*
+ * Selection (Alg. 1: recent set, TopK, union).
+ *
+ *  scores  fp32 [batch, n_kv_heads, seq_len], non-negative and finite.
+ *  idx     out, int32 dense [batch, n_kv_heads, budget], ascending token
+ *          positions: the budget - recent highest-scoring tokens among
+ *          positions < seq_len - recent (ties: lower position wins) followed
+ *          by the `recent` last positions.
+ */
+int32_t aha_select_topk(const aha_params *p, const float *scores, int32_t *idx,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Compaction (Alg. 1 Generation: K_S, V_S, F_0 = refined prefill score).
+ *
+ *  k, v         as in aha_prefill_scores.
+ *  scores, idx  as produced by the two calls above.
+ *  k_cache, v_cache  out, element type p->dtype, dense
+ *               [batch, n_kv_heads, cache_slots, head_dim]; cache_slots >=
+ *               budget + 1.  Slot s < budget receives row idx[s]; the other
+ *               slots are zero-filled.
+ *  scores_c     out, fp32 dense [batch, n_kv_heads, cache_slots]: running
+ *               score F of each slot (0 for empty slots).
+ *  pos_c        out, int32 dense [batch, n_kv_heads, cache_slots]: token
+ *               position of each slot, -1 for an empty slot.
+ *  free_slot    out, int32 [batch, n_kv_heads]: the slot the next generated
+ *               token will occupy (= budget).
+ */
+int32_t aha_compact_kv(const aha_params *p, const void *k, const void *v,
+                       const float *scores, const int32_t *idx, void *k_cache,
+                       void *v_cache, float *scores_c, int32_t *pos_c,
+                       int32_t *free_slot, int32_t cache_slots, void *stream);
+
+/*
+ * One generation step with running eviction (Alg. 1 Generation, loop body),
+ * for every (batch, KV head), in place on the compact cache:
+ *   1. k_new / v_new are written to slot free_slot, score 0, position
+ *      logical_pos - 1;
+ *   2. w_s = q . k_cache[s] over the budget + 1 live slots (slots 0..budget);
+ *   3. out = sum_s softmax_s(w_s / sqrt(d)) v_cache[s]   (the attention output);
+ *   4. scores_c[s] += sum_{g in group} softmax_s(scale * w_s), with the scale
+ *      of p->scale_mode evaluated at c = logical_pos;
+ *   5. slots whose position >= logical_pos - recent are protected; of the
+ *      others the one with the smallest score is evicted (ties: the highest
+ *      position): pos_c = -1 there and free_slot points to it.
+ *
+ *  q_new        [batch, n_q_heads, head_dim] dense, p->dtype.
+ *  k_new, v_new [batch, n_kv_heads, head_dim] dense, p->dtype.
+ *  logical_pos  number of tokens seen so far including the new one.
+ *  out          [batch, n_q_heads, head_dim] dense, p->dtype.
+ * p->seq_len, window, value_prior, pool_kernel and the strides are ignored.
+ * Exactly budget + 1 slots must be live on entry (budget occupied + the free
+ * one), which aha_compact_kv and every previous step guarantee.
+ */
+int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_new,
+                        const void *v_new, void *k_cache, void *v_cache,
+                        float *scores_c, int32_t *pos_c, int32_t *free_slot,
+                        int32_t cache_slots, int32_t logical_pos, void *out,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* Thread-local description of the last error returned on this thread. */
+const char *aha_last_error(void);
+
+/* Library version string, e.g. "aha-gfx950 0.1". */
+const char *aha_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AHA_H_ */

@@ -1,0 +1,271 @@
+// C ABI of the AhaKV eviction path: argument checks, workspace layout and
+// kernel launches.  Every check runs on the host before anything is
+// enqueued, so the error paths need no GPU.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "aha_host.h"
+
+namespace aha {
+
+static thread_local char g_err[512] = "";
+
+static int32_t fail(int32_t code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int esize(int dtype) { return dtype == AHA_BF16 ? 2 : 4; }
+
+// Checks shared by all entry points.
+static int32_t check_common(const aha_params *p) {
+    if (!p) return fail(AHA_ERR_INVALID_ARG, "params is null");
+    if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1)
+        return fail(AHA_ERR_INVALID_ARG, "batch, n_q_heads and n_kv_heads must be >= 1");
+    if (p->n_q_heads % p->n_kv_heads != 0)
+        return fail(AHA_ERR_INVALID_ARG, "n_q_heads (%d) is not a multiple of n_kv_heads (%d)",
+                    p->n_q_heads, p->n_kv_heads);
+    if (p->dtype != AHA_F32 && p->dtype != AHA_BF16)
+        return fail(AHA_ERR_INVALID_ARG, "dtype %d is neither AHA_F32 nor AHA_BF16", p->dtype);
+    if (p->head_dim != 64 && p->head_dim != 128)
+        return fail(AHA_ERR_UNSUPPORTED, "head_dim %d: only 64 and 128 are built", p->head_dim);
+    if (p->budget < 1) return fail(AHA_ERR_INVALID_ARG, "budget must be >= 1");
+    if (p->recent < 0 || p->recent > p->budget)
+        return fail(AHA_ERR_INVALID_ARG, "recent (%d) must lie in [0, budget=%d]", p->recent,
+                    p->budget);
+    if (p->scale_mode != AHA_SCALE_FIXED && p->scale_mode != AHA_SCALE_ADAPTIVE)
+        return fail(AHA_ERR_INVALID_ARG, "scale_mode %d is unknown", p->scale_mode);
+    if (p->scale_mode == AHA_SCALE_FIXED && !(p->fixed_scale >= 0.f))
+        return fail(AHA_ERR_INVALID_ARG, "fixed_scale must be >= 0");
+    return AHA_OK;
+}
+
+static int32_t check_stride(const char *name, const int64_t s[3], int dtype, int d) {
+    const int a = 16 / esize(dtype);
+    for (int t = 0; t < 3; ++t)
+        if (s[t] < 0 || s[t] % a != 0)
+            return fail(AHA_ERR_INVALID_ARG, "%s_stride[%d]=%lld must be a non-negative multiple of %d elements",
+                        name, t, (long long)s[t], a);
+    if (s[2] < d)
+        return fail(AHA_ERR_INVALID_ARG, "%s_stride[2]=%lld is smaller than head_dim", name,
+                    (long long)s[2]);
+    return AHA_OK;
+}
+
+static int32_t check_prefill(const aha_params *p, bool need_strides) {
+    int32_t rc = check_common(p);
+    if (rc) return rc;
+    if (p->seq_len < 1) return fail(AHA_ERR_INVALID_ARG, "seq_len must be >= 1");
+    if (p->budget > p->seq_len)
+        return fail(AHA_ERR_INVALID_ARG, "budget (%d) exceeds seq_len (%d)", p->budget, p->seq_len);
+    if (p->window < 1 || p->window > p->seq_len)
+        return fail(AHA_ERR_INVALID_ARG, "window (%d) must lie in [1, seq_len=%d]", p->window,
+                    p->seq_len);
+    if (p->value_prior != 0 && p->value_prior != 1)
+        return fail(AHA_ERR_INVALID_ARG, "value_prior must be 0 or 1");
+    if (p->value_prior && (p->pool_kernel < 1 || p->pool_kernel > 255 || p->pool_kernel % 2 == 0))
+        return fail(AHA_ERR_INVALID_ARG, "pool_kernel (%d) must be odd and in [1, 255]",
+                    p->pool_kernel);
+    if ((int64_t)(p->n_q_heads / p->n_kv_heads) * p->window > (int64_t)1 << 30)
+        return fail(AHA_ERR_UNSUPPORTED, "group * window is too large");
+    if (need_strides) {
+        if ((rc = check_stride("q", p->q_stride, p->dtype, p->head_dim))) return rc;
+        if ((rc = check_stride("k", p->k_stride, p->dtype, p->head_dim))) return rc;
+        if ((rc = check_stride("v", p->v_stride, p->dtype, p->head_dim))) return rc;
+    }
+    return AHA_OK;
+}
+
+static int32_t check_ptr(const char *name, const void *ptr, size_t align) {
+    if (!ptr) return fail(AHA_ERR_INVALID_ARG, "%s is null", name);
+    if ((uintptr_t)ptr % align != 0)
+        return fail(AHA_ERR_INVALID_ARG, "%s is not %zu-byte aligned", name, align);
+    return AHA_OK;
+}
+
+static ScoreGeom make_geom(const aha_params *p, const void *q, const void *k, const void *v) {
+    ScoreGeom g{};
+    g.q = q; g.k = k; g.v = v;
+    for (int t = 0; t < 3; ++t) { g.qs[t] = p->q_stride[t]; g.ks[t] = p->k_stride[t]; g.vs[t] = p->v_stride[t]; }
+    g.batch = p->batch; g.Hq = p->n_q_heads; g.Hkv = p->n_kv_heads; g.G = g.Hq / g.Hkv;
+    g.d = p->head_dim; g.n = p->seq_len; g.r = p->window; g.R = g.G * g.r;
+    g.budget = p->budget; g.scale_mode = p->scale_mode; g.fixed_scale = p->fixed_scale;
+    g.lambda_floor = p->lambda_floor; g.value_prior = p->value_prior; g.pool = p->pool_kernel;
+    g.dtype = p->dtype;
+    return g;
+}
+
+// Workspace layout of aha_prefill_scores.
+static PrefillPlan plan_prefill(const aha_params *p) {
+    PrefillPlan pl{};
+    const int G = p->n_q_heads / p->n_kv_heads;
+    const int64_t R = (int64_t)G * p->window;
+    const int n = p->seq_len;
+    pl.Z = p->batch * p->n_kv_heads;
+    pl.n_vtiles = (n + kVTileRows - 1) / kVTileRows;
+    if (p->dtype == AHA_BF16) {
+        const int blocks = (int)((R + 31) / 32);
+        pl.NB = blocks >= 8 ? 8 : blocks > 2 ? 4 : blocks;  // 1, 2, 4, 8
+        if (blocks == 3) pl.NB = 4;
+        pl.qtile = pl.NB * 32;
+        pl.n_qtiles = (int)((R + pl.qtile - 1) / pl.qtile);
+        // pass-1 key chunks: enough workgroups to fill 256 CUs a few times over,
+        // chunks a multiple of the 256 keys a workgroup sweeps per step
+        const int64_t tiles = (int64_t)pl.Z * pl.n_qtiles;
+        int64_t want = (1024 + tiles - 1) / tiles;  // chunks per tile
+        if (want < 1) want = 1;
+        int64_t ck = ((n + want - 1) / want + kP2Keys - 1) / kP2Keys * kP2Keys;
+        if (ck < kP2Keys) ck = kP2Keys;
+        pl.chunk_keys = (int)ck;
+        pl.nchunks = (int)((n + ck - 1) / ck);
+    } else {
+        pl.NB = 0;
+        pl.qtile = 1;
+        pl.n_qtiles = 1;
+        pl.chunk_keys = n;
+        pl.nchunks = 1;
+    }
+    size_t off = 0;
+    pl.off_counters = off;
+    off = align_up(off + sizeof(int) * (size_t)pl.Z * pl.n_qtiles, 256);
+    pl.off_rowL = off;
+    const size_t rows = p->dtype == AHA_BF16 ? (size_t)pl.n_qtiles * pl.qtile : (size_t)R;
+    off = align_up(off + sizeof(float) * (size_t)pl.Z * rows, 256);
+    pl.off_partial = off;
+    if (p->dtype == AHA_BF16)
+        off = align_up(off + sizeof(float) * 2 * (size_t)pl.Z * rows * pl.nchunks, 256);
+    pl.off_gamma = off;
+    off = align_up(off + sizeof(float) * (size_t)pl.Z * n, 256);
+    pl.off_gblockmax = off;
+    off = align_up(off + sizeof(float) * (size_t)pl.Z * pl.n_vtiles, 256);
+    pl.bytes = off;
+    return pl;
+}
+
+static int32_t check_ws(const void *ws, size_t have, size_t need) {
+    if (need == 0) return AHA_OK;
+    if (!ws) return fail(AHA_ERR_WORKSPACE, "workspace is null (%zu bytes needed)", need);
+    if ((uintptr_t)ws % 256 != 0) return fail(AHA_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+    if (have < need)
+        return fail(AHA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", have, need);
+    return AHA_OK;
+}
+
+static int32_t hip_result(hipError_t e, const char *what) {
+    if (e == hipSuccess) return AHA_OK;
+    return fail(AHA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace aha
+
+using namespace aha;
+
+extern "C" {
+
+int32_t aha_workspace_bytes(const aha_params *p, size_t *out_bytes) {
+    if (!out_bytes) return fail(AHA_ERR_INVALID_ARG, "out_bytes is null");
+    int32_t rc = check_prefill(p, false);
+    if (rc) return rc;
+    *out_bytes = plan_prefill(p).bytes;
+    return AHA_OK;
+}
+
+int32_t aha_prefill_scores(const aha_params *p, const void *q, const void *k, const void *v,
+                           float *scores, void *workspace, size_t workspace_bytes, void *stream) {
+    int32_t rc = check_prefill(p, true);
+    if (rc) return rc;
+    if ((rc = check_ptr("q", q, 16)) || (rc = check_ptr("k", k, 16)) ||
+        (rc = check_ptr("scores", scores, 4)))
+        return rc;
+    if (p->value_prior && (rc = check_ptr("v", v, 16))) return rc;
+    const PrefillPlan pl = plan_prefill(p);
+    if ((rc = check_ws(workspace, workspace_bytes, pl.bytes))) return rc;
+    if (pl.nchunks > 65535 || pl.n_qtiles > 65535 || pl.Z > 65535)
+        return fail(AHA_ERR_UNSUPPORTED, "problem exceeds the launch grid limits");
+    const ScoreGeom g = make_geom(p, q, k, v);
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = hip_result(launch_value_prior(g, pl, workspace, st), "value-prior kernel"))) return rc;
+    if (p->dtype == AHA_BF16)
+        return hip_result(launch_score_bf16(g, pl, workspace, scores, st), "bf16 score kernels");
+    return hip_result(launch_score_f32(g, pl, workspace, scores, st), "fp32 score kernels");
+}
+
+int32_t aha_select_topk(const aha_params *p, const float *scores, int32_t *idx, void *workspace,
+                        size_t workspace_bytes, void *stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    int32_t rc = check_prefill(p, false);
+    if (rc) return rc;
+    if ((rc = check_ptr("scores", scores, 4)) || (rc = check_ptr("idx", idx, 4))) return rc;
+    return hip_result(launch_topk(scores, p->batch * p->n_kv_heads, p->seq_len, p->budget,
+                                  p->recent, idx, (hipStream_t)stream),
+                      "top-k kernel");
+}
+
+int32_t aha_compact_kv(const aha_params *p, const void *k, const void *v, const float *scores,
+                       const int32_t *idx, void *k_cache, void *v_cache, float *scores_c,
+                       int32_t *pos_c, int32_t *free_slot, int32_t cache_slots, void *stream) {
+    int32_t rc = check_prefill(p, true);
+    if (rc) return rc;
+    if ((rc = check_ptr("k", k, 16)) || (rc = check_ptr("v", v, 16)) ||
+        (rc = check_ptr("scores", scores, 4)) || (rc = check_ptr("idx", idx, 4)) ||
+        (rc = check_ptr("k_cache", k_cache, 16)) || (rc = check_ptr("v_cache", v_cache, 16)) ||
+        (rc = check_ptr("scores_c", scores_c, 4)) || (rc = check_ptr("pos_c", pos_c, 4)) ||
+        (rc = check_ptr("free_slot", free_slot, 4)))
+        return rc;
+    if (cache_slots < p->budget + 1)
+        return fail(AHA_ERR_INVALID_ARG, "cache_slots (%d) must be >= budget + 1 (%d)", cache_slots,
+                    p->budget + 1);
+    const ScoreGeom g = make_geom(p, nullptr, k, v);
+    return hip_result(launch_compact(g, scores, idx, p->budget, cache_slots, p->dtype, k_cache,
+                                     v_cache, scores_c, pos_c, free_slot, (hipStream_t)stream),
+                      "compaction kernel");
+}
+
+int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_new,
+                        const void *v_new, void *k_cache, void *v_cache, float *scores_c,
+                        int32_t *pos_c, int32_t *free_slot, int32_t cache_slots,
+                        int32_t logical_pos, void *out, void *workspace, size_t workspace_bytes,
+                        void *stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    int32_t rc = check_common(p);
+    if (rc) return rc;
+    if ((rc = check_ptr("q_new", q_new, 16)) || (rc = check_ptr("k_new", k_new, 16)) ||
+        (rc = check_ptr("v_new", v_new, 16)) || (rc = check_ptr("k_cache", k_cache, 16)) ||
+        (rc = check_ptr("v_cache", v_cache, 16)) || (rc = check_ptr("scores_c", scores_c, 4)) ||
+        (rc = check_ptr("pos_c", pos_c, 4)) || (rc = check_ptr("free_slot", free_slot, 4)) ||
+        (rc = check_ptr("out", out, 16)))
+        return rc;
+    if (cache_slots < p->budget + 1)
+        return fail(AHA_ERR_INVALID_ARG, "cache_slots (%d) must be >= budget + 1 (%d)", cache_slots,
+                    p->budget + 1);
+    if (logical_pos < p->budget + 1)
+        return fail(AHA_ERR_INVALID_ARG, "logical_pos (%d) must be >= budget + 1 (%d)", logical_pos,
+                    p->budget + 1);
+    const int G = p->n_q_heads / p->n_kv_heads;
+    if (G > 8)
+        return fail(AHA_ERR_UNSUPPORTED, "decode is built for query groups of up to 8 heads, not %d", G);
+    const int live = p->budget + 1;
+    const size_t w_floats = (size_t)(G * live > 16 * G * p->head_dim ? G * live : 16 * G * p->head_dim);
+    if ((w_floats + (size_t)G * live) * 4 > 150 * 1024)
+        return fail(AHA_ERR_UNSUPPORTED,
+                    "decode keeps group * (budget + 1) dots in LDS; %d * %d does not fit", G, live);
+    DecodeGeom g{};
+    g.q = q_new; g.k_new = k_new; g.v_new = v_new; g.kc = k_cache; g.vc = v_cache; g.out = out;
+    g.fc = scores_c; g.pos = pos_c; g.free_slot = free_slot;
+    g.batch = p->batch; g.Hq = p->n_q_heads; g.Hkv = p->n_kv_heads; g.G = G; g.d = p->head_dim;
+    g.budget = p->budget; g.recent = p->recent; g.slots = cache_slots; g.logical_pos = logical_pos;
+    g.scale_mode = p->scale_mode; g.fixed_scale = p->fixed_scale; g.lambda_floor = p->lambda_floor;
+    return hip_result(launch_decode(g, p->dtype, (hipStream_t)stream), "decode kernel");
+}
+
+const char *aha_last_error(void) { return g_err; }
+
+const char *aha_version(void) { return "aha-gfx950 0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,91 @@
+// Device-side helpers shared by the gfx950 kernels of the AhaKV eviction path.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/aha.h"
+
+namespace aha {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+
+// bf16 <-> fp32 on raw bits (bf16 is the upper half of an fp32).
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    return f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+}
+
+// Softmax scale of a row that normalises over c keys, already multiplied by
+// log2(e) so that exp2 can be used (Sec. 4.2: lambda = sqrt(2 ln(c/k)/d) with
+// k the total budget; the logarithm is clamped at 0 and the result floored).
+// Evaluated in double so that the fp32 value is correctly rounded.
+__device__ __forceinline__ float row_scale_log2(int scale_mode, float fixed_scale,
+                                                float lambda_floor, int c, int budget,
+                                                int head_dim) {
+    double s;
+    if (scale_mode == AHA_SCALE_FIXED) {
+        s = (double)fixed_scale;
+    } else {
+        double lg = log((double)c / (double)budget);
+        if (lg < 0.0) lg = 0.0;
+        s = sqrt(2.0 * lg / (double)head_dim);
+        double fl = lambda_floor < 0.f ? 1.0 / sqrt((double)head_dim) : (double)lambda_floor;
+        if (s < fl) s = fl;
+    }
+    return (float)(s * 1.4426950408889634074);
+}
+
+// 2^x on the transcendental unit (v_exp_f32): no denormal results, exp2(-inf) = 0.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Loads that bypass the per-CU cache (for data another workgroup of the same
+// launch has just written and fenced).
+__device__ __forceinline__ float load_agent(const float *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Softmax geometry of the flattened query rows of one KV head: row rho of the
+// group is query head g = rho / r, window row ii = rho % r, token position
+// i = n - r + ii.
+struct RowMap {
+    int n, r, R;  // sequence length, window, G * r
+    __device__ __forceinline__ int pos(int rho) const { return rho < R ? n - r + rho % r : -1; }
+    __device__ __forceinline__ int head(int rho) const { return rho / r; }
+    // largest / smallest position among rows [lo, hi) (hi > lo, clipped to R)
+    __device__ __forceinline__ int max_pos(int lo, int hi) const {
+        if (hi > R) hi = R;
+        if (lo >= hi) return -1;
+        return (lo / r != (hi - 1) / r) ? n - 1 : n - r + (hi - 1) % r;
+    }
+    __device__ __forceinline__ int min_pos(int lo, int hi) const {
+        if (hi > R) hi = R;
+        if (lo >= hi) return n;
+        return (lo / r != (hi - 1) / r) ? n - r : n - r + lo % r;
+    }
+};
+
+}  // namespace aha

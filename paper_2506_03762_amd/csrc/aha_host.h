@@ -1,0 +1,70 @@
+// Host-side declarations shared by the kernel translation units and the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/aha.h"
+
+namespace aha {
+
+// Geometry of one prefill call, passed by value to the kernels.
+struct ScoreGeom {
+    const void *q, *k, *v;
+    int64_t qs[3], ks[3], vs[3];  // element strides: batch, head, token
+    int batch, Hq, Hkv, G, d, n;
+    int r;       // window
+    int R;       // G * r flattened query rows per KV head
+    int budget;
+    int scale_mode;
+    float fixed_scale, lambda_floor;
+    int value_prior, pool;
+    int dtype;   // AHA_F32 | AHA_BF16
+};
+
+// Where things live in the caller's workspace during aha_prefill_scores.
+struct PrefillPlan {
+    int Z;           // batch * Hkv problems
+    int NB;          // 32-row blocks per query tile (bf16 path): 1, 2, 4 or 8
+    int qtile;       // NB * 32 rows
+    int n_qtiles;    // query tiles per problem
+    int chunk_keys;  // keys per pass-1 workgroup
+    int nchunks;     // pass-1 key chunks per (problem, query tile)
+    int n_vtiles;    // value-prior tiles per problem
+    size_t off_counters, off_rowL, off_partial, off_gamma, off_gblockmax;
+    size_t bytes;
+};
+
+constexpr int kVTileRows = 256;   // rows per value-prior workgroup
+constexpr int kP2Keys = 256;      // keys per pass-2 workgroup (4 waves x 64)
+
+// value_prior.hip
+hipError_t launch_value_prior(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
+                              hipStream_t st);
+// score_f32.hip
+hipError_t launch_score_f32(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
+                            float *scores, hipStream_t st);
+// score_bf16.hip
+hipError_t launch_score_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
+                             float *scores, hipStream_t st);
+// topk.hip
+hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent,
+                       int32_t *idx, hipStream_t st);
+// compact.hip
+hipError_t launch_compact(const ScoreGeom &g, const float *scores, const int32_t *idx,
+                          int budget, int slots, int dtype, void *kc, void *vc, float *fc,
+                          int32_t *pos, int32_t *free_slot, hipStream_t st);
+// decode.hip
+struct DecodeGeom {
+    const void *q, *k_new, *v_new;
+    void *kc, *vc, *out;
+    float *fc;
+    int32_t *pos, *free_slot;
+    int batch, Hq, Hkv, G, d, budget, recent, slots, logical_pos;
+    int scale_mode;
+    float fixed_scale, lambda_floor;
+};
+hipError_t launch_decode(const DecodeGeom &g, int dtype, hipStream_t st);
+
+}  // namespace aha

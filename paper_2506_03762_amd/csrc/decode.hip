@@ -1,0 +1,254 @@
+// One generation step with running eviction (Alg. 1 Generation, loop body).
+//
+// One workgroup of 1024 threads per (batch, KV head) streams that head's
+// compact K cache once and its V cache once with 16-byte loads (the lanes of
+// a row adjacent, 64 rows per sweep), so the step is bound by HBM bandwidth;
+// the raw dots of all live slots stay in LDS, from which both the attention
+// output (scale 1/sqrt(d)) and the score update (adaptive scale) are formed.
+// No cross-workgroup exchange is needed: the whole head lives in one CU.
+#include "aha_dev.h"
+#include "aha_host.h"
+
+namespace aha {
+
+constexpr int kDecThreads = 1024;
+constexpr int kDecWaves = kDecThreads / 64;
+
+template <int ESIZE>
+__device__ __forceinline__ void unpack(const u32x4 &w, float (&f)[16 / ESIZE]) {
+    if constexpr (ESIZE == 2) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            f[2 * t] = bf16_lo(w[t]);
+            f[2 * t + 1] = bf16_hi(w[t]);
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) f[t] = __uint_as_float(w[t]);
+    }
+}
+
+template <int ESIZE, int D, int G>
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w_floats) {
+    constexpr int CH = 16 / ESIZE;       // channels per 16-byte chunk
+    constexpr int LPR = D / CH;          // lanes per row
+    constexpr int RP = kDecThreads / LPR;  // rows per sweep
+    constexpr int ROWB = D * ESIZE;
+
+    extern __shared__ __attribute__((aligned(16))) float dsm[];
+    float *s_w = dsm;              // [G][live] raw dots; later [waves][G][D] partial outputs
+    float *s_p = dsm + w_floats;   // [G][live] output probabilities
+    __shared__ float s_red[kDecWaves][2 * G];
+    __shared__ unsigned long long s_key[kDecWaves];
+    __shared__ int s_victim;
+
+    const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = z / g.Hkv, h = z % g.Hkv;
+    const int live = g.budget + 1;
+    const int fs = g.free_slot[z];
+    const int rg = tid / LPR, sub = tid % LPR;
+    char *kcz = (char *)g.kc + (int64_t)z * g.slots * ROWB;
+    char *vcz = (char *)g.vc + (int64_t)z * g.slots * ROWB;
+    const char *knew = (const char *)g.k_new + (int64_t)z * ROWB;
+    const char *vnew = (const char *)g.v_new + (int64_t)z * ROWB;
+    float *fcz = g.fc + (int64_t)z * g.slots;
+    int32_t *posz = g.pos + (int64_t)z * g.slots;
+
+    float qr[G][CH];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+        const char *qp = (const char *)g.q + ((int64_t)(b * g.Hq + h * G + gi)) * ROWB + sub * 16;
+        unpack<ESIZE>(*(const u32x4 *)qp, qr[gi]);
+    }
+
+    // ---- raw dots over the live slots (the new key stands in for slot fs) ----
+    float mloc[G];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) mloc[gi] = -INFINITY;
+#pragma unroll 4
+    for (int s = rg; s < live; s += RP) {
+        const char *src = (s == fs) ? knew : kcz + (int64_t)s * ROWB;
+        const u32x4 kw = *(const u32x4 *)(src + sub * 16);
+        if (s == fs) *(u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16) = kw;
+        float kf[CH];
+        unpack<ESIZE>(kw, kf);
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            float w = 0.f;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) w = fmaf(qr[gi][c], kf[c], w);
+#pragma unroll
+            for (int o = LPR / 2; o > 0; o >>= 1) w += __shfl_xor(w, o);
+            if (sub == 0) s_w[gi * live + s] = w;
+            mloc[gi] = fmaxf(mloc[gi], w);
+        }
+    }
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+        const float m = wave_max(mloc[gi]);
+        if (lane == 0) s_red[wave][gi] = m;
+    }
+    __syncthreads();
+    float mx[G];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+        float m = s_red[0][gi];
+#pragma unroll
+        for (int w = 1; w < kDecWaves; ++w) m = fmaxf(m, s_red[w][gi]);
+        mx[gi] = m;
+    }
+    __syncthreads();
+
+    // ---- the two softmax denominators ----
+    const float c_out = kLog2e * rsqrtf((float)D);
+    const float c_sc = row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor, g.logical_pos,
+                                      g.budget, D);
+    float zo[G], zs[G];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) zo[gi] = zs[gi] = 0.f;
+    for (int s = tid; s < live; s += kDecThreads) {
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            const float d = s_w[gi * live + s] - mx[gi];
+            zo[gi] += exp2f(d * c_out);
+            zs[gi] += exp2f(d * c_sc);
+        }
+    }
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+        const float a = wave_sum(zo[gi]), c = wave_sum(zs[gi]);
+        if (lane == 0) { s_red[wave][2 * gi] = a; s_red[wave][2 * gi + 1] = c; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+        float a = 0.f, c = 0.f;
+#pragma unroll
+        for (int w = 0; w < kDecWaves; ++w) { a += s_red[w][2 * gi]; c += s_red[w][2 * gi + 1]; }
+        zo[gi] = a;
+        zs[gi] = c;
+    }
+
+    // ---- probabilities, running score, eviction candidate ----
+    unsigned long long best = ~0ull;
+    int best_slot = -1;
+    for (int s = tid; s < live; s += kDecThreads) {
+        float add = 0.f;
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            const float d = s_w[gi * live + s] - mx[gi];
+            s_p[gi * live + s] = exp2f(d * c_out) / zo[gi];
+            add += exp2f(d * c_sc) / zs[gi];
+        }
+        const float f = (s == fs ? 0.f : fcz[s]) + add;
+        fcz[s] = f;
+        int ps;
+        if (s == fs) { ps = g.logical_pos - 1; posz[s] = ps; } else { ps = posz[s]; }
+        if (ps < g.logical_pos - g.recent) {
+            const unsigned long long key =
+                ((unsigned long long)__float_as_uint(f) << 32) | (uint32_t)(~ps);
+            if (key < best) { best = key; best_slot = s; }
+        }
+    }
+    unsigned long long wbest = best;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned long long t = __shfl_xor(wbest, o);
+        wbest = t < wbest ? t : wbest;
+    }
+    if (lane == 0) s_key[wave] = wbest;
+    __syncthreads();  // also: s_w is free from here on
+    unsigned long long gbest = s_key[0];
+#pragma unroll
+    for (int w = 1; w < kDecWaves; ++w) gbest = s_key[w] < gbest ? s_key[w] : gbest;
+    if (best_slot >= 0 && best == gbest) s_victim = best_slot;
+
+    // ---- attention output: sum_s p_s V_s ----
+    float o[G][CH];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) o[gi][c] = 0.f;
+#pragma unroll 4
+    for (int s = rg; s < live; s += RP) {
+        const char *src = (s == fs) ? vnew : vcz + (int64_t)s * ROWB;
+        const u32x4 vw = *(const u32x4 *)(src + sub * 16);
+        if (s == fs) *(u32x4 *)(vcz + (int64_t)s * ROWB + sub * 16) = vw;
+        float vf[CH];
+        unpack<ESIZE>(vw, vf);
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            const float p = s_p[gi * live + s];
+#pragma unroll
+            for (int c = 0; c < CH; ++c) o[gi][c] = fmaf(p, vf[c], o[gi][c]);
+        }
+    }
+    float *s_o = s_w;  // [waves][G][D]
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            float v = o[gi][c];
+#pragma unroll
+            for (int off = LPR; off < 64; off <<= 1) v += __shfl_xor(v, off);
+            if (lane < LPR) s_o[(wave * G + gi) * D + sub * CH + c] = v;
+        }
+    __syncthreads();
+    for (int t = tid; t < G * D; t += kDecThreads) {
+        const int gi = t / D, c = t % D;
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < kDecWaves; ++w) v += s_o[(w * G + gi) * D + c];
+        const int64_t oi = ((int64_t)(b * g.Hq + h * G + gi)) * D + c;
+        if constexpr (ESIZE == 2)
+            ((uint16_t *)g.out)[oi] = (uint16_t)f32_to_bf16_rne(v);
+        else
+            ((float *)g.out)[oi] = v;
+    }
+    if (tid == 0) {
+        const int victim = s_victim;
+        posz[victim] = -1;
+        g.free_slot[z] = victim;
+    }
+}
+
+template <int ESIZE, int D>
+static hipError_t launch_g(const DecodeGeom &g, hipStream_t st) {
+    const int live = g.budget + 1;
+    const int w_floats = max(g.G * live, kDecWaves * g.G * D);
+    const size_t smem = (size_t)(w_floats + g.G * live) * sizeof(float);
+    dim3 grid(g.batch * g.Hkv);
+#define AHA_DEC(GG)                                                                              \
+    {                                                                                            \
+        static size_t attr = 0;                                                                  \
+        if (smem > attr) {                                                                       \
+            hipError_t e = hipFuncSetAttribute((const void *)decode_kernel<ESIZE, D, GG>,        \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,       \
+                                               (int)smem);                                       \
+            if (e != hipSuccess) return e;                                                       \
+            attr = smem;                                                                         \
+        }                                                                                        \
+        hipLaunchKernelGGL((decode_kernel<ESIZE, D, GG>), grid, dim3(kDecThreads), smem, st, g,  \
+                           w_floats);                                                            \
+    }
+    switch (g.G) {
+        case 1: AHA_DEC(1) break;
+        case 2: AHA_DEC(2) break;
+        case 3: AHA_DEC(3) break;
+        case 4: AHA_DEC(4) break;
+        case 5: AHA_DEC(5) break;
+        case 6: AHA_DEC(6) break;
+        case 7: AHA_DEC(7) break;
+        default: AHA_DEC(8) break;
+    }
+#undef AHA_DEC
+    return hipGetLastError();
+}
+
+hipError_t launch_decode(const DecodeGeom &g, int dtype, hipStream_t st) {
+    if (dtype == AHA_BF16)
+        return g.d == 64 ? launch_g<2, 64>(g, st) : launch_g<2, 128>(g, st);
+    return g.d == 64 ? launch_g<4, 64>(g, st) : launch_g<4, 128>(g, st);
+}
+
+}  // namespace aha

@@ -1,0 +1,391 @@
+// bf16 eviction scores on the gfx950 matrix cores (Sec. 4.1 - 4.3; Alg. 1
+// Prefill).  Two passes, both recomputing tiles of K Q^T with
+// v_mfma_f32_32x32x16_bf16 (keys on M, queries on N); the n x n probability
+// matrix never exists in memory.
+//
+//   pass 1: per observed query row, max and sum of exp2 over its keys
+//           (log2 domain, scale applied in fp32 after the MFMA);
+//   pass 2: per key, sum over the observed rows of exp2(t - L_row), times the
+//           value prior.
+//
+// With keys on M the 32x32 accumulator gives every lane ONE query column
+// (lane % 32) and 16 key rows, so the per-row scale, maximum and log-sum-exp
+// are per-lane scalars in both passes; pass 1 reduces over keys in-lane, and
+// pass 2 accumulates over query blocks in-lane and folds the 32 lanes of a
+// half-wave once per key block.
+//
+// Work split: a workgroup keeps one tile of query rows (up to 256 flattened
+// rows of a KV head's query group) in LDS as the B operand; each of its four
+// waves owns 64-key blocks whose A fragments it loads straight from global
+// memory into registers (each K byte is fetched once per tile), so waves run
+// independently between the tile barriers.
+#include "aha_dev.h"
+#include "aha_host.h"
+
+namespace aha {
+
+constexpr int kMB = 2;                 // 32-key M blocks per wave step
+constexpr int kWaveKeys = 32 * kMB;    // keys per wave step
+constexpr int kWgKeys = 4 * kWaveKeys; // keys per workgroup step (= kP2Keys)
+static_assert(kWgKeys == kP2Keys, "pass-2 grid assumes 256 keys per workgroup");
+
+template <int D, int NB>
+struct TileSmem {
+    static constexpr int LD = D + 8;  // padded row, 16-byte aligned, conflict-free b128 reads
+    static constexpr int ROWS = NB * 32;
+    static constexpr size_t q_bytes = (size_t)ROWS * LD * 2;
+    static constexpr size_t bytes = q_bytes + ROWS * 4 * 3;
+};
+
+// Query tile -> LDS: rows rho0 .. rho0+ROWS of the KV head's flattened query
+// rows (zero beyond R), and per row the log2-domain scale and the position.
+template <int D, int NB>
+__device__ __forceinline__ void load_q_tile(const ScoreGeom &g, const RowMap &rm, int b, int h,
+                                            int rho0, __bf16 *sQ, float *sLam, int *sPos) {
+    using S = TileSmem<D, NB>;
+    constexpr int CPR = D / 8;  // 16-byte chunks per row
+    const int tid = threadIdx.x;
+    for (int t = tid; t < S::ROWS * CPR; t += 256) {
+        const int rr = t / CPR, c = t % CPR, rho = rho0 + rr;
+        u32x4 w = {0u, 0u, 0u, 0u};
+        if (rho < g.R) {
+            const int hq = h * g.G + rm.head(rho);
+            const __bf16 *src = (const __bf16 *)g.q + b * g.qs[0] + hq * g.qs[1] +
+                                (int64_t)rm.pos(rho) * g.qs[2] + c * 8;
+            w = *(const u32x4 *)src;
+        }
+        *(u32x4 *)(sQ + rr * S::LD + c * 8) = w;
+    }
+    for (int rr = tid; rr < S::ROWS; rr += 256) {
+        const int rho = rho0 + rr, i = rm.pos(rho);
+        sPos[rr] = i;
+        sLam[rr] = rho < g.R ? row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor, i + 1,
+                                              g.budget, g.d)
+                             : 0.f;
+    }
+}
+
+// A fragments of a wave's key block: lane holds row kb + mb*32 + lane%32,
+// channels ks*16 + (lane/32)*8 .. +8.  Rows past the sequence are clamped
+// (their results are masked or never written).
+template <int D>
+__device__ __forceinline__ void load_a(const __bf16 *kbase, int64_t k_tstride, int kb, int n,
+                                       int lane, bf16x8 (&a)[kMB][D / 16]) {
+#pragma unroll
+    for (int mb = 0; mb < kMB; ++mb) {
+        const int row = min(kb + mb * 32 + (lane & 31), n - 1);
+        const __bf16 *p = kbase + (int64_t)row * k_tstride + (lane >> 5) * 8;
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) a[mb][ks] = *(const bf16x8 *)(p + ks * 16);
+    }
+}
+
+template <int D, int NB>
+__device__ __forceinline__ void mma_block(const bf16x8 (&a)[kMB][D / 16], const __bf16 *sQ,
+                                          int nb, int lane, f32x16 (&acc)[kMB]) {
+    using S = TileSmem<D, NB>;
+    const __bf16 *bp = sQ + (nb * 32 + (lane & 31)) * S::LD + (lane >> 5) * 8;
+#pragma unroll
+    for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+        const bf16x8 bfrag = *(const bf16x8 *)(bp + ks * 16);
+#pragma unroll
+        for (int mb = 0; mb < kMB; ++mb)
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb][ks], bfrag, acc[mb], 0, 0, 0);
+    }
+}
+
+// Key row of accumulator element v of M block mb, for this lane.
+__device__ __forceinline__ int acc_key(int kb, int mb, int v, int lane) {
+    return kb + mb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+}
+
+// ---------------------------------------------------------------- pass 1 --
+template <int D, int NB>
+__global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles,
+                                                            int chunk_keys, int nchunks,
+                                                            float2 *partial, int *counters,
+                                                            float *rowL) {
+    using S = TileSmem<D, NB>;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __bf16 *sQ = (__bf16 *)smem;
+    float *sLam = (float *)(smem + S::q_bytes);
+    int *sPos = (int *)(sLam + S::ROWS);
+    float2 *sRed = (float2 *)smem;  // reuses the query tile after the main loop
+    __shared__ int s_last;
+
+    const int chunk = blockIdx.x, qt = blockIdx.y, z = blockIdx.z;
+    const int b = z / g.Hkv, h = z % g.Hkv;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const RowMap rm{g.n, g.r, g.R};
+    const int rho0 = qt * S::ROWS;
+    const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
+
+    load_q_tile<D, NB>(g, rm, b, h, rho0, sQ, sLam, sPos);
+    __syncthreads();
+
+    float lam[NB], m[NB], s[NB];
+    int pos[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        lam[nb] = sLam[nb * 32 + (lane & 31)];
+        pos[nb] = sPos[nb * 32 + (lane & 31)];
+        m[nb] = -INFINITY;
+        s[nb] = 0.f;
+    }
+
+    const int key_begin = chunk * chunk_keys;
+    const int key_end = min(rm.max_pos(rho0, rho0 + S::ROWS) + 1, key_begin + chunk_keys);
+    for (int kb = key_begin + wave * kWaveKeys; kb < key_end; kb += kWgKeys) {
+        bf16x8 a[kMB][D / 16];
+        load_a<D>(kbase, g.ks[2], kb, g.n, lane, a);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int blo = rho0 + nb * 32;
+            if (rm.max_pos(blo, blo + 32) < kb) continue;  // nothing of this block sees these keys
+            f32x16 acc[kMB];
+            mma_block<D, NB>(a, sQ, nb, lane, acc);
+            const bool need_mask = kb + kWaveKeys - 1 > rm.min_pos(blo, blo + 32);
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float t = acc[mb][v] * lam[nb];
+                    if (need_mask && acc_key(kb, mb, v, lane) > pos[nb]) t = -INFINITY;
+                    acc[mb][v] = t;
+                    tmax = fmaxf(tmax, t);
+                }
+            const float mn = fmaxf(m[nb], tmax);
+            const float mref = mn == -INFINITY ? 0.f : mn;
+            float sum = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sum += fast_exp2(acc[mb][v] - mref);
+            s[nb] = s[nb] * fast_exp2(m[nb] - mref) + sum;
+            m[nb] = mn;
+        }
+    }
+
+    // fold the two half-waves (same query column, different key rows)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const float m2 = __shfl_xor(m[nb], 32), s2 = __shfl_xor(s[nb], 32);
+        const float mn = fmaxf(m[nb], m2);
+        const float mref = mn == -INFINITY ? 0.f : mn;
+        s[nb] = s[nb] * fast_exp2(m[nb] - mref) + s2 * fast_exp2(m2 - mref);
+        m[nb] = mn;
+    }
+    __syncthreads();  // everyone is done reading the query tile
+    if (lane < 32) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) sRed[wave * S::ROWS + nb * 32 + lane] = make_float2(m[nb], s[nb]);
+    }
+    __syncthreads();
+    float2 *my_partial = partial + ((int64_t)(z * n_qtiles + qt) * nchunks) * S::ROWS;
+    if (tid < S::ROWS) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) M = fmaxf(M, sRed[w * S::ROWS + tid].x);
+        const float mref = M == -INFINITY ? 0.f : M;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float2 e = sRed[w * S::ROWS + tid];
+            sum += e.y * fast_exp2(e.x - mref);
+        }
+        my_partial[(int64_t)chunk * S::ROWS + tid] = make_float2(M, sum);
+    }
+    // the last workgroup of this (problem, query tile) folds the chunks
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        const int ticket = atomicAdd(&counters[z * n_qtiles + qt], 1);
+        s_last = (ticket == nchunks - 1);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    if (tid < S::ROWS) {
+        float M = -INFINITY, sum = 0.f;
+        for (int c = 0; c < nchunks; ++c) {
+            const float *e = (const float *)&my_partial[(int64_t)c * S::ROWS + tid];
+            const float em = load_agent(e), es = load_agent(e + 1);
+            const float mn = fmaxf(M, em);
+            const float mref = mn == -INFINITY ? 0.f : mn;
+            sum = sum * fast_exp2(M - mref) + es * fast_exp2(em - mref);
+            M = mn;
+        }
+        rowL[(int64_t)(z * n_qtiles + qt) * S::ROWS + tid] =
+            (rho0 + tid < g.R) ? M + log2f(sum) : INFINITY;
+    }
+}
+
+// ---------------------------------------------------------------- pass 2 --
+// Sum of 16 per-lane values over the 32 lanes of each half-wave by recursive
+// halving: after the call lane l holds the total of element
+// v = 8*bit4(l) + 4*bit3(l) + 2*bit2(l) + bit1(l)   (both lanes of a pair hold it).
+__device__ __forceinline__ float fold16_over32(const f32x16 &x, int lane) {
+    float a[8], b4[4], c2[2];
+    bool hi = lane & 16;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const float send = hi ? x[t] : x[t + 8], keep = hi ? x[t + 8] : x[t];
+        a[t] = keep + __shfl_xor(send, 16);
+    }
+    hi = lane & 8;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const float send = hi ? a[t] : a[t + 4], keep = hi ? a[t + 4] : a[t];
+        b4[t] = keep + __shfl_xor(send, 8);
+    }
+    hi = lane & 4;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const float send = hi ? b4[t] : b4[t + 2], keep = hi ? b4[t + 2] : b4[t];
+        c2[t] = keep + __shfl_xor(send, 4);
+    }
+    hi = lane & 2;
+    const float send = hi ? c2[0] : c2[1], keep = hi ? c2[1] : c2[0];
+    float d = keep + __shfl_xor(send, 2);
+    d += __shfl_xor(d, 1);
+    return d;
+}
+
+template <int D, int NB>
+__global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_qtiles,
+                                                            const float *rowL,
+                                                            const float *gamma,
+                                                            const float *gblockmax,
+                                                            int n_vtiles, float *scores) {
+    using S = TileSmem<D, NB>;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __bf16 *sQ = (__bf16 *)smem;
+    float *sLam = (float *)(smem + S::q_bytes);
+    int *sPos = (int *)(sLam + S::ROWS);
+    float *sL = (float *)(sPos + S::ROWS);
+    __shared__ float s_gmax[4];
+
+    const int z = blockIdx.y;
+    const int b = z / g.Hkv, h = z % g.Hkv;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const RowMap rm{g.n, g.r, g.R};
+    const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
+    const int kb0 = blockIdx.x * kWgKeys;
+    const int kb = kb0 + wave * kWaveKeys;
+
+    bf16x8 a[kMB][D / 16];
+    load_a<D>(kbase, g.ks[2], kb, g.n, lane, a);
+
+    if (g.value_prior) {
+        float gm = 0.f;
+        for (int t = tid; t < n_vtiles; t += 256) gm = fmaxf(gm, gblockmax[z * n_vtiles + t]);
+        gm = wave_max(gm);
+        if (lane == 0) s_gmax[wave] = gm;
+    }
+
+    f32x16 col[kMB];
+#pragma unroll
+    for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) col[mb][v] = 0.f;
+
+    for (int qt = 0; qt < n_qtiles; ++qt) {
+        const int rho0 = qt * S::ROWS;
+        if (rm.max_pos(rho0, rho0 + S::ROWS) < kb0) continue;  // workgroup-uniform
+        __syncthreads();
+        load_q_tile<D, NB>(g, rm, b, h, rho0, sQ, sLam, sPos);
+        for (int rr = tid; rr < S::ROWS; rr += 256)
+            sL[rr] = rowL[(int64_t)(z * n_qtiles + qt) * S::ROWS + rr];
+        __syncthreads();
+        if (kb >= g.n) continue;  // wave-uniform; barriers above are still reached
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int blo = rho0 + nb * 32;
+            if (rm.max_pos(blo, blo + 32) < kb) continue;
+            f32x16 acc[kMB];
+            mma_block<D, NB>(a, sQ, nb, lane, acc);
+            const float lam = sLam[nb * 32 + (lane & 31)];
+            const float L = sL[nb * 32 + (lane & 31)];
+            const int pos = sPos[nb * 32 + (lane & 31)];
+            const bool need_mask = kb + kWaveKeys - 1 > rm.min_pos(blo, blo + 32);
+#pragma unroll
+            for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float p = fast_exp2(fmaf(acc[mb][v], lam, -L));
+                    if (need_mask && acc_key(kb, mb, v, lane) > pos) p = 0.f;
+                    col[mb][v] += p;
+                }
+        }
+    }
+    __syncthreads();
+    float ginv = 1.f;
+    if (g.value_prior)
+        ginv = 1.f / fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3]));
+#pragma unroll
+    for (int mb = 0; mb < kMB; ++mb) {
+        const float tot = fold16_over32(col[mb], lane);
+        const int v = ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2 +
+                      ((lane >> 1) & 1);
+        const int j = acc_key(kb, mb, v, lane);
+        if ((lane & 1) == 0 && j < g.n) {
+            float out = tot;
+            if (g.value_prior) out = tot * (gamma[(int64_t)z * g.n + j] * ginv);
+            scores[(int64_t)z * g.n + j] = out;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- launch --
+template <int D, int NB>
+static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
+                           hipStream_t st) {
+    using S = TileSmem<D, NB>;
+    char *w = (char *)ws;
+    float2 *partial = (float2 *)(w + pl.off_partial);
+    int *counters = (int *)(w + pl.off_counters);
+    float *rowL = (float *)(w + pl.off_rowL);
+    const float *gamma = (const float *)(w + pl.off_gamma);
+    const float *gbm = (const float *)(w + pl.off_gblockmax);
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)bf16_pass1_kernel<D, NB>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)S::bytes);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void *)bf16_pass2_kernel<D, NB>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::bytes);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    dim3 g1(pl.nchunks, pl.n_qtiles, pl.Z);
+    hipLaunchKernelGGL((bf16_pass1_kernel<D, NB>), g1, dim3(256), S::bytes, st, g, pl.n_qtiles,
+                       pl.chunk_keys, pl.nchunks, partial, counters, rowL);
+    dim3 g2((g.n + kWgKeys - 1) / kWgKeys, pl.Z);
+    hipLaunchKernelGGL((bf16_pass2_kernel<D, NB>), g2, dim3(256), S::bytes, st, g, pl.n_qtiles,
+                       rowL, gamma, gbm, pl.n_vtiles, scores);
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_d(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
+                           hipStream_t st) {
+    switch (pl.NB) {
+        case 1: return launch_t<D, 1>(g, pl, ws, scores, st);
+        case 2: return launch_t<D, 2>(g, pl, ws, scores, st);
+        case 4: return launch_t<D, 4>(g, pl, ws, scores, st);
+        default: return launch_t<D, 8>(g, pl, ws, scores, st);
+    }
+}
+
+hipError_t launch_score_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
+                             hipStream_t st) {
+    return g.d == 64 ? launch_d<64>(g, pl, ws, scores, st) : launch_d<128>(g, pl, ws, scores, st);
+}
+
+}  // namespace aha

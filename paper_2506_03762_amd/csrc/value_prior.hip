@@ -1,0 +1,92 @@
+// Value prior (Sec. 4.3): nu_j = ||V_j||^2, gamma = average pool of nu over
+// tokens (odd width, stride 1, mean over the in-range taps), and the per-tile
+// maxima of gamma from which the consumers form gamma / max(gamma).
+//
+// HBM-bound: V is read exactly once (plus (pool-1)/2 halo rows per tile).
+// The same launch clears the ticket counters that the score pass uses, so no
+// separate fill is needed.
+#include "aha_dev.h"
+#include "aha_host.h"
+
+namespace aha {
+
+// One workgroup = kVTileRows consecutive tokens of one (batch, KV head).
+// 16-byte loads; LPR lanes cover one row.
+template <int ESIZE>
+__global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, float *gamma,
+                                                     float *gblockmax, int *counters,
+                                                     int counters_per_z) {
+    const int z = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
+    if (tile == 0) {
+        for (int t = tid; t < counters_per_z; t += 256) counters[z * counters_per_z + t] = 0;
+    }
+    if (!g.value_prior) return;
+
+    __shared__ float s_nu[kVTileRows + 256];
+    __shared__ float s_max[4];
+    const int b = z / g.Hkv, h = z % g.Hkv;
+    const char *vbase =
+        (const char *)g.v + (int64_t)ESIZE * (b * g.vs[0] + h * g.vs[1]);
+    const int half = (g.pool - 1) / 2;
+    const int t0 = tile * kVTileRows;
+    const int lo = max(0, t0 - half);
+    const int hi = min(g.n, t0 + kVTileRows + half);  // exclusive
+    const int lpr = g.d * ESIZE / 16;                 // lanes per row: 8, 16 or 32
+    const int rows_per_pass = 256 / lpr;
+    const int sub = tid % lpr, rloc = tid / lpr;
+
+    for (int row = lo + rloc; row < hi; row += rows_per_pass) {
+        const u32x4 w = *(const u32x4 *)(vbase + (int64_t)ESIZE * row * g.vs[2] + sub * 16);
+        float s = 0.f;
+        if (ESIZE == 2) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                float a = bf16_lo(w[t]), c = bf16_hi(w[t]);
+                s = fmaf(a, a, s);
+                s = fmaf(c, c, s);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                float a = __uint_as_float(w[t]);
+                s = fmaf(a, a, s);
+            }
+        }
+        for (int o = lpr >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o);
+        if (sub == 0) s_nu[row - lo] = s;
+    }
+    __syncthreads();
+
+    const int j = t0 + tid;
+    float gam = 0.f;
+    if (j < g.n) {
+        const int a = max(0, j - half), e = min(g.n - 1, j + half);
+        float s = 0.f;
+        for (int t = a; t <= e; ++t) s += s_nu[t - lo];
+        gam = s / (float)(e - a + 1);
+        gamma[(int64_t)z * g.n + j] = gam;
+    }
+    float m = wave_max(gam);
+    if ((tid & 63) == 0) s_max[tid >> 6] = m;
+    __syncthreads();
+    if (tid == 0)
+        gblockmax[z * n_vtiles + tile] = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+}
+
+hipError_t launch_value_prior(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
+                              hipStream_t st) {
+    char *w = (char *)ws;
+    float *gamma = (float *)(w + pl.off_gamma);
+    float *gbm = (float *)(w + pl.off_gblockmax);
+    int *counters = (int *)(w + pl.off_counters);
+    dim3 grid(g.value_prior ? pl.n_vtiles : 1, pl.Z);
+    if (g.dtype == AHA_BF16)
+        hipLaunchKernelGGL(vprior_kernel<2>, grid, dim3(256), 0, st, g, pl.n_vtiles, gamma, gbm,
+                           counters, pl.n_qtiles);
+    else
+        hipLaunchKernelGGL(vprior_kernel<4>, grid, dim3(256), 0, st, g, pl.n_vtiles, gamma, gbm,
+                           counters, pl.n_qtiles);
+    return hipGetLastError();
+}
+
+}  // namespace aha

@@ -1,0 +1,126 @@
+"""Host side of the C ABI, no GPU needed: the library loads, exports every
+symbol the header declares, sizes its workspace and rejects bad arguments
+before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_03762_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2506_03762_amd import build
+        build.build()
+    return B.load()
+
+
+def good(**kw):
+    base = dict(batch=1, n_q_heads=8, n_kv_heads=2, head_dim=128, seq_len=4096, window=64,
+                budget=512, recent=64, dtype=B.AHA_BF16, q_stride=(8 * 4096 * 128, 4096 * 128, 128),
+                k_stride=(2 * 4096 * 128, 4096 * 128, 128), v_stride=(2 * 4096 * 128, 4096 * 128, 128))
+    base.update(kw)
+    return B.Params(**base)
+
+
+def test_header_symbols_are_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "aha.h")).read()
+    declared = set(re.findall(r"\b(aha_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert B.version().startswith("aha-gfx950")
+
+
+def test_struct_layout_matches_header():
+    # 14 four-byte fields then nine int64 strides
+    assert ctypes.sizeof(B.aha_params) == 14 * 4 + 9 * 8
+    assert B.aha_params.q_stride.offset == 56
+
+
+def test_workspace_bytes(lib):
+    n1 = B.workspace_bytes(good())
+    assert n1 > 0 and n1 % 256 == 0
+    assert B.workspace_bytes(good(seq_len=32768, budget=2048)) > n1
+    assert B.workspace_bytes(good(dtype=B.AHA_F32, head_dim=64)) > 0
+    # full accumulation needs row statistics for every row
+    assert B.workspace_bytes(good(window=4096)) > n1
+
+
+DUMMY = ctypes.c_void_p(0x1000)
+
+
+def call_prefill(lib, p, q=DUMMY, k=DUMMY, v=DUMMY, s=DUMMY, ws=DUMMY, nbytes=1 << 40):
+    cp = p.c()
+    return lib.aha_prefill_scores(ctypes.byref(cp), q, k, v, s, ws, nbytes, None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n_q_heads=7), B.AHA_ERR_INVALID_ARG),
+    (dict(head_dim=96), B.AHA_ERR_UNSUPPORTED),
+    (dict(budget=0), B.AHA_ERR_INVALID_ARG),
+    (dict(budget=5000), B.AHA_ERR_INVALID_ARG),
+    (dict(recent=513), B.AHA_ERR_INVALID_ARG),
+    (dict(recent=-1), B.AHA_ERR_INVALID_ARG),
+    (dict(window=0), B.AHA_ERR_INVALID_ARG),
+    (dict(window=4097), B.AHA_ERR_INVALID_ARG),
+    (dict(pool_kernel=4), B.AHA_ERR_INVALID_ARG),
+    (dict(pool_kernel=257), B.AHA_ERR_INVALID_ARG),
+    (dict(dtype=3), B.AHA_ERR_INVALID_ARG),
+    (dict(scale_mode=2), B.AHA_ERR_INVALID_ARG),
+    (dict(scale_mode=B.AHA_SCALE_FIXED, fixed_scale=-0.1), B.AHA_ERR_INVALID_ARG),
+    (dict(k_stride=(0, 0, 100)), B.AHA_ERR_INVALID_ARG),   # not a multiple of 8 elements
+    (dict(q_stride=(0, 0, 64)), B.AHA_ERR_INVALID_ARG),    # rows overlap
+    (dict(batch=0), B.AHA_ERR_INVALID_ARG),
+])
+def test_bad_params_are_rejected(lib, kw, code):
+    assert call_prefill(lib, good(**kw)) == code
+    assert len(B.load().aha_last_error()) > 0
+
+
+def test_bad_pointers_and_workspace(lib):
+    p = good()
+    assert call_prefill(lib, p, q=None) == B.AHA_ERR_INVALID_ARG
+    assert call_prefill(lib, p, k=ctypes.c_void_p(0x1004)) == B.AHA_ERR_INVALID_ARG
+    assert call_prefill(lib, p, s=None) == B.AHA_ERR_INVALID_ARG
+    assert call_prefill(lib, p, v=None) == B.AHA_ERR_INVALID_ARG
+    assert call_prefill(lib, p, ws=None) == B.AHA_ERR_WORKSPACE
+    assert call_prefill(lib, p, ws=ctypes.c_void_p(0x1010)) == B.AHA_ERR_WORKSPACE
+    assert call_prefill(lib, p, nbytes=B.workspace_bytes(p) - 1) == B.AHA_ERR_WORKSPACE
+    assert b"workspace" in lib.aha_last_error()
+    cp = p.c()
+    assert lib.aha_workspace_bytes(ctypes.byref(cp), None) == B.AHA_ERR_INVALID_ARG
+    assert lib.aha_workspace_bytes(None, ctypes.byref(ctypes.c_size_t())) == B.AHA_ERR_INVALID_ARG
+
+
+def test_other_entry_points_validate(lib):
+    p = good()
+    cp = p.c()
+    assert lib.aha_select_topk(ctypes.byref(cp), None, DUMMY, None, 0, None) == B.AHA_ERR_INVALID_ARG
+    assert lib.aha_compact_kv(ctypes.byref(cp), DUMMY, DUMMY, DUMMY, DUMMY, DUMMY, DUMMY, DUMMY,
+                              DUMMY, DUMMY, 512, None) == B.AHA_ERR_INVALID_ARG  # slots < B+1
+    assert lib.aha_compact_kv(ctypes.byref(cp), DUMMY, DUMMY, DUMMY, DUMMY, None, DUMMY, DUMMY,
+                              DUMMY, DUMMY, 513, None) == B.AHA_ERR_INVALID_ARG
+    args = [DUMMY] * 8
+    assert lib.aha_decode_step(ctypes.byref(cp), *args, 513, 512, DUMMY, None, 0, None) \
+        == B.AHA_ERR_INVALID_ARG                                              # logical_pos too small
+    assert lib.aha_decode_step(ctypes.byref(cp), *args, 100, 4097, DUMMY, None, 0, None) \
+        == B.AHA_ERR_INVALID_ARG                                              # too few slots
+    cp3 = good(n_q_heads=18).c()
+    assert lib.aha_decode_step(ctypes.byref(cp3), *args, 513, 4097, DUMMY, None, 0, None) \
+        == B.AHA_ERR_UNSUPPORTED                                              # group of 9
+    cpb = good(budget=4096, n_q_heads=16).c()
+    assert lib.aha_decode_step(ctypes.byref(cpb), *args, 4097, 5000, DUMMY, None, 0, None) \
+        == B.AHA_ERR_UNSUPPORTED                                              # dots exceed LDS
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libaha.so")
+    with pytest.raises(RuntimeError, match="not built"):
+        B.load()

@@ -1,0 +1,192 @@
+"""Parity of the HIP path (through the C ABI) with the float64 oracle, element
+by element on the same seeded inputs: sizes the oracle finishes in seconds,
+spanning several tiles and ragged tails, plus the edge cases."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import SCALE_ADAPTIVE, SCALE_FIXED
+from paper_2506_03762_amd import synth
+from tests import harness as H
+from tests.harness import Opts
+
+pytestmark = pytest.mark.gpu
+
+
+def check_prefill(w, opts=Opts(), decode_steps=0, layer=0):
+    print("case", w.name, w.dtype, "n", w.seq_len, "Hq/Hkv", w.n_q_heads, w.n_kv_heads,
+          "d", w.head_dim, "B", w.budget, "Br", w.recent, opts, flush=True)
+    inputs = synth.make_prefill(w, layer)
+    gpu = H.run_prefill_gpu(w, opts, inputs)
+    ref = H.run_prefill_oracle(w, opts, inputs)
+    H.assert_scores_close(gpu.scores, ref.scores, w, opts)
+    excused = H.assert_sets_match(gpu.idx, ref.idx, ref.scores, w)
+    H.assert_compact_matches(gpu, w, inputs[1], inputs[2])
+    if decode_steps:
+        flips = H.run_and_check_decode(w, gpu, ref, decode_steps, opts)
+        assert flips <= 1
+    return gpu, ref, excused
+
+
+# ------------------------------------------------------------------- fp32 --
+def test_c1_tiny_fp32_exact_config():
+    gpu, ref, excused = check_prefill(synth.C1, decode_steps=8)
+    assert excused == 0
+    assert H.max_rel_err(gpu.scores, ref.scores, synth.C1) < 1e-5
+
+
+@pytest.mark.parametrize("opts", [
+    Opts(value_prior=False),
+    Opts(scale_mode=SCALE_FIXED, fixed_scale=0.125),
+    Opts(window=512, scale_mode=SCALE_FIXED, fixed_scale=0.125, value_prior=False),  # H2O
+    Opts(window=512),                                   # full accumulation, adaptive + floor
+    Opts(lambda_floor=0.0, pool=1),
+    Opts(window=1, pool=15),
+    Opts(scale_mode=SCALE_FIXED, fixed_scale=0.0, value_prior=False),  # uniform rows
+])
+def test_fp32_switches(opts):
+    check_prefill(synth.C1, opts)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(seq_len=515, budget=131, recent=17, window=29),             # ragged everything
+    dict(seq_len=300, head_dim=128, n_q_heads=4, n_kv_heads=2, budget=64, recent=8, window=24),
+    dict(seq_len=257, batch=3, n_q_heads=6, n_kv_heads=2, budget=40, recent=0, window=16),
+    dict(seq_len=96, budget=96, recent=32, window=32),               # keep everything
+    dict(seq_len=64, budget=16, recent=16, window=8),                # recents only
+    dict(seq_len=33, budget=9, recent=3, window=33),
+])
+def test_fp32_shapes(kw):
+    w = synth.scaled(synth.C1, name="c1_variant", **kw)
+    check_prefill(w, decode_steps=3)
+
+
+# ------------------------------------------------------------------- bf16 --
+BF = synth.scaled(synth.C3, name="bf16_small", seq_len=1536, n_q_heads=8, n_kv_heads=2,
+                  budget=192, recent=32, window=32)
+
+
+def test_bf16_small_gqa_with_rope():
+    gpu, ref, excused = check_prefill(BF, decode_steps=6)
+    assert H.max_rel_err(gpu.scores, ref.scores, BF) < 2e-3   # fp32 accumulation: far inside 2e-2
+
+
+@pytest.mark.parametrize("opts", [
+    Opts(value_prior=False),
+    Opts(scale_mode=SCALE_FIXED, fixed_scale=1 / math.sqrt(128), value_prior=False),
+    Opts(window=1536, scale_mode=SCALE_FIXED, fixed_scale=1 / math.sqrt(128), value_prior=False),
+    Opts(window=1536),
+    Opts(window=1, lambda_floor=0.0, pool=3),
+    Opts(window=100, pool=31),
+])
+def test_bf16_switches(opts):
+    check_prefill(BF, opts)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(seq_len=1573, window=37, budget=211, recent=19),                      # ragged tail
+    dict(seq_len=700, n_q_heads=4, n_kv_heads=4, window=64, budget=128, recent=64),   # MHA
+    dict(seq_len=640, n_q_heads=16, n_kv_heads=2, window=48, budget=100, recent=10),  # G=8
+    dict(seq_len=520, head_dim=64, n_q_heads=4, n_kv_heads=2, window=20, budget=64, recent=8),
+    dict(seq_len=300, batch=3, n_q_heads=2, n_kv_heads=1, window=300, budget=50, recent=5),
+    dict(seq_len=200, n_q_heads=6, n_kv_heads=2, window=40, budget=200, recent=40),   # G=3, keep all
+    dict(seq_len=31, n_q_heads=2, n_kv_heads=2, window=31, budget=8, recent=8),       # below one tile
+])
+def test_bf16_shapes(kw):
+    w = synth.scaled(BF, name="bf16_variant", **kw)
+    check_prefill(w, decode_steps=3)
+
+
+def test_c2_llama2_7b_layer():
+    gpu, ref, excused = check_prefill(synth.C2, decode_steps=4)
+    print("C2 excused near-ties:", excused)
+
+
+def test_strided_inputs_token_major_layout():
+    """Q/K/V stored [b, n, h, d] and passed by strides give the same result."""
+    import torch
+    from paper_2506_03762_amd import binding as B
+    w = BF
+    Q, K, V = synth.make_prefill(w)
+    opts = Opts()
+    dense = H.run_prefill_gpu(w, opts, (Q, K, V))
+    q, k, v = (H.to_device(np.ascontiguousarray(a.transpose(0, 2, 1, 3)), w.dtype).permute(0, 2, 1, 3)
+               for a in (Q, K, V))
+    p = H.gpu_params(w, opts).with_strides(q, k, v)
+    assert p.q_stride[2] == w.n_q_heads * w.head_dim
+    ws = B.alloc_workspace(p)
+    scores = torch.empty((w.batch, w.n_kv_heads, w.seq_len), dtype=torch.float32, device="cuda")
+    B.aha_prefill_scores(p, q, k, v, scores, ws)
+    assert np.array_equal(scores.cpu().numpy().astype(np.float64), dense.scores)
+
+
+def test_repeat_calls_are_bit_identical():
+    a = H.run_prefill_gpu(BF)
+    b = H.run_prefill_gpu(BF)
+    assert np.array_equal(a.scores, b.scores) and np.array_equal(a.idx, b.idx)
+
+
+# ------------------------------------------------------------------ top-k --
+def topk_both(scores32, budget, recent):
+    import torch
+    from paper_2506_03762_amd import binding as B
+    b, h, n = scores32.shape
+    p = B.Params(batch=b, n_q_heads=h, n_kv_heads=h, head_dim=128, seq_len=n, window=1,
+                 budget=budget, recent=recent)
+    idx = torch.full((b, h, budget), -5, dtype=torch.int32, device="cuda")
+    B.aha_select_topk(p, torch.from_numpy(scores32).cuda(), idx)
+    return idx.cpu().numpy(), oracle.select_topk(scores32.astype(np.float64), budget, recent)
+
+
+@pytest.mark.parametrize("n,budget,recent", [
+    (32768, 2048, 64), (32768, 1024, 64), (16384, 3276, 64), (4096, 512, 64), (1000, 1000, 10),
+    (777, 1, 0), (777, 1, 1), (5, 3, 1), (1, 1, 0), (40000, 5000, 100),
+])
+def test_topk_bit_exact_on_random_and_tied_scores(n, budget, recent):
+    rng = np.random.default_rng(n + budget)
+    heavy = np.exp(rng.standard_normal((2, 3, n)) * 3).astype(np.float32)      # wide range
+    tied = (rng.integers(0, 7, (2, 3, n)) / 8.0).astype(np.float32)            # many exact ties
+    const = np.full((1, 2, n), 0.25, np.float32)
+    zeros = np.zeros((1, 1, n), np.float32)
+    narrow = (1.0 + rng.random((1, 2, n)) * 1e-6).astype(np.float32)           # keys differ in low bits
+    for s in (heavy, tied, const, zeros, narrow):
+        got, want = topk_both(s, budget, recent)
+        assert np.array_equal(got, want)
+
+
+# ----------------------------------------------------------------- decode --
+def test_decode_many_steps_gqa4_bf16():
+    w = synth.scaled(BF, name="bf16_decode", seq_len=900, n_q_heads=16, n_kv_heads=4,
+                     budget=130, recent=20, window=32, batch=2)
+    check_prefill(w, decode_steps=40)
+
+
+def test_decode_fixed_scale_and_no_recent_fp32():
+    w = synth.scaled(synth.C1, name="f32_decode", budget=60, recent=0, window=16)
+    check_prefill(w, Opts(scale_mode=SCALE_FIXED, fixed_scale=0.125), decode_steps=20)
+
+
+def test_decode_extra_slots_are_ignored():
+    """cache_slots larger than budget + 1: the surplus slots stay untouched."""
+    import torch
+    from paper_2506_03762_amd import binding as B
+    w = BF
+    ref = H.run_prefill_oracle(w)
+    p = H.gpu_params(w)
+    oc = oracle.compact_kv(ref.cache.K[:, :, :w.budget], ref.cache.V[:, :, :w.budget],
+                           ref.cache.F[:, :, :w.budget],
+                           np.broadcast_to(np.arange(w.budget, dtype=np.int32),
+                                           ref.idx.shape), slots=w.budget + 5)
+    oc.pos[:, :, :w.budget] = ref.cache.pos[:, :, :w.budget]
+    oc.F = oc.F.astype(np.float32).astype(np.float64)
+    gc = H.upload_cache(oc, w, p)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device="cuda")
+    q, k, v = synth.make_decode_inputs(w, 0)
+    B.aha_decode_step(p, H.to_device(q, "bf16"), H.to_device(k, "bf16"), H.to_device(v, "bf16"),
+                      gc.k, gc.v, gc.scores, gc.pos, gc.free_slot, w.seq_len + 1, out)
+    oracle.decode_step(oc, q, k, v, w.seq_len + 1, H.oracle_cfg(w, Opts()))
+    assert np.array_equal(gc.pos.cpu().numpy(), oc.pos)
+    assert np.array_equal(gc.free_slot.cpu().numpy(), oc.free_slot)
+    assert np.all(gc.pos.cpu().numpy()[:, :, w.budget + 1:] == -1)
