@@ -1,0 +1,288 @@
+#!/usr/bin/env python3
+"""Benchmark of the AhaKV eviction hot path on one MI355X.
+
+One "step" is one pass of the whole path over one layer of synthetic input
+already resident in HBM: prefill eviction scores -> top-k selection -> KV
+compaction -> one decode step with running eviction on the fresh cache.  The
+workload is the 32K-context GQA layer (batch 1, 32 query / 8 KV heads,
+head_dim 128, bf16, window 64, budget 2048).
+
+Prints ONE JSON line (see the design doc for the meaning of every field).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, GB/s
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def avg_ms(pairs):
+    return sum(a.elapsed_time(b) for a, b in pairs) / max(len(pairs), 1)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="skip the oracle timing (used under rocprofv3)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the C4 decode and C2 full-accumulation side measurements")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2506_03762_amd import binding as B, synth
+    from tests import harness as H
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.load()
+    K_STEPS, W_STEPS = args.steps, args.warmup
+
+    # ------------------------------------------------------------ workload --
+    w = synth.C3
+    log("generating", w.name)
+    Q, K, V = synth.make_prefill(w, threads=16)
+    q, k, v = (H.to_device(a, w.dtype) for a in (Q, K, V))
+    p = H.gpu_params(w).with_strides(q, k, v)
+    ws = B.alloc_workspace(p)
+    b, hq, hk, n, d, G = w.batch, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim, w.group
+    scores = torch.empty((b, hk, n), dtype=torch.float32, device="cuda")
+    idx = torch.empty((b, hk, w.budget), dtype=torch.int32, device="cuda")
+    cache = B.CompactCache.empty(p)
+    qn, kn, vn = (H.to_device(a, w.dtype) for a in synth.make_decode_inputs(w, 0))
+    out = torch.empty((b, hq, d), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        B.aha_prefill_scores(p, q, k, v, scores, ws)
+        B.aha_select_topk(p, scores, idx, ws)
+        B.aha_compact_kv(p, k, v, scores, idx, cache.k, cache.v, cache.scores, cache.pos,
+                         cache.free_slot)
+        B.aha_decode_step(p, qn, kn, vn, cache.k, cache.v, cache.scores, cache.pos,
+                          cache.free_slot, n + 1, out)
+
+    for _ in range(W_STEPS):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K_STEPS):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / K_STEPS
+
+    # ------------------------------------------- per-kernel times (events) --
+    def ev():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record()
+        return e
+
+    stage_sets, call_sets = [], []
+    for _ in range(K_STEPS):
+        st = [ev() for _ in range(4)]
+        B.profile_events(st)
+        B.aha_prefill_scores(p, q, k, v, scores, ws)
+        B.profile_events(None)
+        e0 = ev(); B.aha_select_topk(p, scores, idx, ws)
+        e1 = ev(); B.aha_compact_kv(p, k, v, scores, idx, cache.k, cache.v, cache.scores,
+                                    cache.pos, cache.free_slot)
+        e2 = ev(); B.aha_decode_step(p, qn, kn, vn, cache.k, cache.v, cache.scores, cache.pos,
+                                     cache.free_slot, n + 1, out)
+        e3 = ev()
+        stage_sets.append(st)
+        call_sets.append((e0, e1, e2, e3))
+    torch.cuda.synchronize()
+    kt = {
+        "value_prior": avg_ms([(s[0], s[1]) for s in stage_sets]),
+        "score_pass1": avg_ms([(s[1], s[2]) for s in stage_sets]),
+        "score_pass2": avg_ms([(s[2], s[3]) for s in stage_sets]),
+        "topk": avg_ms([(c[0], c[1]) for c in call_sets]),
+        "compact": avg_ms([(c[1], c[2]) for c in call_sets]),
+        "decode_step": avg_ms([(c[2], c[3]) for c in call_sets]),
+    }
+    e = 2  # bf16 bytes
+    kbytes = b * hk * n * d * e
+    qbytes = b * hq * w.window * d * e
+    alg = {  # algorithmic HBM bytes per launch
+        "value_prior": kbytes + b * hk * n * 4,
+        "score_pass1": kbytes + qbytes,
+        "score_pass2": kbytes + qbytes + b * hk * n * 4,
+        "topk": b * hk * n * 4 + b * hk * w.budget * 4,
+        "compact": 4 * b * hk * w.budget * d * e + b * hk * w.budget * 12,
+        "decode_step": b * hk * (2 * (w.budget + 1) * d * e + 8 * (w.budget + 1) + 2 * d * e)
+                       + 2 * b * hq * d * e,
+    }
+    kernels = {name: {"us": kt[name] * 1e3, "alg_bytes": alg[name],
+                      "GBps": alg[name] / (kt[name] * 1e-3) / 1e9 if kt[name] > 0 else None}
+               for name in kt}
+    score_flops_pass = 2.0 * d * b * hq * (w.window * n - w.window * (w.window - 1) / 2)
+    for name in ("score_pass1", "score_pass2"):
+        kernels[name]["TFLOPs"] = score_flops_pass / (kt[name] * 1e-3) / 1e12
+    dom = max(("value_prior", "score_pass1", "score_pass2", "topk", "compact", "decode_step"),
+              key=lambda nm: kt[nm])
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["GBps"],
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dom]["GBps"] / HBM_PEAK_GBS,
+                "traffic": None}
+    # the whole score stage against the bytes the method needs once (K + V + Q window)
+    stage_ms = kt["value_prior"] + kt["score_pass1"] + kt["score_pass2"]
+    stage_bytes = 2 * kbytes + qbytes + b * hk * n * 4
+    roofline_stage = {"stage": "prefill_scores (3 launches)", "bound": "hbm",
+                      "achieved": stage_bytes / (stage_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                      "unit": "GB/s", "frac": stage_bytes / (stage_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "mfma_TFLOPs": 2 * score_flops_pass / (stage_ms * 1e-3) / 1e12}
+
+    result = {
+        "metric": "prefill eviction us/layer @32K ctx (scores + top-k + compaction + 1 decode step)",
+        "value": ms_per_step * 1e3, "unit": "us/layer", "n_gpus": 1, "steps": K_STEPS,
+        "warmup": W_STEPS, "ms_per_step": ms_per_step, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "batch": b, "n_q_heads": hq, "n_kv_heads": hk,
+                   "head_dim": d, "seq_len": n, "window": w.window, "budget": w.budget,
+                   "recent": w.recent, "scale": "adaptive", "value_prior": True},
+        "tokens_per_s": b * n / (ms_per_step * 1e-3),
+        "roofline": roofline, "roofline_stage": roofline_stage, "kernels": kernels,
+    }
+
+    if not args.no_extras:
+        result["decode_c4"] = bench_decode_c4(torch, B, synth, H, K_STEPS)
+        result["full_accumulation_c2"] = bench_full_c2(torch, B, synth, H, max(5, K_STEPS // 5))
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, (Q, K, V), synth, H)
+    print(json.dumps(result))
+
+
+def bench_decode_c4(torch, B, synth, H, steps):
+    """Decode step at batch 8 x 32 heads, budget 1024 (bound by HBM bandwidth)."""
+    w = synth.C4
+    log("generating", w.name)
+    Q, K, V = synth.make_prefill(w, threads=16)
+    q, k, v = (H.to_device(a, w.dtype) for a in (Q, K, V))
+    p = H.gpu_params(w).with_strides(q, k, v)
+    ws = B.alloc_workspace(p)
+    b, hq, hk, n, d = w.batch, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
+    scores = torch.empty((b, hk, n), dtype=torch.float32, device="cuda")
+    idx = torch.empty((b, hk, w.budget), dtype=torch.int32, device="cuda")
+    B.aha_prefill_scores(p, q, k, v, scores, ws)
+    B.aha_select_topk(p, scores, idx, ws)
+    ncopies = 4  # 4 x 134 MB of cache state: more than the 256 MB last-level cache
+    caches = [B.CompactCache.empty(p) for _ in range(ncopies)]
+    for c in caches:
+        B.aha_compact_kv(p, k, v, scores, idx, c.k, c.v, c.scores, c.pos, c.free_slot)
+    del q
+    nsteps = w.decode_steps
+    g = torch.Generator(device="cuda"); g.manual_seed(1234)
+    qs = torch.randn((nsteps, b, hq, d), device="cuda", generator=g).to(torch.bfloat16)
+    ks = torch.randn((nsteps, b, hk, d), device="cuda", generator=g).to(torch.bfloat16)
+    vs = torch.randn((nsteps, b, hk, d), device="cuda", generator=g).to(torch.bfloat16)
+    out = torch.empty((b, hq, d), dtype=torch.bfloat16, device="cuda")
+    alg = b * hk * (2 * (w.budget + 1) * d * 2 + 8 * (w.budget + 1) + 2 * d * 2) + 2 * b * hq * d * 2
+
+    def run(rotate):
+        # the paper-shaped run: 256 consecutive steps; mean over steps 32..255
+        evs = []
+        for t in range(nsteps):
+            c = caches[t % ncopies] if rotate else caches[0]
+            e0 = torch.cuda.Event(enable_timing=True); e0.record()
+            B.aha_decode_step(p, qs[t], ks[t], vs[t], c.k, c.v, c.scores, c.pos, c.free_slot,
+                              n + 1 + (t // ncopies if rotate else t), out)
+            e1 = torch.cuda.Event(enable_timing=True); e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        return avg_ms(evs[32:]) * 1e3
+
+    def reset():
+        for c in caches:
+            B.aha_compact_kv(p, k, v, scores, idx, c.k, c.v, c.scores, c.pos, c.free_slot)
+
+    run(False)  # warm-up pass over all 256 steps
+    reset()
+    us_hot = run(False)
+    reset()
+    us_cold = run(True)
+    return {"workload": w.name, "decode_step_us": us_hot, "tokens_per_s": b / (us_hot * 1e-6),
+            "alg_bytes": alg,
+            "roofline": {"bound": "hbm", "achieved": alg / (us_hot * 1e-6) / 1e9,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": alg / (us_hot * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                         "note": "134 MB of cache state fits the 256 MB last-level cache"},
+            "cache_defeated": {"decode_step_us": us_cold, "copies": ncopies,
+                               "achieved": alg / (us_cold * 1e-6) / 1e9,
+                               "frac": alg / (us_cold * 1e-6) / 1e9 / HBM_PEAK_GBS}}
+
+
+def bench_full_c2(torch, B, synth, H, steps):
+    """Full accumulation (window = n, fixed 1/sqrt(d), no value prior) on the
+    Llama-2-7B-shaped layer: the n x n contraction, bound by the matrix cores."""
+    w = synth.C2
+    log("generating", w.name)
+    Q, K, V = synth.make_prefill(w, threads=16)
+    q, k, v = (H.to_device(a, w.dtype) for a in (Q, K, V))
+    opts = H.Opts(window=w.seq_len, scale_mode=0, fixed_scale=1 / math.sqrt(w.head_dim),
+                  value_prior=False)
+    p = H.gpu_params(w, opts).with_strides(q, k, v)
+    ws = B.alloc_workspace(p)
+    b, hq, hk, n, d = w.batch, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
+    scores = torch.empty((b, hk, n), dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        B.aha_prefill_scores(p, q, k, v, scores, ws)
+    sets = []
+    for _ in range(steps):
+        st = []
+        for _ in range(4):
+            e = torch.cuda.Event(enable_timing=True); e.record(); st.append(e)
+        B.profile_events(st)
+        B.aha_prefill_scores(p, q, k, v, scores, ws)
+        B.profile_events(None)
+        sets.append(st)
+    torch.cuda.synchronize()
+    p1 = avg_ms([(s[1], s[2]) for s in sets]); p2 = avg_ms([(s[2], s[3]) for s in sets])
+    flops_pass = 2.0 * d * b * hq * n * (n + 1) / 2
+    tf = 2 * flops_pass / ((p1 + p2) * 1e-3) / 1e12
+    return {"workload": w.name + " window=n fixed-scale", "pass1_us": p1 * 1e3, "pass2_us": p2 * 1e3,
+            "flops_per_pass": flops_pass,
+            "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS},
+            "pass1_TFLOPs": flops_pass / (p1 * 1e-3) / 1e12,
+            "pass2_TFLOPs": flops_pass / (p2 * 1e-3) / 1e12}
+
+
+def cpu_baseline(w, inputs, synth, H):
+    """The float64 oracle, as it stands, on the host cores: the same step once."""
+    import numpy as np
+    import oracle
+    Q, K, V = inputs
+    log("timing the CPU oracle on", w.name)
+    qn, kn, vn = synth.make_decode_inputs(w, 0)
+    reps, t0 = 0, time.perf_counter()
+    while reps < 3 or time.perf_counter() - t0 < 10.0:
+        ref = H.run_prefill_oracle(w, H.Opts(), (Q, K, V))
+        oracle.decode_step(ref.cache, qn, kn, vn, w.seq_len + 1, H.oracle_cfg(w, H.Opts()))
+        reps += 1
+    dt = (time.perf_counter() - t0) / reps
+    cores = min(oracle.num_threads(), w.batch * w.n_kv_heads)
+    return {"value": dt * 1e6, "unit": "us/layer", "cores": cores, "kind": "oracle",
+            "sample": "the whole step (1 layer, all 8 KV heads; OpenMP over (batch, KV head)), mean of %d runs" % reps,
+            "tokens_per_s": w.batch * w.seq_len / dt}
+
+
+if __name__ == "__main__":
+    main()

@@ -176,6 +176,18 @@ int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_ne
                         int32_t cache_slots, int32_t logical_pos, void *out,
                         void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Optional stage timing for aha_prefill_scores (Sec. 4.1 - 4.3 are computed by
+ * three launches: value prior, row statistics, column sums).  `events` is an
+ * array of `count` caller-created hipEvent_t handles (HOST array, copied by
+ * the call); while set, aha_prefill_scores on this thread records events[0]
+ * before its first launch and events[1], [2], [3] after the value-prior,
+ * row-statistics and column-sum launches, on the call's stream.  count must
+ * be 0 (with events NULL: switch off) or 4.  The library neither creates,
+ * waits on nor destroys the events.
+ */
+int32_t aha_profile_events(void *const *events, int32_t count);
+
 /* Thread-local description of the last error returned on this thread. */
 const char *aha_last_error(void);
 

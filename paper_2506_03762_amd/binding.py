@@ -28,7 +28,7 @@ AHA_F32, AHA_BF16 = 0, 1
 AHA_SCALE_FIXED, AHA_SCALE_ADAPTIVE = 0, 1
 
 EXPORTS = ("aha_workspace_bytes", "aha_prefill_scores", "aha_select_topk", "aha_compact_kv",
-           "aha_decode_step", "aha_last_error", "aha_version")
+           "aha_decode_step", "aha_profile_events", "aha_last_error", "aha_version")
 
 
 class AhaError(RuntimeError):
@@ -70,7 +70,8 @@ def load() -> ctypes.CDLL:
     lib.aha_select_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.aha_compact_kv.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     lib.aha_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
-    for name in EXPORTS[:5]:
+    lib.aha_profile_events.argtypes = [ctypes.POINTER(vp), i32]
+    for name in EXPORTS[:6]:
         getattr(lib, name).restype = i32
     lib.aha_last_error.restype = ctypes.c_char_p
     lib.aha_version.restype = ctypes.c_char_p
@@ -181,6 +182,16 @@ def aha_decode_step(p: Params, q_new, k_new, v_new, k_cache, v_cache, scores_c, 
                                   _ptr(free_slot), int(k_cache.shape[2]), int(logical_pos),
                                   _ptr(out), _ptr(workspace),
                                   workspace.numel() if workspace is not None else 0, _stream()))
+
+
+def profile_events(events=None):
+    """Stage events for aha_prefill_scores: four recorded torch.cuda.Event objects
+    (enable_timing=True) or None to switch the hook off."""
+    if events is None:
+        _check(load().aha_profile_events(None, 0))
+        return
+    arr = (ctypes.c_void_p * 4)(*[ctypes.c_void_p(e.cuda_event) for e in events])
+    _check(load().aha_profile_events(arr, 4))
 
 
 @dataclass

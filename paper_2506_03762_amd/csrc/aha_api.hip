@@ -9,6 +9,12 @@
 namespace aha {
 
 static thread_local char g_err[512] = "";
+static thread_local hipEvent_t g_stage_ev[4] = {nullptr, nullptr, nullptr, nullptr};
+static thread_local bool g_stage_on = false;
+
+static hipError_t stage(int i, hipStream_t st) {
+    return g_stage_on ? hipEventRecord(g_stage_ev[i], st) : hipSuccess;
+}
 
 static int32_t fail(int32_t code, const char *fmt, ...) {
     va_list ap;
@@ -188,10 +194,16 @@ int32_t aha_prefill_scores(const aha_params *p, const void *q, const void *k, co
         return fail(AHA_ERR_UNSUPPORTED, "problem exceeds the launch grid limits");
     const ScoreGeom g = make_geom(p, q, k, v);
     hipStream_t st = (hipStream_t)stream;
+    if ((rc = hip_result(stage(0, st), "stage event"))) return rc;
     if ((rc = hip_result(launch_value_prior(g, pl, workspace, st), "value-prior kernel"))) return rc;
+    if ((rc = hip_result(stage(1, st), "stage event"))) return rc;
+    hipEvent_t mid = g_stage_on ? g_stage_ev[2] : nullptr;
     if (p->dtype == AHA_BF16)
-        return hip_result(launch_score_bf16(g, pl, workspace, scores, st), "bf16 score kernels");
-    return hip_result(launch_score_f32(g, pl, workspace, scores, st), "fp32 score kernels");
+        rc = hip_result(launch_score_bf16(g, pl, workspace, scores, st, mid), "bf16 score kernels");
+    else
+        rc = hip_result(launch_score_f32(g, pl, workspace, scores, st, mid), "fp32 score kernels");
+    if (rc) return rc;
+    return hip_result(stage(3, st), "stage event");
 }
 
 int32_t aha_select_topk(const aha_params *p, const float *scores, int32_t *idx, void *workspace,
@@ -262,6 +274,20 @@ int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_ne
     g.budget = p->budget; g.recent = p->recent; g.slots = cache_slots; g.logical_pos = logical_pos;
     g.scale_mode = p->scale_mode; g.fixed_scale = p->fixed_scale; g.lambda_floor = p->lambda_floor;
     return hip_result(launch_decode(g, p->dtype, (hipStream_t)stream), "decode kernel");
+}
+
+int32_t aha_profile_events(void *const *events, int32_t count) {
+    if (count == 0 && !events) {
+        g_stage_on = false;
+        return AHA_OK;
+    }
+    if (count != 4 || !events) return fail(AHA_ERR_INVALID_ARG, "events must be NULL/0 or 4 handles");
+    for (int i = 0; i < 4; ++i) {
+        if (!events[i]) return fail(AHA_ERR_INVALID_ARG, "events[%d] is null", i);
+        g_stage_ev[i] = (hipEvent_t)events[i];
+    }
+    g_stage_on = true;
+    return AHA_OK;
 }
 
 const char *aha_last_error(void) { return g_err; }

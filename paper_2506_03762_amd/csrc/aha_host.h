@@ -43,11 +43,12 @@ constexpr int kP2Keys = 256;      // keys per pass-2 workgroup (4 waves x 64)
 hipError_t launch_value_prior(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
                               hipStream_t st);
 // score_f32.hip
+// `mid`, when not null, is recorded between the two passes.
 hipError_t launch_score_f32(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
-                            float *scores, hipStream_t st);
+                            float *scores, hipStream_t st, hipEvent_t mid);
 // score_bf16.hip
 hipError_t launch_score_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
-                             float *scores, hipStream_t st);
+                             float *scores, hipStream_t st, hipEvent_t mid);
 // topk.hip
 hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent,
                        int32_t *idx, hipStream_t st);

@@ -344,7 +344,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
 // ---------------------------------------------------------------- launch --
 template <int D, int NB>
 static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
-                           hipStream_t st) {
+                           hipStream_t st, hipEvent_t mid) {
     using S = TileSmem<D, NB>;
     char *w = (char *)ws;
     float2 *partial = (float2 *)(w + pl.off_partial);
@@ -366,6 +366,7 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     dim3 g1(pl.nchunks, pl.n_qtiles, pl.Z);
     hipLaunchKernelGGL((bf16_pass1_kernel<D, NB>), g1, dim3(256), S::bytes, st, g, pl.n_qtiles,
                        pl.chunk_keys, pl.nchunks, partial, counters, rowL);
+    if (mid) (void)hipEventRecord(mid, st);
     dim3 g2((g.n + kWgKeys - 1) / kWgKeys, pl.Z);
     hipLaunchKernelGGL((bf16_pass2_kernel<D, NB>), g2, dim3(256), S::bytes, st, g, pl.n_qtiles,
                        rowL, gamma, gbm, pl.n_vtiles, scores);
@@ -374,18 +375,19 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
 
 template <int D>
 static hipError_t launch_d(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
-                           hipStream_t st) {
+                           hipStream_t st, hipEvent_t mid) {
     switch (pl.NB) {
-        case 1: return launch_t<D, 1>(g, pl, ws, scores, st);
-        case 2: return launch_t<D, 2>(g, pl, ws, scores, st);
-        case 4: return launch_t<D, 4>(g, pl, ws, scores, st);
-        default: return launch_t<D, 8>(g, pl, ws, scores, st);
+        case 1: return launch_t<D, 1>(g, pl, ws, scores, st, mid);
+        case 2: return launch_t<D, 2>(g, pl, ws, scores, st, mid);
+        case 4: return launch_t<D, 4>(g, pl, ws, scores, st, mid);
+        default: return launch_t<D, 8>(g, pl, ws, scores, st, mid);
     }
 }
 
 hipError_t launch_score_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
-                             hipStream_t st) {
-    return g.d == 64 ? launch_d<64>(g, pl, ws, scores, st) : launch_d<128>(g, pl, ws, scores, st);
+                             hipStream_t st, hipEvent_t mid) {
+    return g.d == 64 ? launch_d<64>(g, pl, ws, scores, st, mid)
+                     : launch_d<128>(g, pl, ws, scores, st, mid);
 }
 
 }  // namespace aha
