@@ -122,18 +122,22 @@ static PrefillPlan plan_prefill(const aha_params *p) {
         // pass-1 key chunks: enough workgroups to fill 256 CUs a few times over,
         // chunks a multiple of the 256 keys a workgroup sweeps per step
         const int64_t tiles = (int64_t)pl.Z * pl.n_qtiles;
-        int64_t want = (1024 + tiles - 1) / tiles;  // chunks per tile
+        int64_t want = (512 + tiles - 1) / tiles;  // chunks per tile
         if (want < 1) want = 1;
         int64_t ck = ((n + want - 1) / want + kP2Keys - 1) / kP2Keys * kP2Keys;
         if (ck < kP2Keys) ck = kP2Keys;
         pl.chunk_keys = (int)ck;
         pl.nchunks = (int)((n + ck - 1) / ck);
+        // pass 2 re-reads the query tiles per key step, so it takes several key
+        // steps per workgroup only when one tile holds all observed rows
+        pl.p2_keys = pl.n_qtiles == 1 ? pl.chunk_keys : kP2Keys;
     } else {
         pl.NB = 0;
         pl.qtile = 1;
         pl.n_qtiles = 1;
         pl.chunk_keys = n;
         pl.nchunks = 1;
+        pl.p2_keys = kP2Keys;
     }
     size_t off = 0;
     pl.off_counters = off;
@@ -148,6 +152,8 @@ static PrefillPlan plan_prefill(const aha_params *p) {
     off = align_up(off + sizeof(float) * (size_t)pl.Z * n, 256);
     pl.off_gblockmax = off;
     off = align_up(off + sizeof(float) * (size_t)pl.Z * pl.n_vtiles, 256);
+    pl.off_lam = off;  // log2-domain softmax scale of each window row
+    off = align_up(off + sizeof(float) * (size_t)p->window, 256);
     pl.bytes = off;
     return pl;
 }

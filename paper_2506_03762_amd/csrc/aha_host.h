@@ -31,8 +31,9 @@ struct PrefillPlan {
     int n_qtiles;    // query tiles per problem
     int chunk_keys;  // keys per pass-1 workgroup
     int nchunks;     // pass-1 key chunks per (problem, query tile)
+    int p2_keys;     // keys per pass-2 workgroup (a multiple of kP2Keys)
     int n_vtiles;    // value-prior tiles per problem
-    size_t off_counters, off_rowL, off_partial, off_gamma, off_gblockmax;
+    size_t off_counters, off_rowL, off_partial, off_gamma, off_gblockmax, off_lam;
     size_t bytes;
 };
 

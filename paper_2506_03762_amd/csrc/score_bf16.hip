@@ -34,14 +34,17 @@ struct TileSmem {
     static constexpr int LD = D + 8;  // padded row, 16-byte aligned, conflict-free b128 reads
     static constexpr int ROWS = NB * 32;
     static constexpr size_t q_bytes = (size_t)ROWS * LD * 2;
-    static constexpr size_t bytes = q_bytes + ROWS * 4 * 3;
+    // query tile, then per row: scale, position, log-sum-exp; then per block: max / min position
+    static constexpr size_t bytes = q_bytes + ROWS * 4 * 3 + NB * 4 * 2;
 };
 
 // Query tile -> LDS: rows rho0 .. rho0+ROWS of the KV head's flattened query
-// rows (zero beyond R), and per row the log2-domain scale and the position.
+// rows (zero beyond R), per row the log2-domain scale and the position, and per
+// 32-row block the largest and smallest position.
 template <int D, int NB>
 __device__ __forceinline__ void load_q_tile(const ScoreGeom &g, const RowMap &rm, int b, int h,
-                                            int rho0, __bf16 *sQ, float *sLam, int *sPos) {
+                                            int rho0, const float *lam_tab, __bf16 *sQ,
+                                            float *sLam, int *sPos, int *sBlk) {
     using S = TileSmem<D, NB>;
     constexpr int CPR = D / 8;  // 16-byte chunks per row
     const int tid = threadIdx.x;
@@ -49,19 +52,23 @@ __device__ __forceinline__ void load_q_tile(const ScoreGeom &g, const RowMap &rm
         const int rr = t / CPR, c = t % CPR, rho = rho0 + rr;
         u32x4 w = {0u, 0u, 0u, 0u};
         if (rho < g.R) {
-            const int hq = h * g.G + rm.head(rho);
-            const __bf16 *src = (const __bf16 *)g.q + b * g.qs[0] + hq * g.qs[1] +
-                                (int64_t)rm.pos(rho) * g.qs[2] + c * 8;
+            const int gi = rho / g.r, ii = rho - gi * g.r;
+            const __bf16 *src = (const __bf16 *)g.q + b * g.qs[0] + (h * g.G + gi) * g.qs[1] +
+                                (int64_t)(g.n - g.r + ii) * g.qs[2] + c * 8;
             w = *(const u32x4 *)src;
         }
         *(u32x4 *)(sQ + rr * S::LD + c * 8) = w;
     }
     for (int rr = tid; rr < S::ROWS; rr += 256) {
-        const int rho = rho0 + rr, i = rm.pos(rho);
-        sPos[rr] = i;
-        sLam[rr] = rho < g.R ? row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor, i + 1,
-                                              g.budget, g.d)
-                             : 0.f;
+        const int rho = rho0 + rr;
+        const bool ok = rho < g.R;
+        const int ii = ok ? rho % g.r : 0;
+        sPos[rr] = ok ? g.n - g.r + ii : -1;
+        sLam[rr] = ok ? lam_tab[ii] : 0.f;
+    }
+    if (tid < NB) {
+        sBlk[tid] = rm.max_pos(rho0 + tid * 32, rho0 + tid * 32 + 32);
+        sBlk[NB + tid] = rm.min_pos(rho0 + tid * 32, rho0 + tid * 32 + 32);
     }
 }
 
@@ -103,10 +110,57 @@ __device__ __forceinline__ int acc_key(int kb, int mb, int v, int lane) {
     return kb + mb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
 }
 
+// Online max / sum-of-exp2 of one 64 x 32 block for this lane's query column.
+// The scale is non-negative, so the maximum of the scaled logits is the scale
+// times the maximum raw dot.
+template <bool MASK>
+__device__ __forceinline__ void stats_update(const f32x16 (&acc)[kMB], float lam, int pos, int kb,
+                                             int lane, float &m, float &s) {
+    float amax = -INFINITY;
+#pragma unroll
+    for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float x = acc[mb][v];
+            if (MASK && acc_key(kb, mb, v, lane) > pos) x = -INFINITY;
+            amax = fmaxf(amax, x);
+        }
+    const float tmax = amax == -INFINITY ? -INFINITY : amax * lam;
+    const float mn = fmaxf(m, tmax);
+    const float mref = mn == -INFINITY ? 0.f : mn;
+    float sum = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float e = fast_exp2(fmaf(acc[mb][v], lam, -mref));
+            if (MASK && acc_key(kb, mb, v, lane) > pos) e = 0.f;
+            sum += e;
+        }
+    s = s * fast_exp2(m - mref) + sum;
+    m = mn;
+}
+
+template <bool MASK>
+__device__ __forceinline__ void colsum_update(const f32x16 (&acc)[kMB], float lam, float L,
+                                              int pos, int kb, int lane, f32x16 (&col)[kMB]) {
+#pragma unroll
+    for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float p = fast_exp2(fmaf(acc[mb][v], lam, -L));
+            if (MASK && acc_key(kb, mb, v, lane) > pos) p = 0.f;
+            col[mb][v] += p;
+        }
+}
+
+__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
 // ---------------------------------------------------------------- pass 1 --
 template <int D, int NB>
 __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles,
                                                             int chunk_keys, int nchunks,
+                                                            const float *lam_tab,
                                                             float2 *partial, int *counters,
                                                             float *rowL) {
     using S = TileSmem<D, NB>;
@@ -114,6 +168,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
     __bf16 *sQ = (__bf16 *)smem;
     float *sLam = (float *)(smem + S::q_bytes);
     int *sPos = (int *)(sLam + S::ROWS);
+    int *sBlk = sPos + 2 * S::ROWS;
     float2 *sRed = (float2 *)smem;  // reuses the query tile after the main loop
     __shared__ int s_last;
 
@@ -124,15 +179,17 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
     const int rho0 = qt * S::ROWS;
     const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
 
-    load_q_tile<D, NB>(g, rm, b, h, rho0, sQ, sLam, sPos);
+    load_q_tile<D, NB>(g, rm, b, h, rho0, lam_tab, sQ, sLam, sPos, sBlk);
     __syncthreads();
 
     float lam[NB], m[NB], s[NB];
-    int pos[NB];
+    int pos[NB], bmax[NB], bmin[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         lam[nb] = sLam[nb * 32 + (lane & 31)];
         pos[nb] = sPos[nb * 32 + (lane & 31)];
+        bmax[nb] = uniform(sBlk[nb]);
+        bmin[nb] = uniform(sBlk[NB + nb]);
         m[nb] = -INFINITY;
         s[nb] = 0.f;
     }
@@ -144,30 +201,13 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
         load_a<D>(kbase, g.ks[2], kb, g.n, lane, a);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            const int blo = rho0 + nb * 32;
-            if (rm.max_pos(blo, blo + 32) < kb) continue;  // nothing of this block sees these keys
+            if (bmax[nb] < kb) continue;  // nothing of this block sees these keys
             f32x16 acc[kMB];
             mma_block<D, NB>(a, sQ, nb, lane, acc);
-            const bool need_mask = kb + kWaveKeys - 1 > rm.min_pos(blo, blo + 32);
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int mb = 0; mb < kMB; ++mb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    float t = acc[mb][v] * lam[nb];
-                    if (need_mask && acc_key(kb, mb, v, lane) > pos[nb]) t = -INFINITY;
-                    acc[mb][v] = t;
-                    tmax = fmaxf(tmax, t);
-                }
-            const float mn = fmaxf(m[nb], tmax);
-            const float mref = mn == -INFINITY ? 0.f : mn;
-            float sum = 0.f;
-#pragma unroll
-            for (int mb = 0; mb < kMB; ++mb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) sum += fast_exp2(acc[mb][v] - mref);
-            s[nb] = s[nb] * fast_exp2(m[nb] - mref) + sum;
-            m[nb] = mn;
+            if (kb + kWaveKeys - 1 > bmin[nb])
+                stats_update<true>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb]);
+            else
+                stats_update<false>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb]);
         }
     }
 
@@ -209,20 +249,38 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
     }
     __syncthreads();
     if (!s_last) return;
-    __threadfence();
-    if (tid < S::ROWS) {
-        float M = -INFINITY, sum = 0.f;
-        for (int c = 0; c < nchunks; ++c) {
-            const float *e = (const float *)&my_partial[(int64_t)c * S::ROWS + tid];
-            const float em = load_agent(e), es = load_agent(e + 1);
-            const float mn = fmaxf(M, em);
-            const float mref = mn == -INFINITY ? 0.f : mn;
-            sum = sum * fast_exp2(M - mref) + es * fast_exp2(em - mref);
-            M = mn;
-        }
-        rowL[(int64_t)(z * n_qtiles + qt) * S::ROWS + tid] =
-            (rho0 + tid < g.R) ? M + log2f(sum) : INFINITY;
+    __threadfence();  // acquire: the other workgroups' partials are visible from here on
+    // all 256 threads: thread t folds chunks t / ROWS, t / ROWS + 256 / ROWS, ... of row t % ROWS
+    constexpr int TPR = 256 / S::ROWS;  // threads per row
+    const int row = tid % S::ROWS, part = tid / S::ROWS;
+    float M = -INFINITY, sum = 0.f;
+    const float *src = (const float *)(my_partial + row);
+#pragma unroll 4
+    for (int c = part; c < nchunks; c += TPR) {
+        const float em = load_agent(src + (int64_t)c * S::ROWS * 2);
+        const float es = load_agent(src + (int64_t)c * S::ROWS * 2 + 1);
+        const float mn = fmaxf(M, em);
+        const float mref = mn == -INFINITY ? 0.f : mn;
+        sum = sum * fast_exp2(M - mref) + es * fast_exp2(em - mref);
+        M = mn;
     }
+    if (TPR > 1) {
+        sRed[part * S::ROWS + row] = make_float2(M, sum);
+        __syncthreads();
+        if (part == 0) {
+#pragma unroll
+            for (int t = 1; t < TPR; ++t) {
+                const float2 e = sRed[t * S::ROWS + row];
+                const float mn = fmaxf(M, e.x);
+                const float mref = mn == -INFINITY ? 0.f : mn;
+                sum = sum * fast_exp2(M - mref) + e.y * fast_exp2(e.x - mref);
+                M = mn;
+            }
+        }
+    }
+    if (part == 0)
+        rowL[(int64_t)(z * n_qtiles + qt) * S::ROWS + row] =
+            (rho0 + row < g.R) ? M + log2f(sum) : INFINITY;
 }
 
 // ---------------------------------------------------------------- pass 2 --
@@ -258,6 +316,7 @@ __device__ __forceinline__ float fold16_over32(const f32x16 &x, int lane) {
 
 template <int D, int NB>
 __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_qtiles,
+                                                            int wg_keys, const float *lam_tab,
                                                             const float *rowL,
                                                             const float *gamma,
                                                             const float *gblockmax,
@@ -268,6 +327,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     float *sLam = (float *)(smem + S::q_bytes);
     int *sPos = (int *)(sLam + S::ROWS);
     float *sL = (float *)(sPos + S::ROWS);
+    int *sBlk = (int *)(sL + S::ROWS);
     __shared__ float s_gmax[4];
 
     const int z = blockIdx.y;
@@ -275,11 +335,6 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const RowMap rm{g.n, g.r, g.R};
     const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
-    const int kb0 = blockIdx.x * kWgKeys;
-    const int kb = kb0 + wave * kWaveKeys;
-
-    bf16x8 a[kMB][D / 16];
-    load_a<D>(kbase, g.ks[2], kb, g.n, lane, a);
 
     if (g.value_prior) {
         float gm = 0.f;
@@ -287,56 +342,59 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
         gm = wave_max(gm);
         if (lane == 0) s_gmax[wave] = gm;
     }
+    int loaded_qt = -1;
+    const int key_begin = blockIdx.x * wg_keys;
+    const int key_end = min(g.n, key_begin + wg_keys);
+    for (int kb0 = key_begin; kb0 < key_end; kb0 += kWgKeys) {
+        const int kb = kb0 + wave * kWaveKeys;
+        bf16x8 a[kMB][D / 16];
+        load_a<D>(kbase, g.ks[2], kb, g.n, lane, a);
+        f32x16 col[kMB];
+#pragma unroll
+        for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) col[mb][v] = 0.f;
 
-    f32x16 col[kMB];
+        for (int qt = 0; qt < n_qtiles; ++qt) {
+            const int rho0 = qt * S::ROWS;
+            if (rm.max_pos(rho0, rho0 + S::ROWS) < kb0) continue;  // workgroup-uniform
+            if (qt != loaded_qt) {
+                __syncthreads();
+                load_q_tile<D, NB>(g, rm, b, h, rho0, lam_tab, sQ, sLam, sPos, sBlk);
+                for (int rr = tid; rr < S::ROWS; rr += 256)
+                    sL[rr] = rowL[(int64_t)(z * n_qtiles + qt) * S::ROWS + rr];
+                __syncthreads();
+                loaded_qt = qt;
+            }
+            if (kb >= g.n) continue;  // wave-uniform; the barriers above were reached
 #pragma unroll
-    for (int mb = 0; mb < kMB; ++mb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) col[mb][v] = 0.f;
-
-    for (int qt = 0; qt < n_qtiles; ++qt) {
-        const int rho0 = qt * S::ROWS;
-        if (rm.max_pos(rho0, rho0 + S::ROWS) < kb0) continue;  // workgroup-uniform
-        __syncthreads();
-        load_q_tile<D, NB>(g, rm, b, h, rho0, sQ, sLam, sPos);
-        for (int rr = tid; rr < S::ROWS; rr += 256)
-            sL[rr] = rowL[(int64_t)(z * n_qtiles + qt) * S::ROWS + rr];
-        __syncthreads();
-        if (kb >= g.n) continue;  // wave-uniform; barriers above are still reached
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int blo = rho0 + nb * 32;
-            if (rm.max_pos(blo, blo + 32) < kb) continue;
-            f32x16 acc[kMB];
-            mma_block<D, NB>(a, sQ, nb, lane, acc);
-            const float lam = sLam[nb * 32 + (lane & 31)];
-            const float L = sL[nb * 32 + (lane & 31)];
-            const int pos = sPos[nb * 32 + (lane & 31)];
-            const bool need_mask = kb + kWaveKeys - 1 > rm.min_pos(blo, blo + 32);
-#pragma unroll
-            for (int mb = 0; mb < kMB; ++mb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    float p = fast_exp2(fmaf(acc[mb][v], lam, -L));
-                    if (need_mask && acc_key(kb, mb, v, lane) > pos) p = 0.f;
-                    col[mb][v] += p;
-                }
+            for (int nb = 0; nb < NB; ++nb) {
+                if (uniform(sBlk[nb]) < kb) continue;
+                f32x16 acc[kMB];
+                mma_block<D, NB>(a, sQ, nb, lane, acc);
+                const float lam = sLam[nb * 32 + (lane & 31)];
+                const float L = sL[nb * 32 + (lane & 31)];
+                const int pos = sPos[nb * 32 + (lane & 31)];
+                if (kb + kWaveKeys - 1 > uniform(sBlk[NB + nb]))
+                    colsum_update<true>(acc, lam, L, pos, kb, lane, col);
+                else
+                    colsum_update<false>(acc, lam, L, pos, kb, lane, col);
+            }
         }
-    }
-    __syncthreads();
-    float ginv = 1.f;
-    if (g.value_prior)
-        ginv = 1.f / fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3]));
+        float ginv = 1.f;
+        if (g.value_prior)  // s_gmax was published by the barrier of the first tile load
+            ginv = 1.f / fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3]));
 #pragma unroll
-    for (int mb = 0; mb < kMB; ++mb) {
-        const float tot = fold16_over32(col[mb], lane);
-        const int v = ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2 +
-                      ((lane >> 1) & 1);
-        const int j = acc_key(kb, mb, v, lane);
-        if ((lane & 1) == 0 && j < g.n) {
-            float out = tot;
-            if (g.value_prior) out = tot * (gamma[(int64_t)z * g.n + j] * ginv);
-            scores[(int64_t)z * g.n + j] = out;
+        for (int mb = 0; mb < kMB; ++mb) {
+            const float tot = fold16_over32(col[mb], lane);
+            const int v = ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2 +
+                          ((lane >> 1) & 1);
+            const int j = acc_key(kb, mb, v, lane);
+            if ((lane & 1) == 0 && j < g.n) {
+                float out = tot;
+                if (g.value_prior) out = tot * (gamma[(int64_t)z * g.n + j] * ginv);
+                scores[(int64_t)z * g.n + j] = out;
+            }
         }
     }
 }
@@ -352,6 +410,7 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     float *rowL = (float *)(w + pl.off_rowL);
     const float *gamma = (const float *)(w + pl.off_gamma);
     const float *gbm = (const float *)(w + pl.off_gblockmax);
+    const float *lam_tab = (const float *)(w + pl.off_lam);
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void *)bf16_pass1_kernel<D, NB>,
@@ -365,11 +424,11 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     }
     dim3 g1(pl.nchunks, pl.n_qtiles, pl.Z);
     hipLaunchKernelGGL((bf16_pass1_kernel<D, NB>), g1, dim3(256), S::bytes, st, g, pl.n_qtiles,
-                       pl.chunk_keys, pl.nchunks, partial, counters, rowL);
+                       pl.chunk_keys, pl.nchunks, lam_tab, partial, counters, rowL);
     if (mid) (void)hipEventRecord(mid, st);
-    dim3 g2((g.n + kWgKeys - 1) / kWgKeys, pl.Z);
+    dim3 g2((g.n + pl.p2_keys - 1) / pl.p2_keys, pl.Z);
     hipLaunchKernelGGL((bf16_pass2_kernel<D, NB>), g2, dim3(256), S::bytes, st, g, pl.n_qtiles,
-                       rowL, gamma, gbm, pl.n_vtiles, scores);
+                       pl.p2_keys, lam_tab, rowL, gamma, gbm, pl.n_vtiles, scores);
     return hipGetLastError();
 }
 

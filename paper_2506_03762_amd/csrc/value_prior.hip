@@ -3,8 +3,9 @@
 // maxima of gamma from which the consumers form gamma / max(gamma).
 //
 // HBM-bound: V is read exactly once (plus (pool-1)/2 halo rows per tile).
-// The same launch clears the ticket counters that the score pass uses, so no
-// separate fill is needed.
+// The same launch clears the ticket counters that the score pass uses and
+// tabulates the softmax scale of every window row (evaluated in double), so no
+// separate fill or set-up launch is needed.
 #include "aha_dev.h"
 #include "aha_host.h"
 
@@ -15,12 +16,19 @@ namespace aha {
 template <int ESIZE>
 __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, float *gamma,
                                                      float *gblockmax, int *counters,
-                                                     int counters_per_z) {
+                                                     int counters_per_z, float *lam_tab) {
     const int z = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
     if (tile == 0) {
         for (int t = tid; t < counters_per_z; t += 256) counters[z * counters_per_z + t] = 0;
     }
-    if (!g.value_prior) return;
+    if (z == 0) {
+        // softmax scale of window row ii (token position n - r + ii, c = position + 1 keys)
+        const int ii = tile * 256 + tid;
+        if (ii < g.r)
+            lam_tab[ii] = row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor,
+                                         g.n - g.r + ii + 1, g.budget, g.d);
+    }
+    if (!g.value_prior || tile >= n_vtiles) return;
 
     __shared__ float s_nu[kVTileRows + 256];
     __shared__ float s_max[4];
@@ -79,13 +87,16 @@ hipError_t launch_value_prior(const ScoreGeom &g, const PrefillPlan &pl, void *w
     float *gamma = (float *)(w + pl.off_gamma);
     float *gbm = (float *)(w + pl.off_gblockmax);
     int *counters = (int *)(w + pl.off_counters);
-    dim3 grid(g.value_prior ? pl.n_vtiles : 1, pl.Z);
+    float *lam_tab = (float *)(w + pl.off_lam);
+    const int lam_blocks = (g.r + 255) / 256;
+    const int vt = g.value_prior ? pl.n_vtiles : 1;
+    dim3 grid(vt > lam_blocks ? vt : lam_blocks, pl.Z);
     if (g.dtype == AHA_BF16)
         hipLaunchKernelGGL(vprior_kernel<2>, grid, dim3(256), 0, st, g, pl.n_vtiles, gamma, gbm,
-                           counters, pl.n_qtiles);
+                           counters, pl.n_qtiles, lam_tab);
     else
         hipLaunchKernelGGL(vprior_kernel<4>, grid, dim3(256), 0, st, g, pl.n_vtiles, gamma, gbm,
-                           counters, pl.n_qtiles);
+                           counters, pl.n_qtiles, lam_tab);
     return hipGetLastError();
 }
 
