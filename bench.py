@@ -79,7 +79,7 @@ def main():
         B.aha_compact_kv(p, k, v, scores, idx, cache.k, cache.v, cache.scores, cache.pos,
                          cache.free_slot)
         B.aha_decode_step(p, qn, kn, vn, cache.k, cache.v, cache.scores, cache.pos,
-                          cache.free_slot, n + 1, out)
+                          cache.free_slot, n + 1, out, ws)
 
     for _ in range(W_STEPS):
         step()
@@ -106,7 +106,7 @@ def main():
         e1 = ev(); B.aha_compact_kv(p, k, v, scores, idx, cache.k, cache.v, cache.scores,
                                     cache.pos, cache.free_slot)
         e2 = ev(); B.aha_decode_step(p, qn, kn, vn, cache.k, cache.v, cache.scores, cache.pos,
-                                     cache.free_slot, n + 1, out)
+                                     cache.free_slot, n + 1, out, ws)
         e3 = ev()
         stage_sets.append(st)
         call_sets.append((e0, e1, e2, e3))
@@ -203,7 +203,7 @@ def bench_decode_c4(torch, B, synth, H, steps):
             c = caches[t % ncopies] if rotate else caches[0]
             e0 = torch.cuda.Event(enable_timing=True); e0.record()
             B.aha_decode_step(p, qs[t], ks[t], vs[t], c.k, c.v, c.scores, c.pos, c.free_slot,
-                              n + 1 + (t // ncopies if rotate else t), out)
+                              n + 1 + (t // ncopies if rotate else t), out, ws)
             e1 = torch.cuda.Event(enable_timing=True); e1.record()
             evs.append((e0, e1))
         torch.cuda.synchronize()

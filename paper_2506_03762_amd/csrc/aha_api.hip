@@ -3,6 +3,7 @@
 // enqueued, so the error paths need no GPU.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 
 #include "aha_host.h"
 
@@ -122,7 +123,8 @@ static PrefillPlan plan_prefill(const aha_params *p) {
         // pass-1 key chunks: enough workgroups to fill 256 CUs a few times over,
         // chunks a multiple of the 256 keys a workgroup sweeps per step
         const int64_t tiles = (int64_t)pl.Z * pl.n_qtiles;
-        int64_t want = (512 + tiles - 1) / tiles;  // chunks per tile
+        static const int target_wgs = getenv("AHA_TUNE_WGS") ? atoi(getenv("AHA_TUNE_WGS")) : 512;
+        int64_t want = (target_wgs + tiles - 1) / tiles;  // chunks per tile
         if (want < 1) want = 1;
         int64_t ck = ((n + want - 1) / want + kP2Keys - 1) / kP2Keys * kP2Keys;
         if (ck < kP2Keys) ck = kP2Keys;
@@ -140,11 +142,9 @@ static PrefillPlan plan_prefill(const aha_params *p) {
         pl.p2_keys = kP2Keys;
     }
     size_t off = 0;
-    pl.off_counters = off;
-    off = align_up(off + sizeof(int) * (size_t)pl.Z * pl.n_qtiles, 256);
-    pl.off_rowL = off;
+    pl.off_rowL = off;  // fp32 path: log-sum-exp of every observed row
     const size_t rows = p->dtype == AHA_BF16 ? (size_t)pl.n_qtiles * pl.qtile : (size_t)R;
-    off = align_up(off + sizeof(float) * (size_t)pl.Z * rows, 256);
+    if (p->dtype != AHA_BF16) off = align_up(off + sizeof(float) * (size_t)pl.Z * rows, 256);
     pl.off_partial = off;
     if (p->dtype == AHA_BF16)
         off = align_up(off + sizeof(float) * 2 * (size_t)pl.Z * rows * pl.nchunks, 256);
@@ -155,6 +155,28 @@ static PrefillPlan plan_prefill(const aha_params *p) {
     pl.off_lam = off;  // log2-domain softmax scale of each window row
     off = align_up(off + sizeof(float) * (size_t)p->window, 256);
     pl.bytes = off;
+    return pl;
+}
+
+// Decode: split a head's slots over workgroups when there are too few heads to fill the GPU.
+static DecodePlan plan_decode(const aha_params *p) {
+    DecodePlan pl{};
+    const int Z = p->batch * p->n_kv_heads, G = p->n_q_heads / p->n_kv_heads;
+    const int live = p->budget + 1;
+    int nsplit = 1;
+    if (Z < 128) {
+        nsplit = (256 + Z - 1) / Z;
+        const int max_by_size = (live + 63) / 64;  // at least 64 slots per workgroup
+        if (nsplit > max_by_size) nsplit = max_by_size;
+        if (nsplit > 64) nsplit = 64;
+    }
+    pl.nsplit = nsplit < 1 ? 1 : nsplit;
+    pl.sps = (live + pl.nsplit - 1) / pl.nsplit;
+    pl.nsplit = (live + pl.sps - 1) / pl.sps;
+    if (pl.nsplit > 1) {
+        pl.off_part = align_up(sizeof(float) * (size_t)Z * G * live, 256);
+        pl.bytes = align_up(pl.off_part + sizeof(float) * (size_t)Z * pl.nsplit * G * (p->head_dim + 2), 256);
+    }
     return pl;
 }
 
@@ -182,7 +204,8 @@ int32_t aha_workspace_bytes(const aha_params *p, size_t *out_bytes) {
     if (!out_bytes) return fail(AHA_ERR_INVALID_ARG, "out_bytes is null");
     int32_t rc = check_prefill(p, false);
     if (rc) return rc;
-    *out_bytes = plan_prefill(p).bytes;
+    const size_t a = plan_prefill(p).bytes, d = plan_decode(p).bytes;
+    *out_bytes = a > d ? a : d;
     return AHA_OK;
 }
 
@@ -249,8 +272,6 @@ int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_ne
                         int32_t *pos_c, int32_t *free_slot, int32_t cache_slots,
                         int32_t logical_pos, void *out, void *workspace, size_t workspace_bytes,
                         void *stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     int32_t rc = check_common(p);
     if (rc) return rc;
     if ((rc = check_ptr("q_new", q_new, 16)) || (rc = check_ptr("k_new", k_new, 16)) ||
@@ -268,18 +289,21 @@ int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_ne
     const int G = p->n_q_heads / p->n_kv_heads;
     if (G > 8)
         return fail(AHA_ERR_UNSUPPORTED, "decode is built for query groups of up to 8 heads, not %d", G);
+    const DecodePlan dpl = plan_decode(p);
     const int live = p->budget + 1;
     const size_t w_floats = (size_t)(G * live > 16 * G * p->head_dim ? G * live : 16 * G * p->head_dim);
-    if ((w_floats + (size_t)G * live) * 4 > 150 * 1024)
+    if (dpl.nsplit == 1 && (w_floats + (size_t)G * live) * 4 > 150 * 1024)
         return fail(AHA_ERR_UNSUPPORTED,
                     "decode keeps group * (budget + 1) dots in LDS; %d * %d does not fit", G, live);
+    if ((rc = check_ws(workspace, workspace_bytes, dpl.bytes))) return rc;
     DecodeGeom g{};
     g.q = q_new; g.k_new = k_new; g.v_new = v_new; g.kc = k_cache; g.vc = v_cache; g.out = out;
     g.fc = scores_c; g.pos = pos_c; g.free_slot = free_slot;
     g.batch = p->batch; g.Hq = p->n_q_heads; g.Hkv = p->n_kv_heads; g.G = G; g.d = p->head_dim;
     g.budget = p->budget; g.recent = p->recent; g.slots = cache_slots; g.logical_pos = logical_pos;
     g.scale_mode = p->scale_mode; g.fixed_scale = p->fixed_scale; g.lambda_floor = p->lambda_floor;
-    return hip_result(launch_decode(g, p->dtype, (hipStream_t)stream), "decode kernel");
+    return hip_result(launch_decode(g, dpl, workspace, p->dtype, (hipStream_t)stream),
+                      "decode kernel");
 }
 
 int32_t aha_profile_events(void *const *events, int32_t count) {

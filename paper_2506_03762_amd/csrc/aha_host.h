@@ -33,7 +33,7 @@ struct PrefillPlan {
     int nchunks;     // pass-1 key chunks per (problem, query tile)
     int p2_keys;     // keys per pass-2 workgroup (a multiple of kP2Keys)
     int n_vtiles;    // value-prior tiles per problem
-    size_t off_counters, off_rowL, off_partial, off_gamma, off_gblockmax, off_lam;
+    size_t off_rowL, off_partial, off_gamma, off_gblockmax, off_lam;
     size_t bytes;
 };
 
@@ -67,6 +67,15 @@ struct DecodeGeom {
     int scale_mode;
     float fixed_scale, lambda_floor;
 };
-hipError_t launch_decode(const DecodeGeom &g, int dtype, hipStream_t st);
+// With few (batch, KV head) problems the slots of a head are split over nsplit workgroups
+// (two launches, partials in the workspace); otherwise one workgroup handles a head.
+struct DecodePlan {
+    int nsplit;      // 1: single-launch path
+    int sps;         // slots per split
+    size_t off_part; // partial outputs behind the raw dots
+    size_t bytes;    // workspace bytes (0 when nsplit == 1)
+};
+hipError_t launch_decode(const DecodeGeom &g, const DecodePlan &pl, void *ws, int dtype,
+                         hipStream_t st);
 
 }  // namespace aha

@@ -212,9 +212,258 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     }
 }
 
-template <int ESIZE, int D>
-static hipError_t launch_g(const DecodeGeom &g, hipStream_t st) {
+// ---- few problems: split the slots of a head over several workgroups ----
+// Stage 1, one workgroup per (slot range, batch, KV head): raw dots to the
+// workspace, and the range's share of the attention output relative to the
+// range's own maximum (flash-decoding style partials).
+template <int ESIZE, int D, int G>
+__global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsplit, int sps,
+                                                           float *ws_w, float *ws_part) {
+    constexpr int CH = 16 / ESIZE, LPR = D / CH, RP = 256 / LPR, ROWB = D * ESIZE;
+    extern __shared__ __attribute__((aligned(16))) float dsm[];
+    float *s_p = dsm;                 // [G][sps] dots, then unnormalised probabilities
+    float *s_o = dsm + G * sps;       // [4 waves][G][D]
+    __shared__ float s_red[4][G];
+
+    const int split = blockIdx.x, z = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = z / g.Hkv, h = z % g.Hkv;
     const int live = g.budget + 1;
+    const int fs = g.free_slot[z];
+    const int s0 = split * sps, s1 = min(live, s0 + sps);
+    const int rg = tid / LPR, sub = tid % LPR;
+    char *kcz = (char *)g.kc + (int64_t)z * g.slots * ROWB;
+    char *vcz = (char *)g.vc + (int64_t)z * g.slots * ROWB;
+    const char *knew = (const char *)g.k_new + (int64_t)z * ROWB;
+    const char *vnew = (const char *)g.v_new + (int64_t)z * ROWB;
+
+    float qr[G][CH];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+        const char *qp = (const char *)g.q + ((int64_t)(b * g.Hq + h * G + gi)) * ROWB + sub * 16;
+        unpack<ESIZE>(*(const u32x4 *)qp, qr[gi]);
+    }
+    float mloc[G];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) mloc[gi] = -INFINITY;
+#pragma unroll 4
+    for (int s = s0 + rg; s < s1; s += RP) {
+        const char *src = (s == fs) ? knew : kcz + (int64_t)s * ROWB;
+        const u32x4 kw = *(const u32x4 *)(src + sub * 16);
+        if (s == fs) *(u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16) = kw;
+        float kf[CH];
+        unpack<ESIZE>(kw, kf);
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            float w = 0.f;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) w = fmaf(qr[gi][c], kf[c], w);
+#pragma unroll
+            for (int o = LPR / 2; o > 0; o >>= 1) w += __shfl_xor(w, o);
+            if (sub == 0) {
+                s_p[gi * sps + s - s0] = w;
+                ws_w[((int64_t)z * G + gi) * live + s] = w;
+            }
+            mloc[gi] = fmaxf(mloc[gi], w);
+        }
+    }
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+        const float m = wave_max(mloc[gi]);
+        if (lane == 0) s_red[wave][gi] = m;
+    }
+    __syncthreads();
+    float mx[G];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi)
+        mx[gi] = fmaxf(fmaxf(s_red[0][gi], s_red[1][gi]), fmaxf(s_red[2][gi], s_red[3][gi]));
+    __syncthreads();
+    const float c_out = kLog2e * rsqrtf((float)D);
+    float zo[G];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) zo[gi] = 0.f;
+    for (int s = s0 + tid; s < s1; s += 256) {
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            const float e = exp2f((s_p[gi * sps + s - s0] - mx[gi]) * c_out);
+            s_p[gi * sps + s - s0] = e;
+            zo[gi] += e;
+        }
+    }
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+        const float a = wave_sum(zo[gi]);
+        if (lane == 0) s_red[wave][gi] = a;
+    }
+    __syncthreads();
+    float o[G][CH];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) o[gi][c] = 0.f;
+#pragma unroll 4
+    for (int s = s0 + rg; s < s1; s += RP) {
+        const char *src = (s == fs) ? vnew : vcz + (int64_t)s * ROWB;
+        const u32x4 vw = *(const u32x4 *)(src + sub * 16);
+        if (s == fs) *(u32x4 *)(vcz + (int64_t)s * ROWB + sub * 16) = vw;
+        float vf[CH];
+        unpack<ESIZE>(vw, vf);
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            const float p = s_p[gi * sps + s - s0];
+#pragma unroll
+            for (int c = 0; c < CH; ++c) o[gi][c] = fmaf(p, vf[c], o[gi][c]);
+        }
+    }
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            float v = o[gi][c];
+#pragma unroll
+            for (int off = LPR; off < 64; off <<= 1) v += __shfl_xor(v, off);
+            if (lane < LPR) s_o[(wave * G + gi) * D + sub * CH + c] = v;
+        }
+    __syncthreads();
+    float *part = ws_part + ((int64_t)z * nsplit + split) * G * (D + 2);
+    for (int t = tid; t < G * D; t += 256) {
+        const int gi = t / D, c = t % D;
+        part[gi * (D + 2) + c] = s_o[(0 * G + gi) * D + c] + s_o[(1 * G + gi) * D + c] +
+                                 s_o[(2 * G + gi) * D + c] + s_o[(3 * G + gi) * D + c];
+    }
+    if (tid < G) {
+        part[tid * (D + 2) + D] = mx[tid];
+        part[tid * (D + 2) + D + 1] = s_red[0][tid] + s_red[1][tid] + s_red[2][tid] + s_red[3][tid];
+    }
+}
+
+// Stage 2, one workgroup per (batch, KV head): merge the partial outputs,
+// update the running scores from the stored dots and pick the victim.
+template <int ESIZE, int D, int G>
+__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeGeom g, int nsplit,
+                                                           const float *ws_w,
+                                                           const float *ws_part) {
+    __shared__ float s_mx[G], s_scale[64][G];
+    __shared__ float s_red[4][G];
+    __shared__ unsigned long long s_key[4];
+    __shared__ int s_victim;
+    const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = z / g.Hkv, h = z % g.Hkv;
+    const int live = g.budget + 1;
+    const int fs = g.free_slot[z];
+    float *fcz = g.fc + (int64_t)z * g.slots;
+    int32_t *posz = g.pos + (int64_t)z * g.slots;
+    const float *part = ws_part + (int64_t)z * nsplit * G * (D + 2);
+    const float c_out = kLog2e * rsqrtf((float)D);
+    const float c_sc = row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor, g.logical_pos,
+                                      g.budget, D);
+    if (tid < G) {
+        float m = -INFINITY;
+        for (int sp = 0; sp < nsplit; ++sp) m = fmaxf(m, part[(sp * G + tid) * (D + 2) + D]);
+        s_mx[tid] = m;
+    }
+    __syncthreads();
+    for (int t = tid; t < nsplit * G; t += 256) {
+        const int sp = t / G, gi = t % G;
+        s_scale[sp][gi] = exp2f((part[(sp * G + gi) * (D + 2) + D] - s_mx[gi]) * c_out);
+    }
+    __syncthreads();
+    for (int t = tid; t < G * D; t += 256) {
+        const int gi = t / D, c = t % D;
+        float num = 0.f, den = 0.f;
+        for (int sp = 0; sp < nsplit; ++sp) {
+            const float sc = s_scale[sp][gi];
+            num = fmaf(part[(sp * G + gi) * (D + 2) + c], sc, num);
+            den = fmaf(part[(sp * G + gi) * (D + 2) + D + 1], sc, den);
+        }
+        const float v = num / den;
+        const int64_t oi = ((int64_t)(b * g.Hq + h * G + gi)) * D + c;
+        if constexpr (ESIZE == 2)
+            ((uint16_t *)g.out)[oi] = (uint16_t)f32_to_bf16_rne(v);
+        else
+            ((float *)g.out)[oi] = v;
+    }
+    // score softmax over all live slots, from the stored raw dots
+    float mx[G], zs[G];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) { mx[gi] = s_mx[gi]; zs[gi] = 0.f; }
+    for (int s = tid; s < live; s += 256) {
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi)
+            zs[gi] += exp2f((ws_w[((int64_t)z * G + gi) * live + s] - mx[gi]) * c_sc);
+    }
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+        const float a = wave_sum(zs[gi]);
+        if (lane == 0) s_red[wave][gi] = a;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) zs[gi] = s_red[0][gi] + s_red[1][gi] + s_red[2][gi] + s_red[3][gi];
+    unsigned long long best = ~0ull;
+    int best_slot = -1;
+    for (int s = tid; s < live; s += 256) {
+        float add = 0.f;
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi)
+            add += exp2f((ws_w[((int64_t)z * G + gi) * live + s] - mx[gi]) * c_sc) / zs[gi];
+        const float f = (s == fs ? 0.f : fcz[s]) + add;
+        fcz[s] = f;
+        int ps;
+        if (s == fs) { ps = g.logical_pos - 1; posz[s] = ps; } else { ps = posz[s]; }
+        if (ps < g.logical_pos - g.recent) {
+            const unsigned long long key =
+                ((unsigned long long)__float_as_uint(f) << 32) | (uint32_t)(~ps);
+            if (key < best) { best = key; best_slot = s; }
+        }
+    }
+    unsigned long long wbest = best;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned long long t = __shfl_xor(wbest, o);
+        wbest = t < wbest ? t : wbest;
+    }
+    if (lane == 0) s_key[wave] = wbest;
+    __syncthreads();
+    unsigned long long gbest = s_key[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) gbest = s_key[w] < gbest ? s_key[w] : gbest;
+    if (best_slot >= 0 && best == gbest) s_victim = best_slot;
+    __syncthreads();
+    if (tid == 0) {
+        const int victim = s_victim;
+        posz[victim] = -1;
+        g.free_slot[z] = victim;
+    }
+}
+
+template <int ESIZE, int D>
+static hipError_t launch_g(const DecodeGeom &g, const DecodePlan &pl, void *ws, hipStream_t st) {
+    const int live = g.budget + 1;
+    if (pl.nsplit > 1) {
+        float *ws_w = (float *)ws;
+        float *ws_part = (float *)((char *)ws + pl.off_part);
+        const size_t smem1 = (size_t)(g.G * pl.sps + 4 * g.G * D) * sizeof(float);
+        dim3 g1(pl.nsplit, g.batch * g.Hkv), g2(g.batch * g.Hkv);
+#define AHA_DECS(GG)                                                                             \
+    {                                                                                            \
+        hipLaunchKernelGGL((decode_split_kernel<ESIZE, D, GG>), g1, dim3(256), smem1, st, g,     \
+                           pl.nsplit, pl.sps, ws_w, ws_part);                                    \
+        hipLaunchKernelGGL((decode_merge_kernel<ESIZE, D, GG>), g2, dim3(256), 0, st, g,         \
+                           pl.nsplit, ws_w, ws_part);                                            \
+    }
+        switch (g.G) {
+            case 1: AHA_DECS(1) break;
+            case 2: AHA_DECS(2) break;
+            case 3: AHA_DECS(3) break;
+            case 4: AHA_DECS(4) break;
+            case 5: AHA_DECS(5) break;
+            case 6: AHA_DECS(6) break;
+            case 7: AHA_DECS(7) break;
+            default: AHA_DECS(8) break;
+        }
+#undef AHA_DECS
+        return hipGetLastError();
+    }
     const int w_floats = max(g.G * live, kDecWaves * g.G * D);
     const size_t smem = (size_t)(w_floats + g.G * live) * sizeof(float);
     dim3 grid(g.batch * g.Hkv);
@@ -245,10 +494,11 @@ static hipError_t launch_g(const DecodeGeom &g, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t launch_decode(const DecodeGeom &g, int dtype, hipStream_t st) {
+hipError_t launch_decode(const DecodeGeom &g, const DecodePlan &pl, void *ws, int dtype,
+                         hipStream_t st) {
     if (dtype == AHA_BF16)
-        return g.d == 64 ? launch_g<2, 64>(g, st) : launch_g<2, 128>(g, st);
-    return g.d == 64 ? launch_g<4, 64>(g, st) : launch_g<4, 128>(g, st);
+        return g.d == 64 ? launch_g<2, 64>(g, pl, ws, st) : launch_g<2, 128>(g, pl, ws, st);
+    return g.d == 64 ? launch_g<4, 64>(g, pl, ws, st) : launch_g<4, 128>(g, pl, ws, st);
 }
 
 }  // namespace aha

@@ -116,6 +116,7 @@ __device__ __forceinline__ int acc_key(int kb, int mb, int v, int lane) {
 template <bool MASK>
 __device__ __forceinline__ void stats_update(const f32x16 (&acc)[kMB], float lam, int pos, int kb,
                                              int lane, float &m, float &s) {
+    if (MASK) asm volatile("" ::: "memory");
     float amax = -INFINITY;
 #pragma unroll
     for (int mb = 0; mb < kMB; ++mb)
@@ -144,6 +145,9 @@ __device__ __forceinline__ void stats_update(const f32x16 (&acc)[kMB], float lam
 template <bool MASK>
 __device__ __forceinline__ void colsum_update(const f32x16 (&acc)[kMB], float lam, float L,
                                               int pos, int kb, int lane, f32x16 (&col)[kMB]) {
+    // The empty asm keeps the masked and the unmasked instantiation apart: without it the
+    // compiler merges the two branches and every block pays the per-element compare/select.
+    if (MASK) asm volatile("" ::: "memory");
 #pragma unroll
     for (int mb = 0; mb < kMB; ++mb)
 #pragma unroll
@@ -152,6 +156,7 @@ __device__ __forceinline__ void colsum_update(const f32x16 (&acc)[kMB], float la
             if (MASK && acc_key(kb, mb, v, lane) > pos) p = 0.f;
             col[mb][v] += p;
         }
+    if (MASK) asm volatile("" ::: "memory");
 }
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -161,8 +166,7 @@ template <int D, int NB>
 __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles,
                                                             int chunk_keys, int nchunks,
                                                             const float *lam_tab,
-                                                            float2 *partial, int *counters,
-                                                            float *rowL) {
+                                                            float2 *partial) {
     using S = TileSmem<D, NB>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __bf16 *sQ = (__bf16 *)smem;
@@ -170,7 +174,6 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
     int *sPos = (int *)(sLam + S::ROWS);
     int *sBlk = sPos + 2 * S::ROWS;
     float2 *sRed = (float2 *)smem;  // reuses the query tile after the main loop
-    __shared__ int s_last;
 
     const int chunk = blockIdx.x, qt = blockIdx.y, z = blockIdx.z;
     const int b = z / g.Hkv, h = z % g.Hkv;
@@ -240,54 +243,22 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
         }
         my_partial[(int64_t)chunk * S::ROWS + tid] = make_float2(M, sum);
     }
-    // the last workgroup of this (problem, query tile) folds the chunks
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const int ticket = atomicAdd(&counters[z * n_qtiles + qt], 1);
-        s_last = (ticket == nchunks - 1);
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();  // acquire: the other workgroups' partials are visible from here on
-    // all 256 threads: thread t folds chunks t / ROWS, t / ROWS + 256 / ROWS, ... of row t % ROWS
-    constexpr int TPR = 256 / S::ROWS;  // threads per row
-    const int row = tid % S::ROWS, part = tid / S::ROWS;
-    float M = -INFINITY, sum = 0.f;
-    const float *src = (const float *)(my_partial + row);
-#pragma unroll 4
-    for (int c = part; c < nchunks; c += TPR) {
-        const float em = load_agent(src + (int64_t)c * S::ROWS * 2);
-        const float es = load_agent(src + (int64_t)c * S::ROWS * 2 + 1);
-        const float mn = fmaxf(M, em);
-        const float mref = mn == -INFINITY ? 0.f : mn;
-        sum = sum * fast_exp2(M - mref) + es * fast_exp2(em - mref);
-        M = mn;
-    }
-    if (TPR > 1) {
-        sRed[part * S::ROWS + row] = make_float2(M, sum);
-        __syncthreads();
-        if (part == 0) {
-#pragma unroll
-            for (int t = 1; t < TPR; ++t) {
-                const float2 e = sRed[t * S::ROWS + row];
-                const float mn = fmaxf(M, e.x);
-                const float mref = mn == -INFINITY ? 0.f : mn;
-                sum = sum * fast_exp2(M - mref) + e.y * fast_exp2(e.x - mref);
-                M = mn;
-            }
-        }
-    }
-    if (part == 0)
-        rowL[(int64_t)(z * n_qtiles + qt) * S::ROWS + row] =
-            (rho0 + row < g.R) ? M + log2f(sum) : INFINITY;
 }
 
 // ---------------------------------------------------------------- pass 2 --
 // Sum of 16 per-lane values over the 32 lanes of each half-wave by recursive
 // halving: after the call lane l holds the total of element
 // v = 8*bit4(l) + 4*bit3(l) + 2*bit2(l) + bit1(l)   (both lanes of a pair hold it).
-__device__ __forceinline__ float fold16_over32(const f32x16 &x, int lane) {
+__device__ __forceinline__ float fold16_over32(const f32x16 &xv, int lane) {
+    // The elements go through an opaque move first: otherwise the compiler turns
+    // "lane-dependent choice between two elements" into a dynamically indexed
+    // vector access, which costs a 16-way compare/select chain per element.
+    float x[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        x[t] = xv[t];
+        asm volatile("" : "+v"(x[t]));
+    }
     float a[8], b4[4], c2[2];
     bool hi = lane & 16;
 #pragma unroll
@@ -314,10 +285,31 @@ __device__ __forceinline__ float fold16_over32(const f32x16 &x, int lane) {
     return d;
 }
 
+// Log2-sum-exp2 of one query row from the per-chunk (max, sum) pairs that pass 1 left
+// (16 independent loads in flight per batch).
+__device__ __forceinline__ float fold_chunks(const float2 *src, int stride, int nchunks) {
+    float M = -INFINITY, sum = 0.f;
+    for (int c0 = 0; c0 < nchunks; c0 += 16) {
+        float2 e[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t)
+            e[t] = c0 + t < nchunks ? src[(int64_t)(c0 + t) * stride] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const float mn = fmaxf(M, e[t].x);
+            const float mref = mn == -INFINITY ? 0.f : mn;
+            sum = sum * fast_exp2(M - mref) + e[t].y * fast_exp2(e[t].x - mref);
+            M = mn;
+        }
+    }
+    return M + log2f(sum);
+}
+
 template <int D, int NB>
 __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_qtiles,
-                                                            int wg_keys, const float *lam_tab,
-                                                            const float *rowL,
+                                                            int wg_keys, int nchunks,
+                                                            const float *lam_tab,
+                                                            const float2 *partial,
                                                             const float *gamma,
                                                             const float *gblockmax,
                                                             int n_vtiles, float *scores) {
@@ -362,7 +354,10 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
                 __syncthreads();
                 load_q_tile<D, NB>(g, rm, b, h, rho0, lam_tab, sQ, sLam, sPos, sBlk);
                 for (int rr = tid; rr < S::ROWS; rr += 256)
-                    sL[rr] = rowL[(int64_t)(z * n_qtiles + qt) * S::ROWS + rr];
+                    sL[rr] = rho0 + rr < g.R
+                                 ? fold_chunks(partial + ((int64_t)(z * n_qtiles + qt) * nchunks) * S::ROWS + rr,
+                                               S::ROWS, nchunks)
+                                 : INFINITY;
                 __syncthreads();
                 loaded_qt = qt;
             }
@@ -406,8 +401,6 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     using S = TileSmem<D, NB>;
     char *w = (char *)ws;
     float2 *partial = (float2 *)(w + pl.off_partial);
-    int *counters = (int *)(w + pl.off_counters);
-    float *rowL = (float *)(w + pl.off_rowL);
     const float *gamma = (const float *)(w + pl.off_gamma);
     const float *gbm = (const float *)(w + pl.off_gblockmax);
     const float *lam_tab = (const float *)(w + pl.off_lam);
@@ -424,11 +417,11 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     }
     dim3 g1(pl.nchunks, pl.n_qtiles, pl.Z);
     hipLaunchKernelGGL((bf16_pass1_kernel<D, NB>), g1, dim3(256), S::bytes, st, g, pl.n_qtiles,
-                       pl.chunk_keys, pl.nchunks, lam_tab, partial, counters, rowL);
+                       pl.chunk_keys, pl.nchunks, lam_tab, partial);
     if (mid) (void)hipEventRecord(mid, st);
     dim3 g2((g.n + pl.p2_keys - 1) / pl.p2_keys, pl.Z);
     hipLaunchKernelGGL((bf16_pass2_kernel<D, NB>), g2, dim3(256), S::bytes, st, g, pl.n_qtiles,
-                       pl.p2_keys, lam_tab, rowL, gamma, gbm, pl.n_vtiles, scores);
+                       pl.p2_keys, pl.nchunks, lam_tab, partial, gamma, gbm, pl.n_vtiles, scores);
     return hipGetLastError();
 }
 

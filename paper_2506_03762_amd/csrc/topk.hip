@@ -4,11 +4,14 @@
 // positions.
 //
 // One workgroup of 1024 threads per problem.  Scores become order-preserving
-// 32-bit keys; a radix select (8-bit digits, per-wave LDS histograms) finds the
-// key of the last selected element, starting at the highest bit in which the
-// keys of this problem differ at all, so that the first digit already spreads
-// over the bins.  An ordered compaction (each thread owns a contiguous index
-// range, one block-wide scan) then writes the indices in ascending order.
+// 32-bit keys that stay in registers (each thread owns a contiguous range of
+// token positions); a radix select (8-bit digits, per-wave LDS histograms)
+// finds the key of the last selected element, starting at the highest bit in
+// which the keys of this problem differ at all, so that the first digit
+// already spreads over the bins.  An ordered compaction (one block-wide scan)
+// then writes the indices in ascending order.  Sequences too long for the
+// register file (more than 64 keys per thread) re-read the scores from memory
+// in every round instead.
 #include "aha_dev.h"
 #include "aha_host.h"
 
@@ -22,6 +25,9 @@ __device__ __forceinline__ uint32_t order_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// ITEMS > 0: keys of positions [tid*ITEMS, tid*ITEMS+ITEMS) live in registers.
+// ITEMS == 0: keys are re-read (thread tid owns [tid*ipt, tid*ipt+ipt)).
+template <int ITEMS>
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restrict__ scores,
                                                             int n, int budget, int recent,
                                                             int32_t *__restrict__ idx) {
@@ -40,12 +46,28 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
     for (int t = tid; t < recent; t += kTopkThreads) out[k + t] = n_cand + t;
     if (k == 0) return;
 
+    constexpr int R = ITEMS > 0 ? ITEMS : 1;
+    const int ipt = ITEMS > 0 ? ITEMS : (n_cand + kTopkThreads - 1) / kTopkThreads;
+    const int j0 = min(tid * ipt, n_cand), j1 = min(j0 + ipt, n_cand);
+    uint32_t key[R];
+    if (ITEMS > 0) {
+        // a key of 0 sorts below every real key (real keys have a bit set) and is never counted
+#pragma unroll
+        for (int t = 0; t < R; ++t) key[t] = j0 + t < j1 ? order_key(sc[j0 + t]) : 0u;
+    }
+
     // range of the keys
     uint32_t kmin = 0xffffffffu, kmax = 0u;
-    for (int j = tid; j < n_cand; j += kTopkThreads) {
-        const uint32_t u = order_key(sc[j]);
-        kmin = min(kmin, u);
-        kmax = max(kmax, u);
+    if (ITEMS > 0) {
+#pragma unroll
+        for (int t = 0; t < R; ++t)
+            if (j0 + t < j1) { kmin = min(kmin, key[t]); kmax = max(kmax, key[t]); }
+    } else {
+        for (int j = j0; j < j1; ++j) {
+            const uint32_t u = order_key(sc[j]);
+            kmin = min(kmin, u);
+            kmax = max(kmax, u);
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -66,9 +88,17 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
             for (int t = tid; t < kTopkWaves * 256; t += kTopkThreads) (&s_hist[0][0])[t] = 0;
             __syncthreads();
             const uint32_t hi_mask = shift >= 24 ? 0u : (0xffffffffu << (shift + 8));
-            for (int j = tid; j < n_cand; j += kTopkThreads) {
-                const uint32_t u = order_key(sc[j]);
-                if ((u & hi_mask) == (prefix & hi_mask)) atomicAdd(&s_hist[wave][(u >> shift) & 255u], 1);
+            const uint32_t want = prefix & hi_mask;
+            if (ITEMS > 0) {
+#pragma unroll
+                for (int t = 0; t < R; ++t)
+                    if (j0 + t < j1 && (key[t] & hi_mask) == want)
+                        atomicAdd(&s_hist[wave][(key[t] >> shift) & 255u], 1);
+            } else {
+                for (int j = j0; j < j1; ++j) {
+                    const uint32_t u = order_key(sc[j]);
+                    if ((u & hi_mask) == want) atomicAdd(&s_hist[wave][(u >> shift) & 255u], 1);
+                }
             }
             __syncthreads();
             if (tid < 256) {
@@ -111,13 +141,16 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
     const uint32_t T = prefix;  // key of the last selected element; take `need` of its equals
 
     // ordered compaction
-    const int ipt = (n_cand + kTopkThreads - 1) / kTopkThreads;
-    const int j0 = min(tid * ipt, n_cand), j1 = min(j0 + ipt, n_cand);
     int gt = 0, eq = 0;
-    for (int j = j0; j < j1; ++j) {
-        const uint32_t u = order_key(sc[j]);
-        gt += u > T;
-        eq += u == T;
+    if (ITEMS > 0) {
+#pragma unroll
+        for (int t = 0; t < R; ++t) { gt += key[t] > T; eq += key[t] == T; }
+    } else {
+        for (int j = j0; j < j1; ++j) {
+            const uint32_t u = order_key(sc[j]);
+            gt += u > T;
+            eq += u == T;
+        }
     }
     int gi = gt, ei = eq;  // inclusive scans over the wave
 #pragma unroll
@@ -130,22 +163,48 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
     int gbase = 0, ebase = 0;
     for (int w = 0; w < wave; ++w) { gbase += s_scan[0][w]; ebase += s_scan[1][w]; }
     int gtc = gbase + gi - gt, eqc = ebase + ei - eq;  // exclusive prefixes
-    for (int j = j0; j < j1; ++j) {
-        const uint32_t u = order_key(sc[j]);
-        if (u > T) {
-            out[gtc + min(eqc, need)] = j;
-            ++gtc;
-        } else if (u == T) {
-            if (eqc < need) out[gtc + eqc] = j;
-            ++eqc;
+    if (ITEMS > 0) {
+#pragma unroll
+        for (int t = 0; t < R; ++t) {
+            if (key[t] > T) {
+                out[gtc + min(eqc, need)] = j0 + t;
+                ++gtc;
+            } else if (key[t] == T) {
+                if (eqc < need) out[gtc + eqc] = j0 + t;
+                ++eqc;
+            }
+        }
+    } else {
+        for (int j = j0; j < j1; ++j) {
+            const uint32_t u = order_key(sc[j]);
+            if (u > T) {
+                out[gtc + min(eqc, need)] = j;
+                ++gtc;
+            } else if (u == T) {
+                if (eqc < need) out[gtc + eqc] = j;
+                ++eqc;
+            }
         }
     }
 }
 
 hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent, int32_t *idx,
                        hipStream_t st) {
-    hipLaunchKernelGGL(topk_kernel, dim3(Z), dim3(kTopkThreads), 0, st, scores, n, budget, recent,
-                       idx);
+    const int n_cand = n - recent;
+    const int ipt = (n_cand + kTopkThreads - 1) / kTopkThreads;
+    dim3 grid(Z), block(kTopkThreads);
+    if (ipt <= 4)
+        hipLaunchKernelGGL(topk_kernel<4>, grid, block, 0, st, scores, n, budget, recent, idx);
+    else if (ipt <= 8)
+        hipLaunchKernelGGL(topk_kernel<8>, grid, block, 0, st, scores, n, budget, recent, idx);
+    else if (ipt <= 16)
+        hipLaunchKernelGGL(topk_kernel<16>, grid, block, 0, st, scores, n, budget, recent, idx);
+    else if (ipt <= 32)
+        hipLaunchKernelGGL(topk_kernel<32>, grid, block, 0, st, scores, n, budget, recent, idx);
+    else if (ipt <= 64)
+        hipLaunchKernelGGL(topk_kernel<64>, grid, block, 0, st, scores, n, budget, recent, idx);
+    else
+        hipLaunchKernelGGL(topk_kernel<0>, grid, block, 0, st, scores, n, budget, recent, idx);
     return hipGetLastError();
 }
 

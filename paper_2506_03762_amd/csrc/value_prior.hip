@@ -3,9 +3,8 @@
 // maxima of gamma from which the consumers form gamma / max(gamma).
 //
 // HBM-bound: V is read exactly once (plus (pool-1)/2 halo rows per tile).
-// The same launch clears the ticket counters that the score pass uses and
-// tabulates the softmax scale of every window row (evaluated in double), so no
-// separate fill or set-up launch is needed.
+// The same launch tabulates the softmax scale of every window row (evaluated
+// in double), so no separate set-up launch is needed.
 #include "aha_dev.h"
 #include "aha_host.h"
 
@@ -15,12 +14,8 @@ namespace aha {
 // 16-byte loads; LPR lanes cover one row.
 template <int ESIZE>
 __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, float *gamma,
-                                                     float *gblockmax, int *counters,
-                                                     int counters_per_z, float *lam_tab) {
+                                                     float *gblockmax, float *lam_tab) {
     const int z = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
-    if (tile == 0) {
-        for (int t = tid; t < counters_per_z; t += 256) counters[z * counters_per_z + t] = 0;
-    }
     if (z == 0) {
         // softmax scale of window row ii (token position n - r + ii, c = position + 1 keys)
         const int ii = tile * 256 + tid;
@@ -43,25 +38,35 @@ __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, 
     const int rows_per_pass = 256 / lpr;
     const int sub = tid % lpr, rloc = tid / lpr;
 
-    for (int row = lo + rloc; row < hi; row += rows_per_pass) {
-        const u32x4 w = *(const u32x4 *)(vbase + (int64_t)ESIZE * row * g.vs[2] + sub * 16);
-        float s = 0.f;
-        if (ESIZE == 2) {
+    // eight independent 16-byte loads in flight per lane
+    for (int row0 = lo + rloc; row0 < hi; row0 += 8 * rows_per_pass) {
+        u32x4 w[8];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                float a = bf16_lo(w[t]), c = bf16_hi(w[t]);
-                s = fmaf(a, a, s);
-                s = fmaf(c, c, s);
-            }
-        } else {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                float a = __uint_as_float(w[t]);
-                s = fmaf(a, a, s);
-            }
+        for (int u = 0; u < 8; ++u) {
+            const int row = min(row0 + u * rows_per_pass, hi - 1);
+            w[u] = *(const u32x4 *)(vbase + (int64_t)ESIZE * row * g.vs[2] + sub * 16);
         }
-        for (int o = lpr >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o);
-        if (sub == 0) s_nu[row - lo] = s;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            float s = 0.f;
+            if (ESIZE == 2) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    float a = bf16_lo(w[u][t]), c = bf16_hi(w[u][t]);
+                    s = fmaf(a, a, s);
+                    s = fmaf(c, c, s);
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    float a = __uint_as_float(w[u][t]);
+                    s = fmaf(a, a, s);
+                }
+            }
+            for (int o = lpr >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o);
+            const int row = row0 + u * rows_per_pass;
+            if (sub == 0 && row < hi) s_nu[row - lo] = s;
+        }
     }
     __syncthreads();
 
@@ -86,17 +91,16 @@ hipError_t launch_value_prior(const ScoreGeom &g, const PrefillPlan &pl, void *w
     char *w = (char *)ws;
     float *gamma = (float *)(w + pl.off_gamma);
     float *gbm = (float *)(w + pl.off_gblockmax);
-    int *counters = (int *)(w + pl.off_counters);
     float *lam_tab = (float *)(w + pl.off_lam);
     const int lam_blocks = (g.r + 255) / 256;
     const int vt = g.value_prior ? pl.n_vtiles : 1;
     dim3 grid(vt > lam_blocks ? vt : lam_blocks, pl.Z);
     if (g.dtype == AHA_BF16)
         hipLaunchKernelGGL(vprior_kernel<2>, grid, dim3(256), 0, st, g, pl.n_vtiles, gamma, gbm,
-                           counters, pl.n_qtiles, lam_tab);
+                           lam_tab);
     else
         hipLaunchKernelGGL(vprior_kernel<4>, grid, dim3(256), 0, st, g, pl.n_vtiles, gamma, gbm,
-                           counters, pl.n_qtiles, lam_tab);
+                           lam_tab);
     return hipGetLastError();
 }
 

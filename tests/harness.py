@@ -206,6 +206,8 @@ def run_and_check_decode(w: synth.Workload, res_gpu: Result, ref: Result, steps:
                       ref.cache.F.astype(np.float32).astype(np.float64), ref.cache.pos.copy(),
                       ref.cache.free_slot.copy())
     gc = upload_cache(oc, w, p)
+    ws = B.alloc_workspace(p)
+    ws.fill_(0xA5)
     rtol = rtol_of(w)
     out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=B.torch_dtype(p.dtype),
                       device="cuda")
@@ -215,7 +217,7 @@ def run_and_check_decode(w: synth.Workload, res_gpu: Result, ref: Result, steps:
         q, k, v = synth.make_decode_inputs(w, t)
         out.fill_(float("nan"))
         B.aha_decode_step(p, to_device(q, w.dtype), to_device(k, w.dtype), to_device(v, w.dtype),
-                          gc.k, gc.v, gc.scores, gc.pos, gc.free_slot, c_t, out)
+                          gc.k, gc.v, gc.scores, gc.pos, gc.free_slot, c_t, out, ws)
         o_ref = oracle.decode_step(oc, q, k, v, c_t, cfg)
         if (t + 1) % check_every and t != steps - 1:
             continue

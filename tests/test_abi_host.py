@@ -114,9 +114,12 @@ def test_other_entry_points_validate(lib):
     cp3 = good(n_q_heads=18).c()
     assert lib.aha_decode_step(ctypes.byref(cp3), *args, 513, 4097, DUMMY, None, 0, None) \
         == B.AHA_ERR_UNSUPPORTED                                              # group of 9
-    cpb = good(budget=4096, n_q_heads=16).c()
+    cpb = good(budget=4096, n_q_heads=16, batch=64).c()
     assert lib.aha_decode_step(ctypes.byref(cpb), *args, 4097, 5000, DUMMY, None, 0, None) \
         == B.AHA_ERR_UNSUPPORTED                                              # dots exceed LDS
+    # few heads: the slots are split over workgroups and the partials need the workspace
+    assert lib.aha_decode_step(ctypes.byref(cp), *args, 513, 4097, DUMMY, None, 0, None) \
+        == B.AHA_ERR_WORKSPACE
 
 
 def test_missing_library_fails_loudly(monkeypatch):

@@ -163,6 +163,16 @@ def test_decode_many_steps_gqa4_bf16():
     check_prefill(w, decode_steps=40)
 
 
+def test_decode_many_heads_single_launch_path():
+    """128 or more (batch, KV head) problems: one workgroup per head, no split."""
+    w = synth.scaled(BF, name="bf16_decode_wide", seq_len=300, n_q_heads=16, n_kv_heads=8,
+                     budget=70, recent=8, window=16, batch=16)
+    check_prefill(w, decode_steps=5)
+    w = synth.scaled(synth.C1, name="f32_decode_wide", seq_len=200, n_q_heads=8, n_kv_heads=8,
+                     budget=33, recent=4, window=8, batch=16)
+    check_prefill(w, decode_steps=5)
+
+
 def test_decode_fixed_scale_and_no_recent_fp32():
     w = synth.scaled(synth.C1, name="f32_decode", budget=60, recent=0, window=16)
     check_prefill(w, Opts(scale_mode=SCALE_FIXED, fixed_scale=0.125), decode_steps=20)
@@ -185,7 +195,8 @@ def test_decode_extra_slots_are_ignored():
     out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device="cuda")
     q, k, v = synth.make_decode_inputs(w, 0)
     B.aha_decode_step(p, H.to_device(q, "bf16"), H.to_device(k, "bf16"), H.to_device(v, "bf16"),
-                      gc.k, gc.v, gc.scores, gc.pos, gc.free_slot, w.seq_len + 1, out)
+                      gc.k, gc.v, gc.scores, gc.pos, gc.free_slot, w.seq_len + 1, out,
+                      B.alloc_workspace(p))
     oracle.decode_step(oc, q, k, v, w.seq_len + 1, H.oracle_cfg(w, Opts()))
     assert np.array_equal(gc.pos.cpu().numpy(), oc.pos)
     assert np.array_equal(gc.free_slot.cpu().numpy(), oc.free_slot)
