@@ -161,6 +161,121 @@ __device__ __forceinline__ void colsum_update(const f32x16 (&acc)[kMB], float la
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// ---- straight-line (unmasked) wave step, software-pipelined by hand ----
+// The matrix pipe needs 8 passes (32 cycles) per MFMA while issuing one takes a
+// single slot, so the vector-ALU work on the PREVIOUS query block is placed
+// between the MFMAs of the NEXT one: 16 slots per block, each one MFMA plus a
+// fixed share of the exponentials.  sched_barrier(0) pins that order; the LDS
+// fragment of k-step ks+2 is requested while k-step ks is being multiplied.
+template <int D, int NB>
+__device__ __forceinline__ bf16x8 ld_bfrag(const __bf16 *sQ, int nb, int ks, int lane) {
+    using S = TileSmem<D, NB>;
+    return *(const bf16x8 *)(sQ + (nb * 32 + (lane & 31)) * S::LD + (lane >> 5) * 8 + ks * 16);
+}
+
+// MFMAs of block nb into `nxt`, with work(slot) for slot = 0..2*KS-1 in between.
+template <int D, int NB, typename F>
+__device__ __forceinline__ void mma_block_with(const bf16x8 (&a)[kMB][D / 16], const __bf16 *sQ,
+                                               int nb, int lane, f32x16 (&nxt)[kMB], F work) {
+    constexpr int KS = D / 16;
+#pragma unroll
+    for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) nxt[mb][v] = 0.f;
+    bf16x8 bf[3];
+    bf[0] = ld_bfrag<D, NB>(sQ, nb, 0, lane);
+    bf[1] = ld_bfrag<D, NB>(sQ, nb, 1, lane);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        if (ks + 2 < KS) bf[(ks + 2) % 3] = ld_bfrag<D, NB>(sQ, nb, ks + 2, lane);
+#pragma unroll
+        for (int mb = 0; mb < kMB; ++mb) {
+            nxt[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb][ks], bf[ks % 3], nxt[mb], 0, 0, 0);
+            float *pin = work(ks * kMB + mb);
+            // tie this slot's vector work to the operand of the NEXT MFMA, so that it cannot
+            // be deferred until all MFMAs of the block have been issued
+            if (pin) {
+                if (mb + 1 < kMB)
+                    asm volatile("" : "+v"(*pin), "+v"(bf[ks % 3]));
+                else if (ks + 1 < KS)
+                    asm volatile("" : "+v"(*pin), "+v"(bf[(ks + 1) % 3]));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+template <int D, int NB>
+__device__ __forceinline__ void fast_step_pass2(const bf16x8 (&a)[kMB][D / 16], const __bf16 *sQ,
+                                                const float *sLam, const float *sL, int lane,
+                                                f32x16 (&col)[kMB]) {
+    constexpr int SLOTS = kMB * (D / 16), EPS = (32 + SLOTS - 1) / SLOTS;  // elements per slot
+    f32x16 acc[2][kMB];
+    mma_block_with<D, NB>(a, sQ, 0, lane, acc[0], [](int) -> float * { return nullptr; });
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const float lam = sLam[nb * 32 + (lane & 31)], L = sL[nb * 32 + (lane & 31)];
+        f32x16(&cur)[kMB] = acc[nb & 1];
+        auto work = [&](int slot) -> float * {
+#pragma unroll
+            for (int e = slot * EPS; e < (slot + 1) * EPS && e < 32; ++e)
+                col[e >> 4][e & 15] += fast_exp2(fmaf(cur[e >> 4][e & 15], lam, -L));
+            return nullptr;
+        };
+        if (nb + 1 < NB) {
+            mma_block_with<D, NB>(a, sQ, nb + 1, lane, acc[(nb + 1) & 1], work);
+        } else {
+#pragma unroll
+            for (int slot = 0; slot < SLOTS; ++slot) work(slot);
+        }
+    }
+}
+
+template <int D, int NB>
+__device__ __forceinline__ void fast_step_pass1(const bf16x8 (&a)[kMB][D / 16], const __bf16 *sQ,
+                                                const float (&lam)[NB], int lane, float (&m)[NB],
+                                                float (&s)[NB]) {
+    constexpr int SLOTS = kMB * (D / 16);
+    // slots 0, 1: block maximum; slot 1 also rescales the running sum; the remaining
+    // slots share the 32 exponentials
+    constexpr int ES = SLOTS - 2;
+    f32x16 acc[2][kMB];
+    mma_block_with<D, NB>(a, sQ, 0, lane, acc[0], [](int) -> float * { return nullptr; });
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        f32x16(&cur)[kMB] = acc[nb & 1];
+        const float lm = lam[nb];
+        float amax0 = -INFINITY, amax1 = -INFINITY, mref = 0.f, sum = 0.f;
+        auto work = [&](int slot) -> float * {
+            if (slot == 0) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) amax0 = fmaxf(amax0, cur[0][v]);
+                return &amax0;
+            } else if (slot == 1) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) amax1 = fmaxf(amax1, cur[kMB - 1][v]);
+                const float mn = fmaxf(m[nb], fmaxf(amax0, amax1) * lm);
+                mref = mn;  // finite: every key of an unmasked block is visible
+                s[nb] *= fast_exp2(m[nb] - mref);
+                m[nb] = mn;
+                return &mref;
+            } else {
+#pragma unroll
+                for (int e = (slot - 2) * 32 / ES; e < (slot - 1) * 32 / ES; ++e)
+                    sum += fast_exp2(fmaf(cur[e >> 4][e & 15], lm, -mref));
+                return &sum;
+            }
+        };
+        if (nb + 1 < NB) {
+            mma_block_with<D, NB>(a, sQ, nb + 1, lane, acc[(nb + 1) & 1], work);
+        } else {
+#pragma unroll
+            for (int slot = 0; slot < SLOTS; ++slot) work(slot);
+        }
+        s[nb] += sum;
+    }
+}
+
 // ---------------------------------------------------------------- pass 1 --
 template <int D, int NB>
 __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles,
@@ -199,9 +314,15 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
 
     const int key_begin = chunk * chunk_keys;
     const int key_end = min(rm.max_pos(rho0, rho0 + S::ROWS) + 1, key_begin + chunk_keys);
+    const int tile_min = rm.min_pos(rho0, rho0 + S::ROWS);  // -1.. when the tile has padding rows
     for (int kb = key_begin + wave * kWaveKeys; kb < key_end; kb += kWgKeys) {
         bf16x8 a[kMB][D / 16];
         load_a<D>(kbase, g.ks[2], kb, g.n, lane, a);
+        if (kb + kWaveKeys - 1 <= tile_min) {
+            // every row of the tile sees all 64 keys: pipelined straight-line code
+            fast_step_pass1<D, NB>(a, sQ, lam, lane, m, s);
+            continue;
+        }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             if (bmax[nb] < kb) continue;  // nothing of this block sees these keys
@@ -362,6 +483,11 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
                 loaded_qt = qt;
             }
             if (kb >= g.n) continue;  // wave-uniform; the barriers above were reached
+            if (kb + kWaveKeys - 1 <= rm.min_pos(rho0, rho0 + S::ROWS)) {
+                // all rows of the tile see all 64 keys: pipelined straight-line code
+                fast_step_pass2<D, NB>(a, sQ, sLam, sL, lane, col);
+                continue;
+            }
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 if (uniform(sBlk[nb]) < kb) continue;
