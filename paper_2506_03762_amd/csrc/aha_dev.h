@@ -48,6 +48,24 @@ __device__ __forceinline__ float row_scale_log2(int scale_mode, float fixed_scal
     return (float)(s * 1.4426950408889634074);
 }
 
+// The same scale in single precision (relative error ~1e-7), for the bf16 path whose
+// tolerance is four orders of magnitude wider; avoids the slow double-precision log.
+__device__ __forceinline__ float row_scale_log2_f32(int scale_mode, float fixed_scale,
+                                                    float lambda_floor, int c, int budget,
+                                                    int head_dim) {
+    float s;
+    if (scale_mode == AHA_SCALE_FIXED) {
+        s = fixed_scale;
+    } else {
+        float lg = logf((float)c / (float)budget);
+        if (lg < 0.f) lg = 0.f;
+        s = sqrtf(2.f * lg / (float)head_dim);
+        const float fl = lambda_floor < 0.f ? rsqrtf((float)head_dim) : lambda_floor;
+        if (s < fl) s = fl;
+    }
+    return s * kLog2e;
+}
+
 // 2^x on the transcendental unit (v_exp_f32): no denormal results, exp2(-inf) = 0.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 

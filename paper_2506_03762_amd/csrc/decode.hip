@@ -101,8 +101,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
 
     // ---- the two softmax denominators ----
     const float c_out = kLog2e * rsqrtf((float)D);
-    const float c_sc = row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor, g.logical_pos,
-                                      g.budget, D);
+    const float c_sc = ESIZE == 2 ? row_scale_log2_f32(g.scale_mode, g.fixed_scale, g.lambda_floor,
+                                                       g.logical_pos, g.budget, D)
+                                  : row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor,
+                                                   g.logical_pos, g.budget, D);
     float zo[G], zs[G];
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) zo[gi] = zs[gi] = 0.f;
@@ -338,13 +340,15 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
 
 // Stage 2, one workgroup per (batch, KV head): merge the partial outputs,
 // update the running scores from the stored dots and pick the victim.
+constexpr int kMergeThreads = 1024;
+
 template <int ESIZE, int D, int G>
-__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeGeom g, int nsplit,
+__global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom g, int nsplit,
                                                            const float *ws_w,
                                                            const float *ws_part) {
     __shared__ float s_mx[G], s_scale[64][G];
-    __shared__ float s_red[4][G];
-    __shared__ unsigned long long s_key[4];
+    __shared__ float s_red[kMergeThreads / 64][G];
+    __shared__ unsigned long long s_key[kMergeThreads / 64];
     __shared__ int s_victim;
     const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = z / g.Hkv, h = z % g.Hkv;
@@ -354,26 +358,44 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeGeom g, int nsp
     int32_t *posz = g.pos + (int64_t)z * g.slots;
     const float *part = ws_part + (int64_t)z * nsplit * G * (D + 2);
     const float c_out = kLog2e * rsqrtf((float)D);
-    const float c_sc = row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor, g.logical_pos,
-                                      g.budget, D);
+    const float c_sc = ESIZE == 2 ? row_scale_log2_f32(g.scale_mode, g.fixed_scale, g.lambda_floor,
+                                                       g.logical_pos, g.budget, D)
+                                  : row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor,
+                                                   g.logical_pos, g.budget, D);
+    // maxima of the splits: one (split, head) pair per thread, then a short LDS fold
+    __shared__ float s_pm[64][G], s_pz[64][G];
+    for (int t = tid; t < nsplit * G; t += kMergeThreads) {
+        const int sp = t / G, gi = t % G;
+        s_pm[sp][gi] = part[(sp * G + gi) * (D + 2) + D];
+        s_pz[sp][gi] = part[(sp * G + gi) * (D + 2) + D + 1];
+    }
+    __syncthreads();
     if (tid < G) {
         float m = -INFINITY;
-        for (int sp = 0; sp < nsplit; ++sp) m = fmaxf(m, part[(sp * G + tid) * (D + 2) + D]);
+        for (int sp = 0; sp < nsplit; ++sp) m = fmaxf(m, s_pm[sp][tid]);
         s_mx[tid] = m;
     }
     __syncthreads();
-    for (int t = tid; t < nsplit * G; t += 256) {
+    for (int t = tid; t < nsplit * G; t += kMergeThreads) {
         const int sp = t / G, gi = t % G;
-        s_scale[sp][gi] = exp2f((part[(sp * G + gi) * (D + 2) + D] - s_mx[gi]) * c_out);
+        s_scale[sp][gi] = exp2f((s_pm[sp][gi] - s_mx[gi]) * c_out);
     }
     __syncthreads();
-    for (int t = tid; t < G * D; t += 256) {
+    for (int t = tid; t < G * D; t += kMergeThreads) {
         const int gi = t / D, c = t % D;
         float num = 0.f, den = 0.f;
-        for (int sp = 0; sp < nsplit; ++sp) {
-            const float sc = s_scale[sp][gi];
-            num = fmaf(part[(sp * G + gi) * (D + 2) + c], sc, num);
-            den = fmaf(part[(sp * G + gi) * (D + 2) + D + 1], sc, den);
+        for (int sp0 = 0; sp0 < nsplit; sp0 += 8) {
+            float x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                x[u] = sp0 + u < nsplit ? part[((sp0 + u) * G + gi) * (D + 2) + c] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (sp0 + u < nsplit) {
+                    const float sc = s_scale[sp0 + u][gi];
+                    num = fmaf(x[u], sc, num);
+                    den = fmaf(s_pz[sp0 + u][gi], sc, den);
+                }
         }
         const float v = num / den;
         const int64_t oi = ((int64_t)(b * g.Hq + h * G + gi)) * D + c;
@@ -382,14 +404,33 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeGeom g, int nsp
         else
             ((float *)g.out)[oi] = v;
     }
-    // score softmax over all live slots, from the stored raw dots
+    // score softmax over all live slots, from the stored raw dots; four slots per thread
+    // and batch are fetched together so that the loads overlap
+    constexpr int NT = kMergeThreads, U = 4;
     float mx[G], zs[G];
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) { mx[gi] = s_mx[gi]; zs[gi] = 0.f; }
-    for (int s = tid; s < live; s += 256) {
+    float wr[U][G], fr[U];
+    int pr[U];
+    const bool one_batch = live <= U * NT;  // then the values stay in registers for pass two
+    auto fetch = [&](int base) {
 #pragma unroll
-        for (int gi = 0; gi < G; ++gi)
-            zs[gi] += exp2f((ws_w[((int64_t)z * G + gi) * live + s] - mx[gi]) * c_sc);
+        for (int u = 0; u < U; ++u) {
+            const int s = base + tid + u * NT;
+            const bool ok = s < live;
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi)
+                wr[u][gi] = ok ? ws_w[((int64_t)z * G + gi) * live + s] : -INFINITY;
+            fr[u] = ok && s != fs ? fcz[s] : 0.f;
+            pr[u] = ok ? (s == fs ? g.logical_pos - 1 : posz[s]) : 0x7fffffff;
+        }
+    };
+    for (int base = 0; base < live; base += U * NT) {
+        fetch(base);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi) zs[gi] += exp2f((wr[u][gi] - mx[gi]) * c_sc);
     }
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) {
@@ -398,22 +439,32 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeGeom g, int nsp
     }
     __syncthreads();
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) zs[gi] = s_red[0][gi] + s_red[1][gi] + s_red[2][gi] + s_red[3][gi];
+    for (int gi = 0; gi < G; ++gi) {
+        float a = 0.f;
+#pragma unroll
+        for (int w = 0; w < NT / 64; ++w) a += s_red[w][gi];
+        zs[gi] = 1.f / a;
+    }
     unsigned long long best = ~0ull;
     int best_slot = -1;
-    for (int s = tid; s < live; s += 256) {
-        float add = 0.f;
+    for (int base = 0; base < live; base += U * NT) {
+        if (!one_batch) fetch(base);
 #pragma unroll
-        for (int gi = 0; gi < G; ++gi)
-            add += exp2f((ws_w[((int64_t)z * G + gi) * live + s] - mx[gi]) * c_sc) / zs[gi];
-        const float f = (s == fs ? 0.f : fcz[s]) + add;
-        fcz[s] = f;
-        int ps;
-        if (s == fs) { ps = g.logical_pos - 1; posz[s] = ps; } else { ps = posz[s]; }
-        if (ps < g.logical_pos - g.recent) {
-            const unsigned long long key =
-                ((unsigned long long)__float_as_uint(f) << 32) | (uint32_t)(~ps);
-            if (key < best) { best = key; best_slot = s; }
+        for (int u = 0; u < U; ++u) {
+            const int s = base + tid + u * NT;
+            if (s >= live) continue;
+            float add = 0.f;
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi) add += exp2f((wr[u][gi] - mx[gi]) * c_sc) * zs[gi];
+            const float f = fr[u] + add;
+            fcz[s] = f;
+            const int ps = pr[u];
+            if (s == fs) posz[s] = ps;
+            if (ps < g.logical_pos - g.recent) {
+                const unsigned long long key =
+                    ((unsigned long long)__float_as_uint(f) << 32) | (uint32_t)(~ps);
+                if (key < best) { best = key; best_slot = s; }
+            }
         }
     }
     unsigned long long wbest = best;
@@ -426,7 +477,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeGeom g, int nsp
     __syncthreads();
     unsigned long long gbest = s_key[0];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) gbest = s_key[w] < gbest ? s_key[w] : gbest;
+    for (int w = 1; w < kMergeThreads / 64; ++w) gbest = s_key[w] < gbest ? s_key[w] : gbest;
     if (best_slot >= 0 && best == gbest) s_victim = best_slot;
     __syncthreads();
     if (tid == 0) {
@@ -448,7 +499,7 @@ static hipError_t launch_g(const DecodeGeom &g, const DecodePlan &pl, void *ws, 
     {                                                                                            \
         hipLaunchKernelGGL((decode_split_kernel<ESIZE, D, GG>), g1, dim3(256), smem1, st, g,     \
                            pl.nsplit, pl.sps, ws_w, ws_part);                                    \
-        hipLaunchKernelGGL((decode_merge_kernel<ESIZE, D, GG>), g2, dim3(256), 0, st, g,         \
+        hipLaunchKernelGGL((decode_merge_kernel<ESIZE, D, GG>), g2, dim3(kMergeThreads), 0, st, g,         \
                            pl.nsplit, ws_w, ws_part);                                            \
     }
         switch (g.G) {

@@ -25,6 +25,25 @@ __device__ __forceinline__ uint32_t order_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Histogram increment with wave-level aggregation: lanes that hit the bin of the first
+// still-active lane are counted with one ballot and added by a single LDS atomic.  Two
+// such rounds absorb the hot bins (scores of one head crowd into a few exponents); the
+// lanes that are left add on their own.
+__device__ __forceinline__ void hist_add(int *hist, uint32_t bin, bool valid, int lane) {
+    unsigned long long active = __ballot(valid);
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        if (active == 0) break;  // wave-uniform
+        const int leader = __ffsll((long long)active) - 1;
+        const uint32_t lbin = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
+        const unsigned long long same = __ballot(valid && bin == lbin);
+        if (lane == leader) atomicAdd(&hist[lbin], __popcll(same));
+        if (bin == lbin) valid = false;
+        active &= ~same;
+    }
+    if (valid) atomicAdd(&hist[bin], 1);
+}
+
 // ITEMS > 0: keys of positions [tid*ITEMS, tid*ITEMS+ITEMS) live in registers.
 // ITEMS == 0: keys are re-read (thread tid owns [tid*ipt, tid*ipt+ipt)).
 template <int ITEMS>
@@ -92,12 +111,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
             if (ITEMS > 0) {
 #pragma unroll
                 for (int t = 0; t < R; ++t)
-                    if (j0 + t < j1 && (key[t] & hi_mask) == want)
-                        atomicAdd(&s_hist[wave][(key[t] >> shift) & 255u], 1);
+                    hist_add(s_hist[wave], (key[t] >> shift) & 255u,
+                             j0 + t < j1 && (key[t] & hi_mask) == want, lane);
             } else {
-                for (int j = j0; j < j1; ++j) {
-                    const uint32_t u = order_key(sc[j]);
-                    if ((u & hi_mask) == want) atomicAdd(&s_hist[wave][(u >> shift) & 255u], 1);
+                for (int t = 0; t < ipt; ++t) {  // same trip count in every lane
+                    const int j = j0 + t;
+                    const uint32_t u = j < j1 ? order_key(sc[j]) : 0u;
+                    hist_add(s_hist[wave], (u >> shift) & 255u, j < j1 && (u & hi_mask) == want, lane);
                 }
             }
             __syncthreads();

@@ -20,8 +20,10 @@ __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, 
         // softmax scale of window row ii (token position n - r + ii, c = position + 1 keys)
         const int ii = tile * 256 + tid;
         if (ii < g.r)
-            lam_tab[ii] = row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor,
-                                         g.n - g.r + ii + 1, g.budget, g.d);
+            lam_tab[ii] = ESIZE == 2 ? row_scale_log2_f32(g.scale_mode, g.fixed_scale, g.lambda_floor,
+                                                          g.n - g.r + ii + 1, g.budget, g.d)
+                                     : row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor,
+                                                      g.n - g.r + ii + 1, g.budget, g.d);
     }
     if (!g.value_prior || tile >= n_vtiles) return;
 
