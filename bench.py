@@ -43,6 +43,9 @@ def main():
                     help="skip the oracle timing (used under rocprofv3)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the C4 decode and C2 full-accumulation side measurements")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 256 MiB device copy (calibrates the rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters against a known size)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -81,6 +84,12 @@ def main():
         B.aha_decode_step(p, qn, kn, vn, cache.k, cache.v, cache.scores, cache.pos,
                           cache.free_slot, n + 1, out, ws)
 
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(W_STEPS):
         step()
     torch.cuda.synchronize()

@@ -3,15 +3,20 @@
 // lower position, written as ascending token positions followed by the recent
 // positions.
 //
-// One workgroup of 1024 threads per problem.  Scores become order-preserving
-// 32-bit keys that stay in registers (each thread owns a contiguous range of
-// token positions); a radix select (8-bit digits, per-wave LDS histograms)
-// finds the key of the last selected element, starting at the highest bit in
-// which the keys of this problem differ at all, so that the first digit
-// already spreads over the bins.  An ordered compaction (one block-wide scan)
-// then writes the indices in ascending order.  Sequences too long for the
-// register file (more than 64 keys per thread) re-read the scores from memory
-// in every round instead.
+// One workgroup of 1024 threads per problem; each thread owns a contiguous
+// range of token positions whose scores, turned into order-preserving 32-bit
+// keys, stay in registers.  The key of the last selected element is found by
+//   1. the key range [kmin, kmax] of the problem (one block reduction);
+//   2. ONE histogram of 4096 bins that are linear in key - kmin over exactly
+//      that range, so the keys spread over the bins whatever their exponents
+//      (few same-address LDS atomics), and a block-wide suffix scan that finds
+//      the bin holding the threshold;
+//   3. an exact rank among the (typically few dozen) keys of that bin, kept in
+//      LDS; if the bin is crowded (many equal or nearly equal scores) the low
+//      bits are resolved by 8-bit radix rounds instead.
+// An ordered compaction (one block-wide scan) then writes the indices in
+// ascending order.  Sequences too long for the register file (more than 64
+// keys per thread) re-read the scores from memory in every pass.
 #include "aha_dev.h"
 #include "aha_host.h"
 
@@ -19,29 +24,41 @@ namespace aha {
 
 constexpr int kTopkThreads = 1024;
 constexpr int kTopkWaves = kTopkThreads / 64;
+constexpr int kBins = 4096;      // first-round bins
+constexpr int kHistCopies = 2;   // waves alternate between copies
+constexpr int kCandMax = 1024;   // keys of the threshold bin ranked directly
 
 __device__ __forceinline__ uint32_t order_key(float f) {
     const uint32_t u = __float_as_uint(f);
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Histogram increment with wave-level aggregation: lanes that hit the bin of the first
-// still-active lane are counted with one ballot and added by a single LDS atomic.  Two
-// such rounds absorb the hot bins (scores of one head crowd into a few exponents); the
-// lanes that are left add on their own.
-__device__ __forceinline__ void hist_add(int *hist, uint32_t bin, bool valid, int lane) {
-    unsigned long long active = __ballot(valid);
+struct TopkSmem {
+    int hist[kHistCopies][kBins];
+    unsigned long long cand[kCandMax];  // key << 32 | ~position: descending = selection order
+    uint32_t red[2][kTopkWaves];
+    int wsum[kTopkWaves];
+    int scan[2][kTopkWaves];
+    int bin, need, ncand;
+    uint32_t T;
+};
+
+// Block-wide: given per-thread counts `loc` of consecutive, ascending key ranges (thread
+// t covers lower keys than thread t+1), find the thread whose range holds the need-th
+// largest key.  Returns the number of keys in the ranges above this thread's.
+__device__ __forceinline__ int suffix_above(int loc, int lane, int wave, int *wsum) {
+    int suf = loc;  // inclusive suffix sum within the wave
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-        if (active == 0) break;  // wave-uniform
-        const int leader = __ffsll((long long)active) - 1;
-        const uint32_t lbin = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
-        const unsigned long long same = __ballot(valid && bin == lbin);
-        if (lane == leader) atomicAdd(&hist[lbin], __popcll(same));
-        if (bin == lbin) valid = false;
-        active &= ~same;
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_down(suf, o);
+        if (lane + o < 64) suf += t;
     }
-    if (valid) atomicAdd(&hist[bin], 1);
+    if (lane == 0) wsum[wave] = suf;
+    __syncthreads();
+    int above = suf - loc;
+    for (int w = wave + 1; w < kTopkWaves; ++w) above += wsum[w];
+    __syncthreads();
+    return above;
 }
 
 // ITEMS > 0: keys of positions [tid*ITEMS, tid*ITEMS+ITEMS) live in registers.
@@ -50,11 +67,8 @@ template <int ITEMS>
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restrict__ scores,
                                                             int n, int budget, int recent,
                                                             int32_t *__restrict__ idx) {
-    __shared__ int s_hist[kTopkWaves][256];
-    __shared__ int s_tot[256];
-    __shared__ uint32_t s_red[2][kTopkWaves];
-    __shared__ int s_digit, s_need;
-    __shared__ int s_scan[2][kTopkWaves];
+    extern __shared__ __attribute__((aligned(16))) char topk_smem[];
+    TopkSmem &sm = *(TopkSmem *)topk_smem;
 
     const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *sc = scores + (int64_t)z * n;
@@ -71,160 +85,189 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
     uint32_t key[R];
     if (ITEMS > 0) {
         // a key of 0 sorts below every real key (real keys have a bit set) and is never counted
+        if (ITEMS % 4 == 0 && (((uintptr_t)(sc + j0)) & 15) == 0 && j0 + ITEMS <= n_cand) {
 #pragma unroll
-        for (int t = 0; t < R; ++t) key[t] = j0 + t < j1 ? order_key(sc[j0 + t]) : 0u;
-    }
-
-    // range of the keys
-    uint32_t kmin = 0xffffffffu, kmax = 0u;
-    if (ITEMS > 0) {
+            for (int t = 0; t < R / 4; ++t) {
+                const float4 v = *(const float4 *)(sc + j0 + 4 * t);
+                key[4 * t] = order_key(v.x); key[4 * t + 1] = order_key(v.y);
+                key[4 * t + 2] = order_key(v.z); key[4 * t + 3] = order_key(v.w);
+            }
+        } else {
 #pragma unroll
-        for (int t = 0; t < R; ++t)
-            if (j0 + t < j1) { kmin = min(kmin, key[t]); kmax = max(kmax, key[t]); }
-    } else {
-        for (int j = j0; j < j1; ++j) {
-            const uint32_t u = order_key(sc[j]);
-            kmin = min(kmin, u);
-            kmax = max(kmax, u);
+            for (int t = 0; t < R; ++t) key[t] = j0 + t < j1 ? order_key(sc[j0 + t]) : 0u;
         }
     }
+    // visit every owned key: f(key, position)
+    auto for_keys = [&](auto f) {
+        if (ITEMS > 0) {
+#pragma unroll
+            for (int t = 0; t < R; ++t)
+                if (j0 + t < j1) f(key[t], j0 + t);
+        } else {
+            for (int j = j0; j < j1; ++j) f(order_key(sc[j]), j);
+        }
+    };
+
+    // 1. range of the keys
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+    for_keys([&](uint32_t u, int) { kmin = min(kmin, u); kmax = max(kmax, u); });
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
         kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
     }
-    if (lane == 0) { s_red[0][wave] = kmin; s_red[1][wave] = kmax; }
+    if (lane == 0) { sm.red[0][wave] = kmin; sm.red[1][wave] = kmax; }
+    for (int t = tid; t < kHistCopies * kBins; t += kTopkThreads) (&sm.hist[0][0])[t] = 0;
+    if (tid == 0) sm.ncand = 0;
     __syncthreads();
-    kmin = s_red[0][0]; kmax = s_red[1][0];
+    kmin = sm.red[0][0]; kmax = sm.red[1][0];
 #pragma unroll
-    for (int w = 1; w < kTopkWaves; ++w) { kmin = min(kmin, s_red[0][w]); kmax = max(kmax, s_red[1][w]); }
+    for (int w = 1; w < kTopkWaves; ++w) { kmin = min(kmin, sm.red[0][w]); kmax = max(kmax, sm.red[1][w]); }
 
-    uint32_t prefix = kmax;  // bits above the current digit are final
-    int need = k;            // how many still to take among keys matching the prefix
+    uint32_t T = kmax;  // key of the last selected element
+    int need = k;       // how many keys equal to T are selected (lowest positions first)
     if (kmin != kmax) {
-        const int hb = 31 - __clz(kmin ^ kmax);  // highest differing bit
-        for (int shift = (hb / 8) * 8; shift >= 0; shift -= 8) {
-            for (int t = tid; t < kTopkWaves * 256; t += kTopkThreads) (&s_hist[0][0])[t] = 0;
-            __syncthreads();
-            const uint32_t hi_mask = shift >= 24 ? 0u : (0xffffffffu << (shift + 8));
-            const uint32_t want = prefix & hi_mask;
-            if (ITEMS > 0) {
+        // 2. one histogram, linear in key - kmin, over the occupied range only
+        const uint32_t range = kmax - kmin;
+        const int sh = max(0, 32 - __clz(range) - 12);  // (range >> sh) < 4096
+        int *hist = sm.hist[wave & (kHistCopies - 1)];
+        for_keys([&](uint32_t u, int) { atomicAdd(&hist[(u - kmin) >> sh], 1); });
+        __syncthreads();
+        int cb[4], loc = 0;
 #pragma unroll
-                for (int t = 0; t < R; ++t)
-                    hist_add(s_hist[wave], (key[t] >> shift) & 255u,
-                             j0 + t < j1 && (key[t] & hi_mask) == want, lane);
-            } else {
-                for (int t = 0; t < ipt; ++t) {  // same trip count in every lane
-                    const int j = j0 + t;
-                    const uint32_t u = j < j1 ? order_key(sc[j]) : 0u;
-                    hist_add(s_hist[wave], (u >> shift) & 255u, j < j1 && (u & hi_mask) == want, lane);
+        for (int t = 0; t < 4; ++t) {
+            cb[t] = 0;
+#pragma unroll
+            for (int c = 0; c < kHistCopies; ++c) cb[t] += sm.hist[c][4 * tid + t];
+            loc += cb[t];
+        }
+        int above = suffix_above(loc, lane, wave, sm.wsum);
+        if (above < need && need <= above + loc) {
+#pragma unroll
+            for (int t = 3; t >= 0; --t) {
+                if (above < need && need <= above + cb[t]) {
+                    sm.bin = 4 * tid + t;
+                    sm.need = need - above;
+                    sm.ncand = cb[t];  // keys in the threshold bin
                 }
+                above += cb[t];
+            }
+        }
+        __syncthreads();
+        const uint32_t bin = (uint32_t)sm.bin;
+        need = sm.need;
+        const int nc = sm.ncand;
+        __syncthreads();
+        if (sh == 0) {
+            T = kmin + bin;  // bins are single keys
+        } else if (nc <= kCandMax) {
+            // 3a. exact rank among the keys of the threshold bin
+            if (tid == 0) sm.ncand = 0;
+            __syncthreads();
+            for_keys([&](uint32_t u, int j) {
+                if (((u - kmin) >> sh) == bin) {
+                    const int slot = atomicAdd(&sm.ncand, 1);
+                    sm.cand[slot] = ((unsigned long long)u << 32) | (uint32_t)(~j);
+                }
+            });
+            __syncthreads();
+            if (tid < nc) {
+                const unsigned long long mine = sm.cand[tid];
+                int rank = 0;  // number of candidates selected before this one
+                int u = 0;
+                for (; u + 4 <= nc; u += 4)
+                    rank += (sm.cand[u] > mine) + (sm.cand[u + 1] > mine) + (sm.cand[u + 2] > mine) +
+                            (sm.cand[u + 3] > mine);
+                for (; u < nc; ++u) rank += sm.cand[u] > mine;
+                if (rank == need - 1) sm.T = (uint32_t)(mine >> 32);
             }
             __syncthreads();
-            if (tid < 256) {
+            T = sm.T;
+            need = -1;  // number of selected keys equal to T: known once the keys above T are counted
+        } else {
+            // 3b. crowded bin: 8-bit radix rounds over the low `sh` bits of key - kmin
+            uint32_t prefix = bin << sh;
+            for (int shift = ((sh - 1) / 8) * 8; shift >= 0; shift -= 8) {
+                __syncthreads();
+                if (tid < 256) { sm.hist[0][tid] = 0; sm.hist[1][tid] = 0; }
+                __syncthreads();
+                const uint32_t hi_mask = 0xffffffffu << min(shift + 8, 31);  // sh <= 20: never 32
+                for_keys([&](uint32_t u, int) {
+                    const uint32_t rel = u - kmin;
+                    if ((rel >> sh) == bin && (rel & hi_mask) == (prefix & hi_mask))
+                        atomicAdd(&hist[(rel >> shift) & 255u], 1);
+                });
+                __syncthreads();
                 int c = 0;
-#pragma unroll
-                for (int w = 0; w < kTopkWaves; ++w) c += s_hist[w][tid];
-                s_tot[tid] = c;
+                if (tid < 256) c = sm.hist[0][tid] + sm.hist[1][tid];
+                const int ab = suffix_above(c, lane, wave, sm.wsum);  // threads >= 256 hold 0
+                if (tid < 256 && ab < need && need <= ab + c) { sm.bin = tid; sm.need = need - ab; }
+                __syncthreads();
+                prefix |= (uint32_t)sm.bin << shift;
+                need = sm.need;
             }
-            __syncthreads();
-            if (wave == 0) {
-                int cb[4];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) cb[t] = s_tot[4 * lane + t];
-                const int loc = cb[0] + cb[1] + cb[2] + cb[3];
-                int suf = loc;  // inclusive suffix sum over lanes
-#pragma unroll
-                for (int o = 1; o < 64; o <<= 1) {
-                    const int t = __shfl_down(suf, o);
-                    if (lane + o < 64) suf += t;
-                }
-                int above = suf - loc;
-                if (above < need && need <= suf) {
-#pragma unroll
-                    for (int t = 3; t >= 0; --t) {
-                        if (above < need && need <= above + cb[t]) {
-                            s_digit = 4 * lane + t;
-                            s_need = need - above;
-                        }
-                        above += cb[t];
-                    }
-                }
-            }
-            __syncthreads();
-            const uint32_t dmask = 255u << shift;
-            prefix = (prefix & ~dmask) | ((uint32_t)s_digit << shift);
-            need = s_need;
-            __syncthreads();
+            T = kmin + prefix;
         }
     }
-    const uint32_t T = prefix;  // key of the last selected element; take `need` of its equals
 
     // ordered compaction
     int gt = 0, eq = 0;
-    if (ITEMS > 0) {
-#pragma unroll
-        for (int t = 0; t < R; ++t) { gt += key[t] > T; eq += key[t] == T; }
-    } else {
-        for (int j = j0; j < j1; ++j) {
-            const uint32_t u = order_key(sc[j]);
-            gt += u > T;
-            eq += u == T;
-        }
-    }
+    for_keys([&](uint32_t u, int) { gt += u > T; eq += u == T; });
     int gi = gt, ei = eq;  // inclusive scans over the wave
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
         const int a = __shfl_up(gi, o), b = __shfl_up(ei, o);
         if (lane >= o) { gi += a; ei += b; }
     }
-    if (lane == 63) { s_scan[0][wave] = gi; s_scan[1][wave] = ei; }
     __syncthreads();
-    int gbase = 0, ebase = 0;
-    for (int w = 0; w < wave; ++w) { gbase += s_scan[0][w]; ebase += s_scan[1][w]; }
-    int gtc = gbase + gi - gt, eqc = ebase + ei - eq;  // exclusive prefixes
-    if (ITEMS > 0) {
-#pragma unroll
-        for (int t = 0; t < R; ++t) {
-            if (key[t] > T) {
-                out[gtc + min(eqc, need)] = j0 + t;
-                ++gtc;
-            } else if (key[t] == T) {
-                if (eqc < need) out[gtc + eqc] = j0 + t;
-                ++eqc;
-            }
-        }
-    } else {
-        for (int j = j0; j < j1; ++j) {
-            const uint32_t u = order_key(sc[j]);
-            if (u > T) {
-                out[gtc + min(eqc, need)] = j;
-                ++gtc;
-            } else if (u == T) {
-                if (eqc < need) out[gtc + eqc] = j;
-                ++eqc;
-            }
-        }
+    if (lane == 63) { sm.scan[0][wave] = gi; sm.scan[1][wave] = ei; }
+    __syncthreads();
+    int gbase = 0, ebase = 0, gtotal = 0;
+    for (int w = 0; w < kTopkWaves; ++w) {
+        if (w < wave) { gbase += sm.scan[0][w]; ebase += sm.scan[1][w]; }
+        gtotal += sm.scan[0][w];
     }
+    if (need < 0) need = k - gtotal;
+    int gtc = gbase + gi - gt, eqc = ebase + ei - eq;  // exclusive prefixes
+    // the k indices are gathered in LDS (the histogram is dead by now) and then written out
+    // with consecutive lanes on consecutive addresses; beyond the staging capacity each
+    // thread writes its own
+    int *stage = &sm.hist[0][0];
+    const bool staged = k <= kHistCopies * kBins;
+    int32_t *dst = staged ? stage : out;
+    for_keys([&](uint32_t u, int j) {
+        if (u > T) {
+            dst[gtc + min(eqc, need)] = j;
+            ++gtc;
+        } else if (u == T) {
+            if (eqc < need) dst[gtc + eqc] = j;
+            ++eqc;
+        }
+    });
+    if (staged) {
+        __syncthreads();
+        for (int t = tid; t < k; t += kTopkThreads) out[t] = stage[t];
+    }
+}
+
+template <int ITEMS>
+static void launch_items(const float *scores, int Z, int n, int budget, int recent, int32_t *idx,
+                         hipStream_t st) {
+    hipLaunchKernelGGL(topk_kernel<ITEMS>, dim3(Z), dim3(kTopkThreads), sizeof(TopkSmem), st, scores,
+                       n, budget, recent, idx);
 }
 
 hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent, int32_t *idx,
                        hipStream_t st) {
+    static_assert(sizeof(TopkSmem) < 64 * 1024, "top-k LDS must fit the default dynamic limit");
     const int n_cand = n - recent;
     const int ipt = (n_cand + kTopkThreads - 1) / kTopkThreads;
-    dim3 grid(Z), block(kTopkThreads);
-    if (ipt <= 4)
-        hipLaunchKernelGGL(topk_kernel<4>, grid, block, 0, st, scores, n, budget, recent, idx);
-    else if (ipt <= 8)
-        hipLaunchKernelGGL(topk_kernel<8>, grid, block, 0, st, scores, n, budget, recent, idx);
-    else if (ipt <= 16)
-        hipLaunchKernelGGL(topk_kernel<16>, grid, block, 0, st, scores, n, budget, recent, idx);
-    else if (ipt <= 32)
-        hipLaunchKernelGGL(topk_kernel<32>, grid, block, 0, st, scores, n, budget, recent, idx);
-    else if (ipt <= 64)
-        hipLaunchKernelGGL(topk_kernel<64>, grid, block, 0, st, scores, n, budget, recent, idx);
-    else
-        hipLaunchKernelGGL(topk_kernel<0>, grid, block, 0, st, scores, n, budget, recent, idx);
+    if (ipt <= 4) launch_items<4>(scores, Z, n, budget, recent, idx, st);
+    else if (ipt <= 8) launch_items<8>(scores, Z, n, budget, recent, idx, st);
+    else if (ipt <= 16) launch_items<16>(scores, Z, n, budget, recent, idx, st);
+    else if (ipt <= 32) launch_items<32>(scores, Z, n, budget, recent, idx, st);
+    else if (ipt <= 64) launch_items<64>(scores, Z, n, budget, recent, idx, st);
+    else launch_items<0>(scores, Z, n, budget, recent, idx, st);
     return hipGetLastError();
 }
 
