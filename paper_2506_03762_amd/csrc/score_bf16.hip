@@ -40,25 +40,54 @@ struct TileSmem {
 
 // Query tile -> LDS: rows rho0 .. rho0+ROWS of the KV head's flattened query
 // rows (zero beyond R), per row the log2-domain scale and the position, and per
-// 32-row block the largest and smallest position.
+// 32-row block the largest and smallest position.  Two halves, so that other
+// loads can be put in flight between the global requests and their use.
 template <int D, int NB>
-__device__ __forceinline__ void load_q_tile(const ScoreGeom &g, const RowMap &rm, int b, int h,
-                                            int rho0, const float *lam_tab, __bf16 *sQ,
-                                            float *sLam, int *sPos, int *sBlk) {
-    using S = TileSmem<D, NB>;
-    constexpr int CPR = D / 8;  // 16-byte chunks per row
+struct QTileRegs {
+    static constexpr int UT = TileSmem<D, NB>::ROWS * (D / 8) / 256;  // 16-byte chunks per thread
+    static_assert(TileSmem<D, NB>::ROWS * (D / 8) % 256 == 0, "tile chunks divide among 256 threads");
+    static constexpr int U = UT < 8 ? UT : 8;   // chunks per batch (bounds the registers held)
+    static constexpr int BATCHES = UT / U;
+    u32x4 w[U];
+};
+
+template <int D, int NB>
+__device__ __forceinline__ void q_tile_request(const ScoreGeom &g, int b, int h, int rho0,
+                                               int batch, QTileRegs<D, NB> &t) {
+    constexpr int CPR = D / 8;
     const int tid = threadIdx.x;
-    for (int t = tid; t < S::ROWS * CPR; t += 256) {
-        const int rr = t / CPR, c = t % CPR, rho = rho0 + rr;
-        u32x4 w = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int u = 0; u < QTileRegs<D, NB>::U; ++u) {
+        const int i = tid + (batch * QTileRegs<D, NB>::U + u) * 256;
+        const int rr = i / CPR, c = i % CPR, rho = rho0 + rr;
+        t.w[u] = u32x4{0u, 0u, 0u, 0u};
         if (rho < g.R) {
             const int gi = rho / g.r, ii = rho - gi * g.r;
             const __bf16 *src = (const __bf16 *)g.q + b * g.qs[0] + (h * g.G + gi) * g.qs[1] +
                                 (int64_t)(g.n - g.r + ii) * g.qs[2] + c * 8;
-            w = *(const u32x4 *)src;
+            t.w[u] = *(const u32x4 *)src;
         }
-        *(u32x4 *)(sQ + rr * S::LD + c * 8) = w;
     }
+}
+
+template <int D, int NB>
+__device__ __forceinline__ void q_tile_commit(int batch, const QTileRegs<D, NB> &t, __bf16 *sQ) {
+    using S = TileSmem<D, NB>;
+    constexpr int CPR = D / 8;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < QTileRegs<D, NB>::U; ++u) {
+        const int i = tid + (batch * QTileRegs<D, NB>::U + u) * 256;
+        *(u32x4 *)(sQ + (i / CPR) * S::LD + (i % CPR) * 8) = t.w[u];
+    }
+}
+
+template <int D, int NB>
+__device__ __forceinline__ void q_tile_meta(const ScoreGeom &g, const RowMap &rm, int rho0,
+                                            const float *lam_tab, float *sLam, int *sPos,
+                                            int *sBlk) {
+    using S = TileSmem<D, NB>;
+    const int tid = threadIdx.x;
     for (int rr = tid; rr < S::ROWS; rr += 256) {
         const int rho = rho0 + rr;
         const bool ok = rho < g.R;
@@ -205,29 +234,18 @@ __device__ __forceinline__ void mma_block_with(const bf16x8 (&a)[kMB][D / 16], c
     }
 }
 
+// Pass 2 keeps the plain order (all MFMAs of a block, then its exponentials): with the
+// column sums, the A fragments and the per-block constants resident, a second accumulator
+// set does not fit in 256 registers, and two waves per SIMD overlap the two pipes anyway.
 template <int D, int NB>
 __device__ __forceinline__ void fast_step_pass2(const bf16x8 (&a)[kMB][D / 16], const __bf16 *sQ,
-                                                const float *sLam, const float *sL, int lane,
-                                                f32x16 (&col)[kMB]) {
-    constexpr int SLOTS = kMB * (D / 16), EPS = (32 + SLOTS - 1) / SLOTS;  // elements per slot
-    f32x16 acc[2][kMB];
-    mma_block_with<D, NB>(a, sQ, 0, lane, acc[0], [](int) -> float * { return nullptr; });
+                                                const float (&lamr)[NB], const float (&Lr)[NB],
+                                                int lane, f32x16 (&col)[kMB]) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-        const float lam = sLam[nb * 32 + (lane & 31)], L = sL[nb * 32 + (lane & 31)];
-        f32x16(&cur)[kMB] = acc[nb & 1];
-        auto work = [&](int slot) -> float * {
-#pragma unroll
-            for (int e = slot * EPS; e < (slot + 1) * EPS && e < 32; ++e)
-                col[e >> 4][e & 15] += fast_exp2(fmaf(cur[e >> 4][e & 15], lam, -L));
-            return nullptr;
-        };
-        if (nb + 1 < NB) {
-            mma_block_with<D, NB>(a, sQ, nb + 1, lane, acc[(nb + 1) & 1], work);
-        } else {
-#pragma unroll
-            for (int slot = 0; slot < SLOTS; ++slot) work(slot);
-        }
+        f32x16 acc[kMB];
+        mma_block<D, NB>(a, sQ, nb, lane, acc);
+        colsum_update<false>(acc, lamr[nb], Lr[nb], 0, 0, lane, col);
     }
 }
 
@@ -297,7 +315,21 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
     const int rho0 = qt * S::ROWS;
     const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
 
-    load_q_tile<D, NB>(g, rm, b, h, rho0, lam_tab, sQ, sLam, sPos, sBlk);
+    // the first key block is requested before the query tile, so both latencies overlap
+    const int key_begin = chunk * chunk_keys;
+    const int key_end = min(rm.max_pos(rho0, rho0 + S::ROWS) + 1, key_begin + chunk_keys);
+    const int kb_first = key_begin + wave * kWaveKeys;
+    bf16x8 a[kMB][D / 16];
+    load_a<D>(kbase, g.ks[2], min(kb_first, g.n - 1), g.n, lane, a);
+    {
+        QTileRegs<D, NB> qt_regs;
+#pragma unroll
+        for (int bt = 0; bt < QTileRegs<D, NB>::BATCHES; ++bt) {
+            q_tile_request<D, NB>(g, b, h, rho0, bt, qt_regs);
+            q_tile_commit<D, NB>(bt, qt_regs, sQ);
+        }
+        q_tile_meta<D, NB>(g, rm, rho0, lam_tab, sLam, sPos, sBlk);
+    }
     __syncthreads();
 
     float lam[NB], m[NB], s[NB];
@@ -312,12 +344,9 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
         s[nb] = 0.f;
     }
 
-    const int key_begin = chunk * chunk_keys;
-    const int key_end = min(rm.max_pos(rho0, rho0 + S::ROWS) + 1, key_begin + chunk_keys);
-    const int tile_min = rm.min_pos(rho0, rho0 + S::ROWS);  // -1.. when the tile has padding rows
-    for (int kb = key_begin + wave * kWaveKeys; kb < key_end; kb += kWgKeys) {
-        bf16x8 a[kMB][D / 16];
-        load_a<D>(kbase, g.ks[2], kb, g.n, lane, a);
+    const int tile_min = rm.min_pos(rho0, rho0 + S::ROWS);
+    for (int kb = kb_first; kb < key_end; kb += kWgKeys) {
+        if (kb != kb_first) load_a<D>(kbase, g.ks[2], kb, g.n, lane, a);
         if (kb + kWaveKeys - 1 <= tile_min) {
             // every row of the tile sees all 64 keys: pipelined straight-line code
             fast_step_pass1<D, NB>(a, sQ, lam, lane, m, s);
@@ -456,6 +485,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
         if (lane == 0) s_gmax[wave] = gm;
     }
     int loaded_qt = -1;
+    float lamr[NB], Lr[NB];  // scale and log-sum-exp of this lane's query column, per block
     const int key_begin = blockIdx.x * wg_keys;
     const int key_end = min(g.n, key_begin + wg_keys);
     for (int kb0 = key_begin; kb0 < key_end; kb0 += kWgKeys) {
@@ -473,19 +503,35 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             if (rm.max_pos(rho0, rho0 + S::ROWS) < kb0) continue;  // workgroup-uniform
             if (qt != loaded_qt) {
                 __syncthreads();
-                load_q_tile<D, NB>(g, rm, b, h, rho0, lam_tab, sQ, sLam, sPos, sBlk);
-                for (int rr = tid; rr < S::ROWS; rr += 256)
-                    sL[rr] = rho0 + rr < g.R
-                                 ? fold_chunks(partial + ((int64_t)(z * n_qtiles + qt) * nchunks) * S::ROWS + rr,
-                                               S::ROWS, nchunks)
-                                 : INFINITY;
+                {
+                    // tile rows and chunk statistics are requested together, then used
+                    QTileRegs<D, NB> qt_regs;
+                    q_tile_request<D, NB>(g, b, h, rho0, 0, qt_regs);
+                    for (int rr = tid; rr < S::ROWS; rr += 256)
+                        sL[rr] = rho0 + rr < g.R
+                                     ? fold_chunks(partial + ((int64_t)(z * n_qtiles + qt) * nchunks) * S::ROWS + rr,
+                                                   S::ROWS, nchunks)
+                                     : INFINITY;
+                    q_tile_commit<D, NB>(0, qt_regs, sQ);
+#pragma unroll
+                    for (int bt = 1; bt < QTileRegs<D, NB>::BATCHES; ++bt) {
+                        q_tile_request<D, NB>(g, b, h, rho0, bt, qt_regs);
+                        q_tile_commit<D, NB>(bt, qt_regs, sQ);
+                    }
+                    q_tile_meta<D, NB>(g, rm, rho0, lam_tab, sLam, sPos, sBlk);
+                }
                 __syncthreads();
                 loaded_qt = qt;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    lamr[nb] = sLam[nb * 32 + (lane & 31)];
+                    Lr[nb] = sL[nb * 32 + (lane & 31)];
+                }
             }
             if (kb >= g.n) continue;  // wave-uniform; the barriers above were reached
             if (kb + kWaveKeys - 1 <= rm.min_pos(rho0, rho0 + S::ROWS)) {
                 // all rows of the tile see all 64 keys: pipelined straight-line code
-                fast_step_pass2<D, NB>(a, sQ, sLam, sL, lane, col);
+                fast_step_pass2<D, NB>(a, sQ, lamr, Lr, lane, col);
                 continue;
             }
 #pragma unroll
@@ -493,8 +539,8 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
                 if (uniform(sBlk[nb]) < kb) continue;
                 f32x16 acc[kMB];
                 mma_block<D, NB>(a, sQ, nb, lane, acc);
-                const float lam = sLam[nb * 32 + (lane & 31)];
-                const float L = sL[nb * 32 + (lane & 31)];
+                const float lam = lamr[nb];
+                const float L = Lr[nb];
                 const int pos = sPos[nb * 32 + (lane & 31)];
                 if (kb + kWaveKeys - 1 > uniform(sBlk[NB + nb]))
                     colsum_update<true>(acc, lam, L, pos, kb, lane, col);
