@@ -44,7 +44,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the C4 decode and C2 full-accumulation side measurements")
     ap.add_argument("--copy-probe", action="store_true",
-                    help="also run one plain 256 MiB device copy (calibrates the rocprofv3 "
+                    help="also run one plain 256 MiB elementwise kernel (calibrates the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters against a known size)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -85,9 +85,10 @@ def main():
                           cache.free_slot, n + 1, out, ws)
 
     if args.copy_probe:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        # an elementwise kernel that reads 256 MiB and writes 256 MiB
+        src = torch.ones(64 << 20, dtype=torch.int32, device="cuda")
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        torch.add(src, 1, out=dst)
         torch.cuda.synchronize()
         del src, dst
     for _ in range(W_STEPS):
@@ -148,9 +149,17 @@ def main():
         kernels[name]["TFLOPs"] = score_flops_pass / (kt[name] * 1e-3) / 1e12
     dom = max(("value_prior", "score_pass1", "score_pass2", "topk", "compact", "decode_step"),
               key=lambda nm: kt[nm])
+    # HBM bytes per launch from the committed rocprofv3 counter summary of this workload
+    traffic = None
+    try:
+        tj = json.load(open(os.path.join(ROOT, "profiles", "c3_hbm_traffic.json")))
+        if tj.get("workload") == w.name and dom in tj["kernels"]:
+            traffic = tj["kernels"][dom]["total_bytes"]
+    except (OSError, ValueError, KeyError):
+        traffic = None
     roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["GBps"],
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dom]["GBps"] / HBM_PEAK_GBS,
-                "traffic": None}
+                "traffic": traffic}
     # the whole score stage against the bytes the method needs once (K + V + Q window)
     stage_ms = kt["value_prior"] + kt["score_pass1"] + kt["score_pass2"]
     stage_bytes = 2 * kbytes + qbytes + b * hk * n * 4
