@@ -18,7 +18,8 @@
 // rows of a KV head's query group) in LDS as the B operand; each of its four
 // waves owns 64-key blocks whose A fragments it loads straight from global
 // memory into registers (each K byte is fetched once per tile), so waves run
-// independently between the tile barriers.
+// independently between the tile barriers; the A fragments are double-buffered so
+// that the next key block is in flight while the current one multiplies.
 #include "aha_dev.h"
 #include "aha_host.h"
 
@@ -190,110 +191,6 @@ __device__ __forceinline__ void colsum_update(const f32x16 (&acc)[kMB], float la
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
-// ---- straight-line (unmasked) wave step, software-pipelined by hand ----
-// The matrix pipe needs 8 passes (32 cycles) per MFMA while issuing one takes a
-// single slot, so the vector-ALU work on the PREVIOUS query block is placed
-// between the MFMAs of the NEXT one: 16 slots per block, each one MFMA plus a
-// fixed share of the exponentials.  sched_barrier(0) pins that order; the LDS
-// fragment of k-step ks+2 is requested while k-step ks is being multiplied.
-template <int D, int NB>
-__device__ __forceinline__ bf16x8 ld_bfrag(const __bf16 *sQ, int nb, int ks, int lane) {
-    using S = TileSmem<D, NB>;
-    return *(const bf16x8 *)(sQ + (nb * 32 + (lane & 31)) * S::LD + (lane >> 5) * 8 + ks * 16);
-}
-
-// MFMAs of block nb into `nxt`, with work(slot) for slot = 0..2*KS-1 in between.
-template <int D, int NB, typename F>
-__device__ __forceinline__ void mma_block_with(const bf16x8 (&a)[kMB][D / 16], const __bf16 *sQ,
-                                               int nb, int lane, f32x16 (&nxt)[kMB], F work) {
-    constexpr int KS = D / 16;
-#pragma unroll
-    for (int mb = 0; mb < kMB; ++mb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) nxt[mb][v] = 0.f;
-    bf16x8 bf[3];
-    bf[0] = ld_bfrag<D, NB>(sQ, nb, 0, lane);
-    bf[1] = ld_bfrag<D, NB>(sQ, nb, 1, lane);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        if (ks + 2 < KS) bf[(ks + 2) % 3] = ld_bfrag<D, NB>(sQ, nb, ks + 2, lane);
-#pragma unroll
-        for (int mb = 0; mb < kMB; ++mb) {
-            nxt[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb][ks], bf[ks % 3], nxt[mb], 0, 0, 0);
-            float *pin = work(ks * kMB + mb);
-            // tie this slot's vector work to the operand of the NEXT MFMA, so that it cannot
-            // be deferred until all MFMAs of the block have been issued
-            if (pin) {
-                if (mb + 1 < kMB)
-                    asm volatile("" : "+v"(*pin), "+v"(bf[ks % 3]));
-                else if (ks + 1 < KS)
-                    asm volatile("" : "+v"(*pin), "+v"(bf[(ks + 1) % 3]));
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-}
-
-// Pass 2 keeps the plain order (all MFMAs of a block, then its exponentials): with the
-// column sums, the A fragments and the per-block constants resident, a second accumulator
-// set does not fit in 256 registers, and two waves per SIMD overlap the two pipes anyway.
-template <int D, int NB>
-__device__ __forceinline__ void fast_step_pass2(const bf16x8 (&a)[kMB][D / 16], const __bf16 *sQ,
-                                                const float (&lamr)[NB], const float (&Lr)[NB],
-                                                int lane, f32x16 (&col)[kMB]) {
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        f32x16 acc[kMB];
-        mma_block<D, NB>(a, sQ, nb, lane, acc);
-        colsum_update<false>(acc, lamr[nb], Lr[nb], 0, 0, lane, col);
-    }
-}
-
-template <int D, int NB>
-__device__ __forceinline__ void fast_step_pass1(const bf16x8 (&a)[kMB][D / 16], const __bf16 *sQ,
-                                                const float (&lam)[NB], int lane, float (&m)[NB],
-                                                float (&s)[NB]) {
-    constexpr int SLOTS = kMB * (D / 16);
-    // slots 0, 1: block maximum; slot 1 also rescales the running sum; the remaining
-    // slots share the 32 exponentials
-    constexpr int ES = SLOTS - 2;
-    f32x16 acc[2][kMB];
-    mma_block_with<D, NB>(a, sQ, 0, lane, acc[0], [](int) -> float * { return nullptr; });
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        f32x16(&cur)[kMB] = acc[nb & 1];
-        const float lm = lam[nb];
-        float amax0 = -INFINITY, amax1 = -INFINITY, mref = 0.f, sum = 0.f;
-        auto work = [&](int slot) -> float * {
-            if (slot == 0) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) amax0 = fmaxf(amax0, cur[0][v]);
-                return &amax0;
-            } else if (slot == 1) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) amax1 = fmaxf(amax1, cur[kMB - 1][v]);
-                const float mn = fmaxf(m[nb], fmaxf(amax0, amax1) * lm);
-                mref = mn;  // finite: every key of an unmasked block is visible
-                s[nb] *= fast_exp2(m[nb] - mref);
-                m[nb] = mn;
-                return &mref;
-            } else {
-#pragma unroll
-                for (int e = (slot - 2) * 32 / ES; e < (slot - 1) * 32 / ES; ++e)
-                    sum += fast_exp2(fmaf(cur[e >> 4][e & 15], lm, -mref));
-                return &sum;
-            }
-        };
-        if (nb + 1 < NB) {
-            mma_block_with<D, NB>(a, sQ, nb + 1, lane, acc[(nb + 1) & 1], work);
-        } else {
-#pragma unroll
-            for (int slot = 0; slot < SLOTS; ++slot) work(slot);
-        }
-        s[nb] += sum;
-    }
-}
-
 // ---------------------------------------------------------------- pass 1 --
 template <int D, int NB>
 __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles,
@@ -319,8 +216,8 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
     const int key_begin = chunk * chunk_keys;
     const int key_end = min(rm.max_pos(rho0, rho0 + S::ROWS) + 1, key_begin + chunk_keys);
     const int kb_first = key_begin + wave * kWaveKeys;
-    bf16x8 a[kMB][D / 16];
-    load_a<D>(kbase, g.ks[2], min(kb_first, g.n - 1), g.n, lane, a);
+    bf16x8 a0[kMB][D / 16], a1[kMB][D / 16];  // two buffers: the next key block loads while one multiplies
+    load_a<D>(kbase, g.ks[2], min(kb_first, g.n - 1), g.n, lane, a0);
     {
         QTileRegs<D, NB> qt_regs;
 #pragma unroll
@@ -345,12 +242,16 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
     }
 
     const int tile_min = rm.min_pos(rho0, rho0 + S::ROWS);
-    for (int kb = kb_first; kb < key_end; kb += kWgKeys) {
-        if (kb != kb_first) load_a<D>(kbase, g.ks[2], kb, g.n, lane, a);
+    auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb) {
         if (kb + kWaveKeys - 1 <= tile_min) {
-            // every row of the tile sees all 64 keys: pipelined straight-line code
-            fast_step_pass1<D, NB>(a, sQ, lam, lane, m, s);
-            continue;
+            // every row of the tile sees all 64 keys: no masks, no skipped blocks
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                f32x16 acc[kMB];
+                mma_block<D, NB>(a, sQ, nb, lane, acc);
+                stats_update<false>(acc, lam[nb], 0, kb, lane, m[nb], s[nb]);
+            }
+            return;
         }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
@@ -362,6 +263,14 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
             else
                 stats_update<false>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb]);
         }
+    };
+    for (int kb = kb_first; kb < key_end; kb += 2 * kWgKeys) {
+        const int k1 = kb + kWgKeys, k2 = k1 + kWgKeys;
+        if (k1 < key_end) load_a<D>(kbase, g.ks[2], k1, g.n, lane, a1);
+        step(a0, kb);
+        if (k1 >= key_end) break;
+        if (k2 < key_end) load_a<D>(kbase, g.ks[2], k2, g.n, lane, a0);
+        step(a1, k1);
     }
 
     // fold the two half-waves (same query column, different key rows)
@@ -455,7 +364,11 @@ __device__ __forceinline__ float fold_chunks(const float2 *src, int stride, int 
     return M + log2f(sum);
 }
 
-template <int D, int NB>
+// SINGLE: all observed rows fit one query tile (the windowed score).  The tile is loaded
+// once, the workgroup walks over several 256-key steps and the A fragments of the next
+// step load while the current one multiplies.  Otherwise (full accumulation) a workgroup
+// owns one 256-key step and streams every query tile that sees it through LDS.
+template <int D, int NB, bool SINGLE>
 __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_qtiles,
                                                             int wg_keys, int nchunks,
                                                             const float *lam_tab,
@@ -477,6 +390,12 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const RowMap rm{g.n, g.r, g.R};
     const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
+    const int key_begin = blockIdx.x * wg_keys;
+    const int key_end = min(g.n, key_begin + wg_keys);
+
+    // the first key block is requested before everything else: its latency is the longest
+    bf16x8 a0[kMB][D / 16];
+    load_a<D>(kbase, g.ks[2], key_begin + wave * kWaveKeys, g.n, lane, a0);
 
     if (g.value_prior) {
         float gm = 0.f;
@@ -484,70 +403,62 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
         gm = wave_max(gm);
         if (lane == 0) s_gmax[wave] = gm;
     }
-    int loaded_qt = -1;
     float lamr[NB], Lr[NB];  // scale and log-sum-exp of this lane's query column, per block
-    const int key_begin = blockIdx.x * wg_keys;
-    const int key_end = min(g.n, key_begin + wg_keys);
-    for (int kb0 = key_begin; kb0 < key_end; kb0 += kWgKeys) {
-        const int kb = kb0 + wave * kWaveKeys;
-        bf16x8 a[kMB][D / 16];
-        load_a<D>(kbase, g.ks[2], kb, g.n, lane, a);
-        f32x16 col[kMB];
-#pragma unroll
-        for (int mb = 0; mb < kMB; ++mb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) col[mb][v] = 0.f;
 
-        for (int qt = 0; qt < n_qtiles; ++qt) {
-            const int rho0 = qt * S::ROWS;
-            if (rm.max_pos(rho0, rho0 + S::ROWS) < kb0) continue;  // workgroup-uniform
-            if (qt != loaded_qt) {
-                __syncthreads();
-                {
-                    // tile rows and chunk statistics are requested together, then used
-                    QTileRegs<D, NB> qt_regs;
-                    q_tile_request<D, NB>(g, b, h, rho0, 0, qt_regs);
-                    for (int rr = tid; rr < S::ROWS; rr += 256)
-                        sL[rr] = rho0 + rr < g.R
-                                     ? fold_chunks(partial + ((int64_t)(z * n_qtiles + qt) * nchunks) * S::ROWS + rr,
-                                                   S::ROWS, nchunks)
-                                     : INFINITY;
-                    q_tile_commit<D, NB>(0, qt_regs, sQ);
+    // query tile qt -> LDS, with the log-sum-exp of its rows folded from pass 1's chunks
+    auto load_tile = [&](int qt) {
+        const int rho0 = qt * S::ROWS;
+        {
+            // tile rows and chunk statistics are requested together, then used
+            QTileRegs<D, NB> qt_regs;
+            q_tile_request<D, NB>(g, b, h, rho0, 0, qt_regs);
+            for (int rr = tid; rr < S::ROWS; rr += 256)
+                sL[rr] = rho0 + rr < g.R
+                             ? fold_chunks(partial + ((int64_t)(z * n_qtiles + qt) * nchunks) * S::ROWS + rr,
+                                           S::ROWS, nchunks)
+                             : INFINITY;
+            q_tile_commit<D, NB>(0, qt_regs, sQ);
 #pragma unroll
-                    for (int bt = 1; bt < QTileRegs<D, NB>::BATCHES; ++bt) {
-                        q_tile_request<D, NB>(g, b, h, rho0, bt, qt_regs);
-                        q_tile_commit<D, NB>(bt, qt_regs, sQ);
-                    }
-                    q_tile_meta<D, NB>(g, rm, rho0, lam_tab, sLam, sPos, sBlk);
-                }
-                __syncthreads();
-                loaded_qt = qt;
+            for (int bt = 1; bt < QTileRegs<D, NB>::BATCHES; ++bt) {
+                q_tile_request<D, NB>(g, b, h, rho0, bt, qt_regs);
+                q_tile_commit<D, NB>(bt, qt_regs, sQ);
+            }
+            q_tile_meta<D, NB>(g, rm, rho0, lam_tab, sLam, sPos, sBlk);
+        }
+        __syncthreads();
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    lamr[nb] = sLam[nb * 32 + (lane & 31)];
-                    Lr[nb] = sL[nb * 32 + (lane & 31)];
-                }
-            }
-            if (kb >= g.n) continue;  // wave-uniform; the barriers above were reached
-            if (kb + kWaveKeys - 1 <= rm.min_pos(rho0, rho0 + S::ROWS)) {
-                // all rows of the tile see all 64 keys: pipelined straight-line code
-                fast_step_pass2<D, NB>(a, sQ, lamr, Lr, lane, col);
-                continue;
-            }
+        for (int nb = 0; nb < NB; ++nb) {
+            lamr[nb] = sLam[nb * 32 + (lane & 31)];
+            Lr[nb] = sL[nb * 32 + (lane & 31)];
+        }
+    };
+    // this wave's 64 keys (A fragments a) against the query tile in LDS
+    auto tile_times_keys = [&](const bf16x8 (&a)[kMB][D / 16], int kb, int rho0,
+                               f32x16 (&col)[kMB]) {
+        if (kb + kWaveKeys - 1 <= rm.min_pos(rho0, rho0 + S::ROWS)) {
+            // all rows of the tile see all 64 keys: no masks, no skipped blocks
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                if (uniform(sBlk[nb]) < kb) continue;
                 f32x16 acc[kMB];
                 mma_block<D, NB>(a, sQ, nb, lane, acc);
-                const float lam = lamr[nb];
-                const float L = Lr[nb];
-                const int pos = sPos[nb * 32 + (lane & 31)];
-                if (kb + kWaveKeys - 1 > uniform(sBlk[NB + nb]))
-                    colsum_update<true>(acc, lam, L, pos, kb, lane, col);
-                else
-                    colsum_update<false>(acc, lam, L, pos, kb, lane, col);
+                colsum_update<false>(acc, lamr[nb], Lr[nb], 0, kb, lane, col);
             }
+            return;
         }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            if (uniform(sBlk[nb]) < kb) continue;
+            f32x16 acc[kMB];
+            mma_block<D, NB>(a, sQ, nb, lane, acc);
+            const int pos = sPos[nb * 32 + (lane & 31)];
+            if (kb + kWaveKeys - 1 > uniform(sBlk[NB + nb]))
+                colsum_update<true>(acc, lamr[nb], Lr[nb], pos, kb, lane, col);
+            else
+                colsum_update<false>(acc, lamr[nb], Lr[nb], pos, kb, lane, col);
+        }
+    };
+    // fold the 32 lanes of each half-wave and write the 64 scores of this wave's keys
+    auto write_scores = [&](f32x16 (&col)[kMB], int kb) {
         float ginv = 1.f;
         if (g.value_prior)  // s_gmax was published by the barrier of the first tile load
             ginv = 1.f / fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3]));
@@ -563,6 +474,48 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
                 scores[(int64_t)z * g.n + j] = out;
             }
         }
+    };
+    auto zero = [&](f32x16 (&col)[kMB]) {
+#pragma unroll
+        for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) col[mb][v] = 0.f;
+    };
+
+    if constexpr (SINGLE) {
+        load_tile(0);
+        bf16x8 a1[kMB][D / 16];
+        auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb0) {
+            const int kb = kb0 + wave * kWaveKeys;
+            if (kb >= g.n) return;
+            f32x16 col[kMB];
+            zero(col);
+            tile_times_keys(a, kb, 0, col);
+            write_scores(col, kb);
+        };
+        for (int kb0 = key_begin; kb0 < key_end; kb0 += 2 * kWgKeys) {
+            const int k1 = kb0 + kWgKeys, k2 = k1 + kWgKeys;
+            if (k1 < key_end) load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, g.n, lane, a1);
+            step(a0, kb0);
+            if (k1 >= key_end) break;
+            if (k2 < key_end) load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, g.n, lane, a0);
+            step(a1, k1);
+        }
+    } else {
+        // one step per workgroup (wg_keys == 256); tiles stream through LDS
+        const int kb0 = key_begin, kb = kb0 + wave * kWaveKeys;
+        f32x16 col[kMB];
+        zero(col);
+        bool first = true;
+        for (int qt = 0; qt < n_qtiles; ++qt) {
+            const int rho0 = qt * S::ROWS;
+            if (rm.max_pos(rho0, rho0 + S::ROWS) < kb0) continue;  // workgroup-uniform
+            if (!first) __syncthreads();  // everyone is done with the previous tile
+            first = false;
+            load_tile(qt);
+            if (kb < g.n) tile_times_keys(a0, kb, rho0, col);
+        }
+        write_scores(col, kb);
     }
 }
 
@@ -582,7 +535,10 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)S::bytes);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void *)bf16_pass2_kernel<D, NB>,
+        e = hipFuncSetAttribute((const void *)bf16_pass2_kernel<D, NB, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::bytes);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void *)bf16_pass2_kernel<D, NB, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::bytes);
         if (e != hipSuccess) return e;
         attr_done = true;
@@ -592,8 +548,14 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
                        pl.chunk_keys, pl.nchunks, lam_tab, partial);
     if (mid) (void)hipEventRecord(mid, st);
     dim3 g2((g.n + pl.p2_keys - 1) / pl.p2_keys, pl.Z);
-    hipLaunchKernelGGL((bf16_pass2_kernel<D, NB>), g2, dim3(256), S::bytes, st, g, pl.n_qtiles,
-                       pl.p2_keys, pl.nchunks, lam_tab, partial, gamma, gbm, pl.n_vtiles, scores);
+    if (pl.n_qtiles == 1)
+        hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, true>), g2, dim3(256), S::bytes, st, g,
+                           pl.n_qtiles, pl.p2_keys, pl.nchunks, lam_tab, partial, gamma, gbm,
+                           pl.n_vtiles, scores);
+    else
+        hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, false>), g2, dim3(256), S::bytes, st, g,
+                           pl.n_qtiles, pl.p2_keys, pl.nchunks, lam_tab, partial, gamma, gbm,
+                           pl.n_vtiles, scores);
     return hipGetLastError();
 }
 
