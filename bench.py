@@ -183,6 +183,7 @@ def main():
     if not args.no_extras:
         result["decode_c4"] = bench_decode_c4(torch, B, synth, H, K_STEPS)
         result["full_accumulation_c2"] = bench_full_c2(torch, B, synth, H, max(5, K_STEPS // 5))
+        result["prefill_c5_layer"] = bench_c5_layer(torch, B, synth, H, max(5, K_STEPS // 5))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, (Q, K, V), synth, H)
     print(json.dumps(result))
@@ -281,6 +282,56 @@ def bench_full_c2(torch, B, synth, H, steps):
                          "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS},
             "pass1_TFLOPs": flops_pass / (p1 * 1e-3) / 1e12,
             "pass2_TFLOPs": flops_pass / (p2 * 1e-3) / 1e12}
+
+
+def bench_c5_layer(torch, B, synth, H, steps):
+    """One layer of the full-depth sweep (batch 4 x 32 heads x 16384, budget 3276): the
+    shape at which the windowed score, the value prior and the compaction are bound by HBM
+    bandwidth.  Timing only: seeded Gaussian Q/K/V drawn on the device."""
+    w = synth.C5
+    b, hq, hk, n, d = w.batch, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
+    g = torch.Generator(device="cuda"); g.manual_seed(synth.BASE_SEED + 5000)
+    q, k, v = (torch.randn((b, hh, n, d), device="cuda", generator=g).to(torch.bfloat16)
+               for hh in (hq, hk, hk))
+    p = H.gpu_params(w).with_strides(q, k, v)
+    ws = B.alloc_workspace(p)
+    scores = torch.empty((b, hk, n), dtype=torch.float32, device="cuda")
+    idx = torch.empty((b, hk, w.budget), dtype=torch.int32, device="cuda")
+    cache = B.CompactCache.empty(p)
+
+    def ev():
+        e = torch.cuda.Event(enable_timing=True); e.record(); return e
+
+    sets = []
+    for it in range(steps + 2):
+        st = [ev() for _ in range(4)]
+        B.profile_events(st)
+        B.aha_prefill_scores(p, q, k, v, scores, ws)
+        B.profile_events(None)
+        e0 = ev(); B.aha_select_topk(p, scores, idx, ws)
+        e1 = ev(); B.aha_compact_kv(p, k, v, scores, idx, cache.k, cache.v, cache.scores,
+                                    cache.pos, cache.free_slot)
+        e2 = ev()
+        if it >= 2:
+            sets.append((st, e0, e1, e2))
+    torch.cuda.synchronize()
+    t = {"value_prior": avg_ms([(s[0][0], s[0][1]) for s in sets]),
+         "score_pass1": avg_ms([(s[0][1], s[0][2]) for s in sets]),
+         "score_pass2": avg_ms([(s[0][2], s[0][3]) for s in sets]),
+         "topk": avg_ms([(s[1], s[2]) for s in sets]),
+         "compact": avg_ms([(s[2], s[3]) for s in sets])}
+    kb = b * hk * n * d * 2
+    alg = {"value_prior": kb + b * hk * n * 4, "score_pass1": kb + b * hq * w.window * d * 2,
+           "score_pass2": kb + b * hq * w.window * d * 2 + b * hk * n * 4,
+           "topk": b * hk * (n + w.budget) * 4,
+           "compact": 4 * b * hk * w.budget * d * 2 + b * hk * w.budget * 12}
+    out = {"workload": w.name + " (one layer)", "us_per_layer": sum(t.values()) * 1e3,
+           "tokens_per_s": b * n / (sum(t.values()) * 1e-3), "kernels": {}}
+    for name in t:
+        gbs = alg[name] / (t[name] * 1e-3) / 1e9
+        out["kernels"][name] = {"us": t[name] * 1e3, "alg_bytes": alg[name], "GBps": gbs,
+                                "hbm_frac": gbs / HBM_PEAK_GBS}
+    return out
 
 
 def cpu_baseline(w, inputs, synth, H):

@@ -3,7 +3,6 @@
 // enqueued, so the error paths need no GPU.
 #include <stdarg.h>
 #include <stdio.h>
-#include <stdlib.h>
 
 #include "aha_host.h"
 
@@ -123,7 +122,7 @@ static PrefillPlan plan_prefill(const aha_params *p) {
         // pass-1 key chunks: enough workgroups to fill 256 CUs a few times over,
         // chunks a multiple of the 256 keys a workgroup sweeps per step
         const int64_t tiles = (int64_t)pl.Z * pl.n_qtiles;
-        static const int target_wgs = getenv("AHA_TUNE_WGS") ? atoi(getenv("AHA_TUNE_WGS")) : 512;
+        const int target_wgs = 512;  // two resident workgroups per CU
         int64_t want = (target_wgs + tiles - 1) / tiles;  // chunks per tile
         if (want < 1) want = 1;
         int64_t ck = ((n + want - 1) / want + kP2Keys - 1) / kP2Keys * kP2Keys;

@@ -40,16 +40,18 @@ __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, 
     const int rows_per_pass = 256 / lpr;
     const int sub = tid % lpr, rloc = tid / lpr;
 
-    // eight independent 16-byte loads in flight per lane
-    for (int row0 = lo + rloc; row0 < hi; row0 += 8 * rows_per_pass) {
-        u32x4 w[8];
+    // eight independent 16-byte loads in flight per lane (more in flight measured slower at
+    // the large shapes)
+    constexpr int U = 8;
+    for (int row0 = lo + rloc; row0 < hi; row0 += U * rows_per_pass) {
+        u32x4 w[U];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < U; ++u) {
             const int row = min(row0 + u * rows_per_pass, hi - 1);
             w[u] = *(const u32x4 *)(vbase + (int64_t)ESIZE * row * g.vs[2] + sub * 16);
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < U; ++u) {
             float s = 0.f;
             if (ESIZE == 2) {
 #pragma unroll
