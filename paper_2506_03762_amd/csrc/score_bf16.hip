@@ -457,22 +457,27 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
                 colsum_update<false>(acc, lamr[nb], Lr[nb], pos, kb, lane, col);
         }
     };
+    // The value-prior factors of the (up to two) scores this lane will write are requested
+    // when a step starts, so that their latency is hidden behind the step's arithmetic.
+    const int my_v = ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2 +
+                     ((lane >> 1) & 1);
+    auto request_gamma = [&](int kb, float (&gam)[kMB]) {
+#pragma unroll
+        for (int mb = 0; mb < kMB; ++mb) {
+            const int j = acc_key(kb, mb, my_v, lane);
+            gam[mb] = (g.value_prior && j < g.n) ? gamma[(int64_t)z * g.n + j] : 1.f;
+        }
+    };
     // fold the 32 lanes of each half-wave and write the 64 scores of this wave's keys
-    auto write_scores = [&](f32x16 (&col)[kMB], int kb) {
+    auto write_scores = [&](f32x16 (&col)[kMB], int kb, const float (&gam)[kMB]) {
         float ginv = 1.f;
         if (g.value_prior)  // s_gmax was published by the barrier of the first tile load
             ginv = 1.f / fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3]));
 #pragma unroll
         for (int mb = 0; mb < kMB; ++mb) {
             const float tot = fold16_over32(col[mb], lane);
-            const int v = ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2 +
-                          ((lane >> 1) & 1);
-            const int j = acc_key(kb, mb, v, lane);
-            if ((lane & 1) == 0 && j < g.n) {
-                float out = tot;
-                if (g.value_prior) out = tot * (gamma[(int64_t)z * g.n + j] * ginv);
-                scores[(int64_t)z * g.n + j] = out;
-            }
+            const int j = acc_key(kb, mb, my_v, lane);
+            if ((lane & 1) == 0 && j < g.n) scores[(int64_t)z * g.n + j] = tot * (gam[mb] * ginv);
         }
     };
     auto zero = [&](f32x16 (&col)[kMB]) {
@@ -488,10 +493,12 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
         auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb0) {
             const int kb = kb0 + wave * kWaveKeys;
             if (kb >= g.n) return;
+            float gam[kMB];
+            request_gamma(kb, gam);
             f32x16 col[kMB];
             zero(col);
             tile_times_keys(a, kb, 0, col);
-            write_scores(col, kb);
+            write_scores(col, kb, gam);
         };
         for (int kb0 = key_begin; kb0 < key_end; kb0 += 2 * kWgKeys) {
             const int k1 = kb0 + kWgKeys, k2 = k1 + kWgKeys;
@@ -504,6 +511,8 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     } else {
         // one step per workgroup (wg_keys == 256); tiles stream through LDS
         const int kb0 = key_begin, kb = kb0 + wave * kWaveKeys;
+        float gam[kMB];
+        request_gamma(kb, gam);
         f32x16 col[kMB];
         zero(col);
         bool first = true;
@@ -515,7 +524,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             load_tile(qt);
             if (kb < g.n) tile_times_keys(a0, kb, rho0, col);
         }
-        write_scores(col, kb);
+        write_scores(col, kb, gam);
     }
 }
 
