@@ -223,7 +223,7 @@ int32_t aha_prefill_scores(const aha_params *p, const void *q, const void *k, co
     const ScoreGeom g = make_geom(p, q, k, v);
     hipStream_t st = (hipStream_t)stream;
     if ((rc = hip_result(stage(0, st), "stage event"))) return rc;
-    if ((rc = hip_result(launch_value_prior(g, pl, workspace, st), "value-prior kernel"))) return rc;
+    if ((rc = hip_result(launch_value_prior(g, pl, workspace, scores, st), "value-prior kernel"))) return rc;
     if ((rc = hip_result(stage(1, st), "stage event"))) return rc;
     hipEvent_t mid = g_stage_on ? g_stage_ev[2] : nullptr;
     if (p->dtype == AHA_BF16)

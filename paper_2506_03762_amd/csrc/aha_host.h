@@ -42,7 +42,7 @@ constexpr int kP2Keys = 256;      // keys per pass-2 workgroup (4 waves x 64)
 
 // value_prior.hip
 hipError_t launch_value_prior(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
-                              hipStream_t st);
+                              float *scores, hipStream_t st);
 // score_f32.hip
 // `mid`, when not null, is recorded between the two passes.
 hipError_t launch_score_f32(const ScoreGeom &g, const PrefillPlan &pl, void *ws,

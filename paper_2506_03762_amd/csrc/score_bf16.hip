@@ -366,8 +366,9 @@ __device__ __forceinline__ float fold_chunks(const float2 *src, int stride, int 
 
 // SINGLE: all observed rows fit one query tile (the windowed score).  The tile is loaded
 // once, the workgroup walks over several 256-key steps and the A fragments of the next
-// step load while the current one multiplies.  Otherwise (full accumulation) a workgroup
-// owns one 256-key step and streams every query tile that sees it through LDS.
+// step load while the current one multiplies; every score is written exactly once.
+// Otherwise (full accumulation) the grid is (key chunk, query tile, problem) as in pass 1
+// and the tiles' contributions meet in the scores through float atomics.
 template <int D, int NB, bool SINGLE>
 __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_qtiles,
                                                             int wg_keys, int nchunks,
@@ -385,13 +386,17 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     int *sBlk = (int *)(sL + S::ROWS);
     __shared__ float s_gmax[4];
 
-    const int z = blockIdx.y;
+    const int z = SINGLE ? blockIdx.y : blockIdx.z;
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const RowMap rm{g.n, g.r, g.R};
     const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
     const int key_begin = blockIdx.x * wg_keys;
-    const int key_end = min(g.n, key_begin + wg_keys);
+    // multi-tile: this workgroup's tile only sees keys up to its last row's position
+    const int my_qt = SINGLE ? 0 : blockIdx.y;
+    const int key_end = min(SINGLE ? g.n : rm.max_pos(my_qt * S::ROWS, (my_qt + 1) * S::ROWS) + 1,
+                            key_begin + wg_keys);
+    if (!SINGLE && key_begin >= key_end) return;  // workgroup-uniform, before any barrier
 
     // the first key block is requested before everything else: its latency is the longest
     bf16x8 a0[kMB][D / 16];
@@ -509,22 +514,41 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             step(a1, k1);
         }
     } else {
-        // one step per workgroup (wg_keys == 256); tiles stream through LDS
-        const int kb0 = key_begin, kb = kb0 + wave * kWaveKeys;
-        float gam[kMB];
-        request_gamma(kb, gam);
-        f32x16 col[kMB];
-        zero(col);
-        bool first = true;
-        for (int qt = 0; qt < n_qtiles; ++qt) {
-            const int rho0 = qt * S::ROWS;
-            if (rm.max_pos(rho0, rho0 + S::ROWS) < kb0) continue;  // workgroup-uniform
-            if (!first) __syncthreads();  // everyone is done with the previous tile
-            first = false;
-            load_tile(qt);
-            if (kb < g.n) tile_times_keys(a0, kb, rho0, col);
+        // full accumulation: this workgroup keeps ONE query tile in LDS and streams its keys
+        // like pass 1; the 64 column sums of a wave step are this tile's contribution and are
+        // added to the (zero-initialised) scores with hardware float atomics, already
+        // multiplied by the value prior.  The order of the additions over the tiles is not
+        // fixed, so repeated calls may differ in the last bits.
+        const int rho0 = my_qt * S::ROWS;
+        load_tile(my_qt);
+        float ginv = 1.f;
+        if (g.value_prior)
+            ginv = 1.f / fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3]));
+        bf16x8 a1[kMB][D / 16];
+        auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb0) {
+            const int kb = kb0 + wave * kWaveKeys;
+            if (kb >= key_end) return;
+            float gam[kMB];
+            request_gamma(kb, gam);
+            f32x16 col[kMB];
+            zero(col);
+            tile_times_keys(a, kb, rho0, col);
+#pragma unroll
+            for (int mb = 0; mb < kMB; ++mb) {
+                const float tot = fold16_over32(col[mb], lane);
+                const int j = acc_key(kb, mb, my_v, lane);
+                if ((lane & 1) == 0 && j < key_end)
+                    unsafeAtomicAdd(&scores[(int64_t)z * g.n + j], tot * (gam[mb] * ginv));
+            }
+        };
+        for (int kb0 = key_begin; kb0 < key_end; kb0 += 2 * kWgKeys) {
+            const int k1 = kb0 + kWgKeys, k2 = k1 + kWgKeys;
+            if (k1 < key_end) load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, g.n, lane, a1);
+            step(a0, kb0);
+            if (k1 >= key_end) break;
+            if (k2 < key_end) load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, g.n, lane, a0);
+            step(a1, k1);
         }
-        write_scores(col, kb, gam);
     }
 }
 
@@ -557,13 +581,14 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
                        pl.chunk_keys, pl.nchunks, lam_tab, partial);
     if (mid) (void)hipEventRecord(mid, st);
     dim3 g2((g.n + pl.p2_keys - 1) / pl.p2_keys, pl.Z);
+    dim3 g2m(pl.nchunks, pl.n_qtiles, pl.Z);
     if (pl.n_qtiles == 1)
         hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, true>), g2, dim3(256), S::bytes, st, g,
                            pl.n_qtiles, pl.p2_keys, pl.nchunks, lam_tab, partial, gamma, gbm,
                            pl.n_vtiles, scores);
     else
-        hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, false>), g2, dim3(256), S::bytes, st, g,
-                           pl.n_qtiles, pl.p2_keys, pl.nchunks, lam_tab, partial, gamma, gbm,
+        hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, false>), g2m, dim3(256), S::bytes, st, g,
+                           pl.n_qtiles, pl.chunk_keys, pl.nchunks, lam_tab, partial, gamma, gbm,
                            pl.n_vtiles, scores);
     return hipGetLastError();
 }

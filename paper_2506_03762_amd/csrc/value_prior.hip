@@ -14,8 +14,14 @@ namespace aha {
 // 16-byte loads; LPR lanes cover one row.
 template <int ESIZE>
 __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, float *gamma,
-                                                     float *gblockmax, float *lam_tab) {
+                                                     float *gblockmax, float *lam_tab,
+                                                     float *zero_scores) {
     const int z = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
+    if (zero_scores && tile < n_vtiles) {
+        // full accumulation adds tile contributions atomically: the scores start from zero
+        const int j = tile * kVTileRows + tid;
+        if (j < g.n) zero_scores[(int64_t)z * g.n + j] = 0.f;
+    }
     if (z == 0) {
         // softmax scale of window row ii (token position n - r + ii, c = position + 1 keys)
         const int ii = tile * 256 + tid;
@@ -91,20 +97,22 @@ __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, 
 }
 
 hipError_t launch_value_prior(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
-                              hipStream_t st) {
+                              float *scores, hipStream_t st) {
     char *w = (char *)ws;
     float *gamma = (float *)(w + pl.off_gamma);
     float *gbm = (float *)(w + pl.off_gblockmax);
     float *lam_tab = (float *)(w + pl.off_lam);
     const int lam_blocks = (g.r + 255) / 256;
-    const int vt = g.value_prior ? pl.n_vtiles : 1;
+    // bf16 full accumulation (several query tiles) needs zeroed scores
+    float *zero_scores = (g.dtype == AHA_BF16 && pl.n_qtiles > 1) ? scores : nullptr;
+    const int vt = (g.value_prior || zero_scores) ? pl.n_vtiles : 1;
     dim3 grid(vt > lam_blocks ? vt : lam_blocks, pl.Z);
     if (g.dtype == AHA_BF16)
         hipLaunchKernelGGL(vprior_kernel<2>, grid, dim3(256), 0, st, g, pl.n_vtiles, gamma, gbm,
-                           lam_tab);
+                           lam_tab, zero_scores);
     else
         hipLaunchKernelGGL(vprior_kernel<4>, grid, dim3(256), 0, st, g, pl.n_vtiles, gamma, gbm,
-                           lam_tab);
+                           lam_tab, zero_scores);
     return hipGetLastError();
 }
 
