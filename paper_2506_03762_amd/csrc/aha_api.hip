@@ -119,19 +119,21 @@ static PrefillPlan plan_prefill(const aha_params *p) {
         if (blocks == 3) pl.NB = 4;
         pl.qtile = pl.NB * 32;
         pl.n_qtiles = (int)((R + pl.qtile - 1) / pl.qtile);
-        // pass-1 key chunks: enough workgroups to fill 256 CUs a few times over,
-        // chunks a multiple of the 256 keys a workgroup sweeps per step
-        const int64_t tiles = (int64_t)pl.Z * pl.n_qtiles;
-        const int target_wgs = 512;  // two resident workgroups per CU
-        int64_t want = (target_wgs + tiles - 1) / tiles;  // chunks per tile
+        // Work units: query tiles are paired (first with last, ...) so that in full
+        // accumulation every pair sees about the same number of keys, and the key steps of
+        // a pair are cut into `nchunks` parts so that about 512 workgroups (two per CU) exist.
+        const int64_t npairs = (pl.n_qtiles + 1) / 2;
+        const int64_t units = (int64_t)pl.Z * npairs;
+        const int target_wgs = 512;
+        int64_t want = (target_wgs + units - 1) / units;
+        const int64_t steps = (n + kP2Keys - 1) / kP2Keys;          // 256-key steps of a full tile
+        const int64_t pair_steps = pl.n_qtiles > 1 ? steps + 1 : steps;
+        if (want > pair_steps) want = pair_steps;
         if (want < 1) want = 1;
-        int64_t ck = ((n + want - 1) / want + kP2Keys - 1) / kP2Keys * kP2Keys;
-        if (ck < kP2Keys) ck = kP2Keys;
-        pl.chunk_keys = (int)ck;
-        pl.nchunks = (int)((n + ck - 1) / ck);
-        // pass 2 re-reads the query tiles per key step, so it takes several key
-        // steps per workgroup only when one tile holds all observed rows
-        pl.p2_keys = pl.n_qtiles == 1 ? pl.chunk_keys : kP2Keys;
+        pl.nchunks = (int)want;
+        pl.chunk_keys = (int)(((steps + want - 1) / want) * kP2Keys);
+        // windowed pass 2 (one tile) walks over the same key ranges, several steps per workgroup
+        pl.p2_keys = pl.chunk_keys;
     } else {
         pl.NB = 0;
         pl.qtile = 1;
@@ -218,7 +220,7 @@ int32_t aha_prefill_scores(const aha_params *p, const void *q, const void *k, co
     if (p->value_prior && (rc = check_ptr("v", v, 16))) return rc;
     const PrefillPlan pl = plan_prefill(p);
     if ((rc = check_ws(workspace, workspace_bytes, pl.bytes))) return rc;
-    if (pl.nchunks > 65535 || pl.n_qtiles > 65535 || pl.Z > 65535)
+    if (pl.nchunks > 65535 || pl.n_qtiles > 2 * 65535 || pl.Z > 65535)
         return fail(AHA_ERR_UNSUPPORTED, "problem exceeds the launch grid limits");
     const ScoreGeom g = make_geom(p, q, k, v);
     hipStream_t st = (hipStream_t)stream;

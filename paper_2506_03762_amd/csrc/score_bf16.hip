@@ -191,10 +191,39 @@ __device__ __forceinline__ void colsum_update(const f32x16 (&acc)[kMB], float la
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Work split shared by pass 1 and by pass 2 in full accumulation.  Query tile `pair` is
+// teamed with tile T-1-pair: a tile of late rows sees many keys, its partner few, together
+// about the same as any other pair.  The 256-key steps of the pair (first tile's, then the
+// partner's) are cut into `nparts` equal ranges; segment `seg` (0: first tile, 1: partner)
+// of a workgroup is the part of its range that falls on that tile.
+struct Segment {
+    int qt;          // query tile, -1: no such segment
+    int kbeg, kend;  // keys [kbeg, kend); empty when kbeg >= kend
+};
+__device__ __forceinline__ Segment pair_segment(const RowMap &rm, int rows, int T, int pair,
+                                                int part, int nparts, int seg) {
+    const int tA = pair, tB = T - 1 - pair;
+    const int endA = rm.max_pos(tA * rows, (tA + 1) * rows) + 1;
+    const int endB = tB != tA ? rm.max_pos(tB * rows, (tB + 1) * rows) + 1 : 0;
+    const int sA = (endA + kWgKeys - 1) / kWgKeys, sB = (endB + kWgKeys - 1) / kWgKeys;
+    const int total = sA + sB, per = (total + nparts - 1) / nparts;
+    const int s0 = part * per, s1 = min(total, s0 + per);
+    Segment r;
+    if (seg == 0) {
+        r.qt = tA;
+        r.kbeg = min(s0, sA) * kWgKeys;
+        r.kend = min(endA, min(s1, sA) * kWgKeys);
+    } else {
+        r.qt = tB != tA ? tB : -1;
+        r.kbeg = (max(s0, sA) - sA) * kWgKeys;
+        r.kend = min(endB, (max(s1, sA) - sA) * kWgKeys);
+    }
+    return r;
+}
+
 // ---------------------------------------------------------------- pass 1 --
 template <int D, int NB>
-__global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles,
-                                                            int chunk_keys, int nchunks,
+__global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles, int nparts,
                                                             const float *lam_tab,
                                                             float2 *partial) {
     using S = TileSmem<D, NB>;
@@ -205,102 +234,112 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
     int *sBlk = sPos + 2 * S::ROWS;
     float2 *sRed = (float2 *)smem;  // reuses the query tile after the main loop
 
-    const int chunk = blockIdx.x, qt = blockIdx.y, z = blockIdx.z;
+    const int part = blockIdx.x, pair = blockIdx.y, z = blockIdx.z;
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const RowMap rm{g.n, g.r, g.R};
-    const int rho0 = qt * S::ROWS;
     const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
 
-    // the first key block is requested before the query tile, so both latencies overlap
-    const int key_begin = chunk * chunk_keys;
-    const int key_end = min(rm.max_pos(rho0, rho0 + S::ROWS) + 1, key_begin + chunk_keys);
-    const int kb_first = key_begin + wave * kWaveKeys;
-    bf16x8 a0[kMB][D / 16], a1[kMB][D / 16];  // two buffers: the next key block loads while one multiplies
-    load_a<D>(kbase, g.ks[2], min(kb_first, g.n - 1), g.n, lane, a0);
-    {
-        QTileRegs<D, NB> qt_regs;
-#pragma unroll
-        for (int bt = 0; bt < QTileRegs<D, NB>::BATCHES; ++bt) {
-            q_tile_request<D, NB>(g, b, h, rho0, bt, qt_regs);
-            q_tile_commit<D, NB>(bt, qt_regs, sQ);
+    for (int seg = 0; seg < 2; ++seg) {
+        const Segment sg = pair_segment(rm, S::ROWS, n_qtiles, pair, part, nparts, seg);
+        if (sg.qt < 0) break;
+        const int qt = sg.qt, rho0 = qt * S::ROWS;
+        float2 *my_partial = partial + ((int64_t)(z * n_qtiles + qt) * nparts + part) * S::ROWS;
+        const int key_begin = sg.kbeg, key_end = sg.kend;
+        if (key_begin >= key_end) {
+            // none of this part's steps fall on this tile: leave neutral statistics
+            if (tid < S::ROWS) my_partial[tid] = make_float2(-INFINITY, 0.f);
+            continue;
         }
-        q_tile_meta<D, NB>(g, rm, rho0, lam_tab, sLam, sPos, sBlk);
-    }
-    __syncthreads();
-
-    float lam[NB], m[NB], s[NB];
-    int pos[NB], bmax[NB], bmin[NB];
+        if (seg) __syncthreads();  // the previous tile (and its reduction buffer) is done with
+        // the first key block is requested before the query tile, so both latencies overlap
+        const int kb_first = key_begin + wave * kWaveKeys;
+        bf16x8 a0[kMB][D / 16], a1[kMB][D / 16];  // the next key block loads while one multiplies
+        load_a<D>(kbase, g.ks[2], min(kb_first, g.n - 1), g.n, lane, a0);
+        {
+            QTileRegs<D, NB> qt_regs;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        lam[nb] = sLam[nb * 32 + (lane & 31)];
-        pos[nb] = sPos[nb * 32 + (lane & 31)];
-        bmax[nb] = uniform(sBlk[nb]);
-        bmin[nb] = uniform(sBlk[NB + nb]);
-        m[nb] = -INFINITY;
-        s[nb] = 0.f;
-    }
-
-    const int tile_min = rm.min_pos(rho0, rho0 + S::ROWS);
-    auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb) {
-        if (kb + kWaveKeys - 1 <= tile_min) {
-            // every row of the tile sees all 64 keys: no masks, no skipped blocks
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                f32x16 acc[kMB];
-                mma_block<D, NB>(a, sQ, nb, lane, acc);
-                stats_update<false>(acc, lam[nb], 0, kb, lane, m[nb], s[nb]);
+            for (int bt = 0; bt < QTileRegs<D, NB>::BATCHES; ++bt) {
+                q_tile_request<D, NB>(g, b, h, rho0, bt, qt_regs);
+                q_tile_commit<D, NB>(bt, qt_regs, sQ);
             }
-            return;
+            q_tile_meta<D, NB>(g, rm, rho0, lam_tab, sLam, sPos, sBlk);
         }
+        __syncthreads();
+
+        float lam[NB], m[NB], s[NB];
+        int pos[NB], bmax[NB], bmin[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            if (bmax[nb] < kb) continue;  // nothing of this block sees these keys
-            f32x16 acc[kMB];
-            mma_block<D, NB>(a, sQ, nb, lane, acc);
-            if (kb + kWaveKeys - 1 > bmin[nb])
-                stats_update<true>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb]);
-            else
-                stats_update<false>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb]);
+            lam[nb] = sLam[nb * 32 + (lane & 31)];
+            pos[nb] = sPos[nb * 32 + (lane & 31)];
+            bmax[nb] = uniform(sBlk[nb]);
+            bmin[nb] = uniform(sBlk[NB + nb]);
+            m[nb] = -INFINITY;
+            s[nb] = 0.f;
         }
-    };
-    for (int kb = kb_first; kb < key_end; kb += 2 * kWgKeys) {
-        const int k1 = kb + kWgKeys, k2 = k1 + kWgKeys;
-        if (k1 < key_end) load_a<D>(kbase, g.ks[2], k1, g.n, lane, a1);
-        step(a0, kb);
-        if (k1 >= key_end) break;
-        if (k2 < key_end) load_a<D>(kbase, g.ks[2], k2, g.n, lane, a0);
-        step(a1, k1);
-    }
 
-    // fold the two half-waves (same query column, different key rows)
+        const int tile_min = rm.min_pos(rho0, rho0 + S::ROWS);
+        auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb) {
+            if (kb + kWaveKeys - 1 <= tile_min) {
+                // every row of the tile sees all 64 keys: no masks, no skipped blocks
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const float m2 = __shfl_xor(m[nb], 32), s2 = __shfl_xor(s[nb], 32);
-        const float mn = fmaxf(m[nb], m2);
-        const float mref = mn == -INFINITY ? 0.f : mn;
-        s[nb] = s[nb] * fast_exp2(m[nb] - mref) + s2 * fast_exp2(m2 - mref);
-        m[nb] = mn;
-    }
-    __syncthreads();  // everyone is done reading the query tile
-    if (lane < 32) {
+                for (int nb = 0; nb < NB; ++nb) {
+                    f32x16 acc[kMB];
+                    mma_block<D, NB>(a, sQ, nb, lane, acc);
+                    stats_update<false>(acc, lam[nb], 0, kb, lane, m[nb], s[nb]);
+                }
+                return;
+            }
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) sRed[wave * S::ROWS + nb * 32 + lane] = make_float2(m[nb], s[nb]);
-    }
-    __syncthreads();
-    float2 *my_partial = partial + ((int64_t)(z * n_qtiles + qt) * nchunks) * S::ROWS;
-    if (tid < S::ROWS) {
-        float M = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) M = fmaxf(M, sRed[w * S::ROWS + tid].x);
-        const float mref = M == -INFINITY ? 0.f : M;
-        float sum = 0.f;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float2 e = sRed[w * S::ROWS + tid];
-            sum += e.y * fast_exp2(e.x - mref);
+            for (int nb = 0; nb < NB; ++nb) {
+                if (bmax[nb] < kb) continue;  // nothing of this block sees these keys
+                f32x16 acc[kMB];
+                mma_block<D, NB>(a, sQ, nb, lane, acc);
+                if (kb + kWaveKeys - 1 > bmin[nb])
+                    stats_update<true>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb]);
+                else
+                    stats_update<false>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb]);
+            }
+        };
+        for (int kb = kb_first; kb < key_end; kb += 2 * kWgKeys) {
+            const int k1 = kb + kWgKeys, k2 = k1 + kWgKeys;
+            if (k1 < key_end) load_a<D>(kbase, g.ks[2], k1, g.n, lane, a1);
+            step(a0, kb);
+            if (k1 >= key_end) break;
+            if (k2 < key_end) load_a<D>(kbase, g.ks[2], k2, g.n, lane, a0);
+            step(a1, k1);
         }
-        my_partial[(int64_t)chunk * S::ROWS + tid] = make_float2(M, sum);
+
+        // fold the two half-waves (same query column, different key rows)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const float m2 = __shfl_xor(m[nb], 32), s2 = __shfl_xor(s[nb], 32);
+            const float mn = fmaxf(m[nb], m2);
+            const float mref = mn == -INFINITY ? 0.f : mn;
+            s[nb] = s[nb] * fast_exp2(m[nb] - mref) + s2 * fast_exp2(m2 - mref);
+            m[nb] = mn;
+        }
+        __syncthreads();  // everyone is done reading the query tile
+        if (lane < 32) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                sRed[wave * S::ROWS + nb * 32 + lane] = make_float2(m[nb], s[nb]);
+        }
+        __syncthreads();
+        if (tid < S::ROWS) {
+            float M = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) M = fmaxf(M, sRed[w * S::ROWS + tid].x);
+            const float mref = M == -INFINITY ? 0.f : M;
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float2 e = sRed[w * S::ROWS + tid];
+                sum += e.y * fast_exp2(e.x - mref);
+            }
+            my_partial[tid] = make_float2(M, sum);
+        }
     }
 }
 
@@ -367,8 +406,8 @@ __device__ __forceinline__ float fold_chunks(const float2 *src, int stride, int 
 // SINGLE: all observed rows fit one query tile (the windowed score).  The tile is loaded
 // once, the workgroup walks over several 256-key steps and the A fragments of the next
 // step load while the current one multiplies; every score is written exactly once.
-// Otherwise (full accumulation) the grid is (key chunk, query tile, problem) as in pass 1
-// and the tiles' contributions meet in the scores through float atomics.
+// Otherwise (full accumulation) the grid is (part, tile pair, problem) as in pass 1 and the
+// tiles' contributions meet in the scores through float atomics.
 template <int D, int NB, bool SINGLE>
 __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_qtiles,
                                                             int wg_keys, int nchunks,
@@ -391,16 +430,13 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const RowMap rm{g.n, g.r, g.R};
     const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
-    const int key_begin = blockIdx.x * wg_keys;
-    // multi-tile: this workgroup's tile only sees keys up to its last row's position
-    const int my_qt = SINGLE ? 0 : blockIdx.y;
-    const int key_end = min(SINGLE ? g.n : rm.max_pos(my_qt * S::ROWS, (my_qt + 1) * S::ROWS) + 1,
-                            key_begin + wg_keys);
-    if (!SINGLE && key_begin >= key_end) return;  // workgroup-uniform, before any barrier
+    // SINGLE: the workgroup's key range; otherwise ranges come per tile segment (below)
+    int key_begin = blockIdx.x * wg_keys;
+    int key_end = min(g.n, key_begin + wg_keys);
 
     // the first key block is requested before everything else: its latency is the longest
     bf16x8 a0[kMB][D / 16];
-    load_a<D>(kbase, g.ks[2], key_begin + wave * kWaveKeys, g.n, lane, a0);
+    if (SINGLE) load_a<D>(kbase, g.ks[2], key_begin + wave * kWaveKeys, g.n, lane, a0);
 
     if (g.value_prior) {
         float gm = 0.f;
@@ -519,35 +555,46 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
         // added to the (zero-initialised) scores with hardware float atomics, already
         // multiplied by the value prior.  The order of the additions over the tiles is not
         // fixed, so repeated calls may differ in the last bits.
-        const int rho0 = my_qt * S::ROWS;
-        load_tile(my_qt);
-        float ginv = 1.f;
-        if (g.value_prior)
-            ginv = 1.f / fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3]));
+        // wg_keys carries the number of parts a tile pair's key steps are cut into
+        const int nparts = wg_keys, part = blockIdx.x, pair = blockIdx.y;
         bf16x8 a1[kMB][D / 16];
-        auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb0) {
-            const int kb = kb0 + wave * kWaveKeys;
-            if (kb >= key_end) return;
-            float gam[kMB];
-            request_gamma(kb, gam);
-            f32x16 col[kMB];
-            zero(col);
-            tile_times_keys(a, kb, rho0, col);
+        for (int seg = 0; seg < 2; ++seg) {
+            const Segment sg = pair_segment(rm, S::ROWS, n_qtiles, pair, part, nparts, seg);
+            if (sg.qt < 0) break;
+            key_begin = sg.kbeg;
+            key_end = sg.kend;
+            if (key_begin >= key_end) continue;  // workgroup-uniform
+            const int rho0 = sg.qt * S::ROWS;
+            if (seg) __syncthreads();  // the previous tile is done with
+            load_a<D>(kbase, g.ks[2], key_begin + wave * kWaveKeys, g.n, lane, a0);
+            load_tile(sg.qt);
+            float ginv = 1.f;
+            if (g.value_prior)
+                ginv = 1.f / fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3]));
+            auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb0) {
+                const int kb = kb0 + wave * kWaveKeys;
+                if (kb >= key_end) return;
+                float gam[kMB];
+                request_gamma(kb, gam);
+                f32x16 col[kMB];
+                zero(col);
+                tile_times_keys(a, kb, rho0, col);
 #pragma unroll
-            for (int mb = 0; mb < kMB; ++mb) {
-                const float tot = fold16_over32(col[mb], lane);
-                const int j = acc_key(kb, mb, my_v, lane);
-                if ((lane & 1) == 0 && j < key_end)
-                    unsafeAtomicAdd(&scores[(int64_t)z * g.n + j], tot * (gam[mb] * ginv));
+                for (int mb = 0; mb < kMB; ++mb) {
+                    const float tot = fold16_over32(col[mb], lane);
+                    const int j = acc_key(kb, mb, my_v, lane);
+                    if ((lane & 1) == 0 && j < key_end)
+                        unsafeAtomicAdd(&scores[(int64_t)z * g.n + j], tot * (gam[mb] * ginv));
+                }
+            };
+            for (int kb0 = key_begin; kb0 < key_end; kb0 += 2 * kWgKeys) {
+                const int k1 = kb0 + kWgKeys, k2 = k1 + kWgKeys;
+                if (k1 < key_end) load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, g.n, lane, a1);
+                step(a0, kb0);
+                if (k1 >= key_end) break;
+                if (k2 < key_end) load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, g.n, lane, a0);
+                step(a1, k1);
             }
-        };
-        for (int kb0 = key_begin; kb0 < key_end; kb0 += 2 * kWgKeys) {
-            const int k1 = kb0 + kWgKeys, k2 = k1 + kWgKeys;
-            if (k1 < key_end) load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, g.n, lane, a1);
-            step(a0, kb0);
-            if (k1 >= key_end) break;
-            if (k2 < key_end) load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, g.n, lane, a0);
-            step(a1, k1);
         }
     }
 }
@@ -576,19 +623,19 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    dim3 g1(pl.nchunks, pl.n_qtiles, pl.Z);
+    dim3 g1(pl.nchunks, (pl.n_qtiles + 1) / 2, pl.Z);  // (part, tile pair, problem)
     hipLaunchKernelGGL((bf16_pass1_kernel<D, NB>), g1, dim3(256), S::bytes, st, g, pl.n_qtiles,
-                       pl.chunk_keys, pl.nchunks, lam_tab, partial);
+                       pl.nchunks, lam_tab, partial);
     if (mid) (void)hipEventRecord(mid, st);
     dim3 g2((g.n + pl.p2_keys - 1) / pl.p2_keys, pl.Z);
-    dim3 g2m(pl.nchunks, pl.n_qtiles, pl.Z);
+    dim3 g2m(pl.nchunks, (pl.n_qtiles + 1) / 2, pl.Z);
     if (pl.n_qtiles == 1)
         hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, true>), g2, dim3(256), S::bytes, st, g,
                            pl.n_qtiles, pl.p2_keys, pl.nchunks, lam_tab, partial, gamma, gbm,
                            pl.n_vtiles, scores);
     else
         hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, false>), g2m, dim3(256), S::bytes, st, g,
-                           pl.n_qtiles, pl.chunk_keys, pl.nchunks, lam_tab, partial, gamma, gbm,
+                           pl.n_qtiles, pl.nchunks, pl.nchunks, lam_tab, partial, gamma, gbm,
                            pl.n_vtiles, scores);
     return hipGetLastError();
 }
