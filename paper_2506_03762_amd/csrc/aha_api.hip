@@ -148,7 +148,7 @@ static PrefillPlan plan_prefill(const aha_params *p) {
     if (p->dtype != AHA_BF16) off = align_up(off + sizeof(float) * (size_t)pl.Z * rows, 256);
     pl.off_partial = off;
     if (p->dtype == AHA_BF16)
-        off = align_up(off + sizeof(float) * 2 * (size_t)pl.Z * rows * pl.nchunks, 256);
+        off = align_up(off + sizeof(float) * (size_t)pl.Z * rows * pl.nchunks, 256);
     pl.off_gamma = off;
     off = align_up(off + sizeof(float) * (size_t)pl.Z * n, 256);
     pl.off_gblockmax = off;

@@ -41,54 +41,67 @@ struct TileSmem {
 
 // Query tile -> LDS: rows rho0 .. rho0+ROWS of the KV head's flattened query
 // rows (zero beyond R), per row the log2-domain scale and the position, and per
-// 32-row block the largest and smallest position.  Two halves, so that other
-// loads can be put in flight between the global requests and their use.
+// 32-row block the largest and smallest position.  Request and commit are
+// separate so that every other load of the tile set-up (first key block, row
+// statistics, value-prior maxima) is in flight together with the tile: under
+// load a dependent round trip to memory costs several microseconds.
 template <int D, int NB>
 struct QTileRegs {
-    static constexpr int UT = TileSmem<D, NB>::ROWS * (D / 8) / 256;  // 16-byte chunks per thread
+    static constexpr int U = TileSmem<D, NB>::ROWS * (D / 8) / 256;  // 16-byte chunks per thread
     static_assert(TileSmem<D, NB>::ROWS * (D / 8) % 256 == 0, "tile chunks divide among 256 threads");
-    static constexpr int U = UT < 8 ? UT : 8;   // chunks per batch (bounds the registers held)
-    static constexpr int BATCHES = UT / U;
     u32x4 w[U];
+    unsigned valid;  // bit u: chunk u belongs to a real row (others are stored as zero)
 };
 
 template <int D, int NB>
 __device__ __forceinline__ void q_tile_request(const ScoreGeom &g, int b, int h, int rho0,
-                                               int batch, QTileRegs<D, NB> &t) {
-    constexpr int CPR = D / 8;
-    const int tid = threadIdx.x;
+                                               int tid, QTileRegs<D, NB> &t) {
+    constexpr int CPR = D / 8;        // 16-byte chunks per row
+    constexpr int STEP = 256 / CPR;   // rows between a thread's consecutive chunks
+    const int c = tid % CPR;
+    // flattened row rho = gi * r + ii (query head of the group, window row); one division
+    // for the first row, increments for the others
+    int rho = rho0 + tid / CPR;
+    int gi = rho / g.r, ii = rho - gi * g.r;
+    const int step_g = STEP / g.r, step_i = STEP % g.r;
+    const __bf16 *base = (const __bf16 *)g.q + b * g.qs[0] + (int64_t)h * g.G * g.qs[1] +
+                         (int64_t)(g.n - g.r) * g.qs[2] + c * 8;
+    // rows past the last one re-read the tile's first row (the tile has at least one real
+    // row), so the loads need no branches and are all issued back to back
+    const int gi0 = rho0 / g.r, ii0 = rho0 - gi0 * g.r;
+    t.valid = 0u;
 #pragma unroll
     for (int u = 0; u < QTileRegs<D, NB>::U; ++u) {
-        const int i = tid + (batch * QTileRegs<D, NB>::U + u) * 256;
-        const int rr = i / CPR, c = i % CPR, rho = rho0 + rr;
-        t.w[u] = u32x4{0u, 0u, 0u, 0u};
-        if (rho < g.R) {
-            const int gi = rho / g.r, ii = rho - gi * g.r;
-            const __bf16 *src = (const __bf16 *)g.q + b * g.qs[0] + (h * g.G + gi) * g.qs[1] +
-                                (int64_t)(g.n - g.r + ii) * g.qs[2] + c * 8;
-            t.w[u] = *(const u32x4 *)src;
+        const bool ok = rho < g.R;
+        t.valid |= ok ? 1u << u : 0u;
+        t.w[u] = *(const u32x4 *)(base + (ok ? gi : gi0) * g.qs[1] + (ok ? ii : ii0) * g.qs[2]);
+        rho += STEP;
+        gi += step_g;
+        ii += step_i;
+        if (ii >= g.r) {
+            ii -= g.r;
+            ++gi;
         }
     }
 }
 
 template <int D, int NB>
-__device__ __forceinline__ void q_tile_commit(int batch, const QTileRegs<D, NB> &t, __bf16 *sQ) {
+__device__ __forceinline__ void q_tile_commit(const QTileRegs<D, NB> &t, int tid, __bf16 *sQ) {
     using S = TileSmem<D, NB>;
     constexpr int CPR = D / 8;
-    const int tid = threadIdx.x;
 #pragma unroll
     for (int u = 0; u < QTileRegs<D, NB>::U; ++u) {
-        const int i = tid + (batch * QTileRegs<D, NB>::U + u) * 256;
-        *(u32x4 *)(sQ + (i / CPR) * S::LD + (i % CPR) * 8) = t.w[u];
+        const int i = tid + u * 256;
+        *(u32x4 *)(sQ + (i / CPR) * S::LD + (i % CPR) * 8) =
+            (t.valid >> u) & 1u ? t.w[u] : u32x4{0u, 0u, 0u, 0u};
     }
 }
 
 template <int D, int NB>
 __device__ __forceinline__ void q_tile_meta(const ScoreGeom &g, const RowMap &rm, int rho0,
-                                            const float *lam_tab, float *sLam, int *sPos,
+                                            int tid, const float *lam_tab, float *sLam, int *sPos,
                                             int *sBlk) {
     using S = TileSmem<D, NB>;
-    const int tid = threadIdx.x;
     for (int rr = tid; rr < S::ROWS; rr += 256) {
         const int rho = rho0 + rr;
         const bool ok = rho < g.R;
@@ -191,6 +204,21 @@ __device__ __forceinline__ void colsum_update(const f32x16 (&acc)[kMB], float la
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Workgroups are handed to the eight XCDs (each with an L2 of its own) round-robin by
+// their linear index.  The score kernels are launched on a one-dimensional grid of
+// 8 * ceil(total / 8) workgroups and work on the logical index returned here, which runs
+// contiguously over an XCD's share: the workgroups of one (batch, KV head) problem, which
+// read the same keys, query tiles and row statistics, then meet in one L2.
+// Indices >= total have no work.
+constexpr int kXcds = 8;
+__device__ __forceinline__ int xcd_contiguous_index(int total) {
+    const int per = (total + kXcds - 1) / kXcds;
+    return ((int)blockIdx.x % kXcds) * per + (int)blockIdx.x / kXcds;
+}
+static inline dim3 xcd_grid(int64_t total) {
+    return dim3((unsigned)(((total + kXcds - 1) / kXcds) * kXcds));
+}
+
 // Work split shared by pass 1 and by pass 2 in full accumulation.  Query tile `pair` is
 // teamed with tile T-1-pair: a tile of late rows sees many keys, its partner few, together
 // about the same as any other pair.  The 256-key steps of the pair (first tile's, then the
@@ -224,8 +252,8 @@ __device__ __forceinline__ Segment pair_segment(const RowMap &rm, int rows, int 
 // ---------------------------------------------------------------- pass 1 --
 template <int D, int NB>
 __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles, int nparts,
-                                                            const float *lam_tab,
-                                                            float2 *partial) {
+                                                            int total_wgs, const float *lam_tab,
+                                                            float *partial) {
     using S = TileSmem<D, NB>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __bf16 *sQ = (__bf16 *)smem;
@@ -234,7 +262,11 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
     int *sBlk = sPos + 2 * S::ROWS;
     float2 *sRed = (float2 *)smem;  // reuses the query tile after the main loop
 
-    const int part = blockIdx.x, pair = blockIdx.y, z = blockIdx.z;
+    // logical workgroup index -> (part, tile pair, problem)
+    const int wg = xcd_contiguous_index(total_wgs);
+    if (wg >= total_wgs) return;
+    const int npairs = (n_qtiles + 1) / 2;
+    const int part = wg % nparts, pair = (wg / nparts) % npairs, z = wg / (nparts * npairs);
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const RowMap rm{g.n, g.r, g.R};
@@ -244,11 +276,11 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
         const Segment sg = pair_segment(rm, S::ROWS, n_qtiles, pair, part, nparts, seg);
         if (sg.qt < 0) break;
         const int qt = sg.qt, rho0 = qt * S::ROWS;
-        float2 *my_partial = partial + ((int64_t)(z * n_qtiles + qt) * nparts + part) * S::ROWS;
+        float *my_partial = partial + ((int64_t)(z * n_qtiles + qt) * nparts + part) * S::ROWS;
         const int key_begin = sg.kbeg, key_end = sg.kend;
         if (key_begin >= key_end) {
             // none of this part's steps fall on this tile: leave neutral statistics
-            if (tid < S::ROWS) my_partial[tid] = make_float2(-INFINITY, 0.f);
+            if (tid < S::ROWS) my_partial[tid] = -INFINITY;
             continue;
         }
         if (seg) __syncthreads();  // the previous tile (and its reduction buffer) is done with
@@ -258,12 +290,9 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
         load_a<D>(kbase, g.ks[2], min(kb_first, g.n - 1), g.n, lane, a0);
         {
             QTileRegs<D, NB> qt_regs;
-#pragma unroll
-            for (int bt = 0; bt < QTileRegs<D, NB>::BATCHES; ++bt) {
-                q_tile_request<D, NB>(g, b, h, rho0, bt, qt_regs);
-                q_tile_commit<D, NB>(bt, qt_regs, sQ);
-            }
-            q_tile_meta<D, NB>(g, rm, rho0, lam_tab, sLam, sPos, sBlk);
+            q_tile_request<D, NB>(g, b, h, rho0, tid, qt_regs);
+            q_tile_meta<D, NB>(g, rm, rho0, tid, lam_tab, sLam, sPos, sBlk);
+            q_tile_commit<D, NB>(qt_regs, tid, sQ);
         }
         __syncthreads();
 
@@ -338,7 +367,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
                 const float2 e = sRed[w * S::ROWS + tid];
                 sum += e.y * fast_exp2(e.x - mref);
             }
-            my_partial[tid] = make_float2(M, sum);
+            my_partial[tid] = M + log2f(sum);  // -inf for a row that saw no key
         }
     }
 }
@@ -383,24 +412,30 @@ __device__ __forceinline__ float fold16_over32(const f32x16 &xv, int lane) {
     return d;
 }
 
-// Log2-sum-exp2 of one query row from the per-chunk (max, sum) pairs that pass 1 left
-// (16 independent loads in flight per batch).
-__device__ __forceinline__ float fold_chunks(const float2 *src, int stride, int nchunks) {
-    float M = -INFINITY, sum = 0.f;
-    for (int c0 = 0; c0 < nchunks; c0 += 16) {
-        float2 e[16];
+// Log2-sum-exp2 of one query row from the per-chunk log2-sum-exp2 values that pass 1 left.
+// A batch of values is requested at once (request), so that it travels together with the
+// other loads of the tile set-up, and merged later (merge) into the running (M, sum) with
+// sum = sum over chunks of exp2(value - M).
+template <int BATCH>
+__device__ __forceinline__ void chunk_request(const float *src, int stride, int c0, int nchunks,
+                                              float (&e)[BATCH]) {
+    // entries past the last chunk re-read it (branch-free, back-to-back loads) and are
+    // neutralised in the merge
 #pragma unroll
-        for (int t = 0; t < 16; ++t)
-            e[t] = c0 + t < nchunks ? src[(int64_t)(c0 + t) * stride] : make_float2(-INFINITY, 0.f);
+    for (int t = 0; t < BATCH; ++t) e[t] = src[(int64_t)min(c0 + t, nchunks - 1) * stride];
+}
+template <int BATCH>
+__device__ __forceinline__ void chunk_merge(const float (&e)[BATCH], int count, float &M,
+                                            float &sum) {
+    float bm = -INFINITY;
 #pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            const float mn = fmaxf(M, e[t].x);
-            const float mref = mn == -INFINITY ? 0.f : mn;
-            sum = sum * fast_exp2(M - mref) + e[t].y * fast_exp2(e[t].x - mref);
-            M = mn;
-        }
-    }
-    return M + log2f(sum);
+    for (int t = 0; t < BATCH; ++t) bm = fmaxf(bm, t < count ? e[t] : -INFINITY);
+    const float mn = fmaxf(M, bm);
+    const float mref = mn == -INFINITY ? 0.f : mn;
+    sum *= fast_exp2(M - mref);
+#pragma unroll
+    for (int t = 0; t < BATCH; ++t) sum += t < count ? fast_exp2(e[t] - mref) : 0.f;
+    M = mn;
 }
 
 // SINGLE: all observed rows fit one query tile (the windowed score).  The tile is loaded
@@ -410,9 +445,9 @@ __device__ __forceinline__ float fold_chunks(const float2 *src, int stride, int 
 // tiles' contributions meet in the scores through float atomics.
 template <int D, int NB, bool SINGLE>
 __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_qtiles,
-                                                            int wg_keys, int nchunks,
+                                                            int total_wgs, int wg_keys, int nchunks,
                                                             const float *lam_tab,
-                                                            const float2 *partial,
+                                                            const float *partial,
                                                             const float *gamma,
                                                             const float *gblockmax,
                                                             int n_vtiles, float *scores) {
@@ -425,52 +460,77 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     int *sBlk = (int *)(sL + S::ROWS);
     __shared__ float s_gmax[4];
 
-    const int z = SINGLE ? blockIdx.y : blockIdx.z;
+    // logical workgroup index -> SINGLE: (key range, problem); else (part, tile pair, problem)
+    const int wg = xcd_contiguous_index(total_wgs);
+    if (wg >= total_wgs) return;
+    const int per_problem = total_wgs / (g.batch * g.Hkv);
+    const int z = wg / per_problem, wg_in_z = wg % per_problem;
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const RowMap rm{g.n, g.r, g.R};
     const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
     // SINGLE: the workgroup's key range; otherwise ranges come per tile segment (below)
-    int key_begin = blockIdx.x * wg_keys;
+    int key_begin = wg_in_z * wg_keys;
     int key_end = min(g.n, key_begin + wg_keys);
 
     // the first key block is requested before everything else: its latency is the longest
     bf16x8 a0[kMB][D / 16];
     if (SINGLE) load_a<D>(kbase, g.ks[2], key_begin + wave * kWaveKeys, g.n, lane, a0);
 
-    if (g.value_prior) {
-        float gm = 0.f;
-        for (int t = tid; t < n_vtiles; t += 256) gm = fmaxf(gm, gblockmax[z * n_vtiles + t]);
-        gm = wave_max(gm);
-        if (lane == 0) s_gmax[wave] = gm;
-    }
+    // this thread's share of the value prior's per-tile maxima (requested here, reduced
+    // during the first tile set-up)
+    float gm = (g.value_prior && tid < n_vtiles) ? gblockmax[z * n_vtiles + tid] : 0.f;
+    bool gmax_pending = g.value_prior;
     float lamr[NB], Lr[NB];  // scale and log-sum-exp of this lane's query column, per block
 
     // query tile qt -> LDS, with the log-sum-exp of its rows folded from pass 1's chunks
+    static_assert(S::ROWS <= 256, "one thread folds the statistics of one tile row");
     auto load_tile = [&](int qt) {
         const int rho0 = qt * S::ROWS;
+        // Full accumulation sets up a tile per segment: there the thread index and the chunk
+        // count go through an opaque move, so that the set-up's address arithmetic is
+        // redone per tile instead of being kept (and spilled) across the main loop, where
+        // a reload of a spilled address would have to wait for every load in flight.
+        int tid = threadIdx.x, nchunks_t = nchunks;
+        if (!SINGLE) {
+            asm volatile("" : "+v"(tid));
+            asm volatile("" : "+s"(nchunks_t));
+        }
         {
-            // tile rows and chunk statistics are requested together, then used
+            // tile rows, chunk statistics and scales are requested together, then used
             QTileRegs<D, NB> qt_regs;
-            q_tile_request<D, NB>(g, b, h, rho0, 0, qt_regs);
-            for (int rr = tid; rr < S::ROWS; rr += 256)
-                sL[rr] = rho0 + rr < g.R
-                             ? fold_chunks(partial + ((int64_t)(z * n_qtiles + qt) * nchunks) * S::ROWS + rr,
-                                           S::ROWS, nchunks)
-                             : INFINITY;
-            q_tile_commit<D, NB>(0, qt_regs, sQ);
-#pragma unroll
-            for (int bt = 1; bt < QTileRegs<D, NB>::BATCHES; ++bt) {
-                q_tile_request<D, NB>(g, b, h, rho0, bt, qt_regs);
-                q_tile_commit<D, NB>(bt, qt_regs, sQ);
+            // (windowed mode has up to 64 chunks per row; full accumulation a few, and less
+            // room in the register file at this point)
+            constexpr int kChunkBatch = SINGLE ? 64 : 8;
+            float ch[kChunkBatch];
+            const bool row_ok = tid < S::ROWS && rho0 + tid < g.R;
+            // (threads without a row of their own read row 0's statistics and drop them)
+            const float *psrc = partial + ((int64_t)(z * n_qtiles + qt) * nchunks_t) * S::ROWS +
+                                 (tid < S::ROWS ? tid : 0);
+            q_tile_request<D, NB>(g, b, h, rho0, tid, qt_regs);
+            chunk_request(psrc, S::ROWS, 0, nchunks_t, ch);
+            q_tile_meta<D, NB>(g, rm, rho0, tid, lam_tab, sLam, sPos, sBlk);
+            if (gmax_pending) {
+                for (int t = tid + 256; t < n_vtiles; t += 256)
+                    gm = fmaxf(gm, gblockmax[z * n_vtiles + t]);
+                gm = wave_max(gm);
+                if (lane == 0) s_gmax[wave] = gm;
+                gmax_pending = false;
             }
-            q_tile_meta<D, NB>(g, rm, rho0, lam_tab, sLam, sPos, sBlk);
+            float M = -INFINITY, sum = 0.f;
+            chunk_merge(ch, nchunks_t, M, sum);
+            for (int c0 = kChunkBatch; c0 < nchunks_t; c0 += kChunkBatch) {
+                chunk_request(psrc, S::ROWS, c0, nchunks_t, ch);
+                chunk_merge(ch, nchunks_t - c0, M, sum);
+            }
+            if (tid < S::ROWS) sL[tid] = row_ok ? M + log2f(sum) : INFINITY;
+            q_tile_commit<D, NB>(qt_regs, tid, sQ);
         }
         __syncthreads();
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            lamr[nb] = sLam[nb * 32 + (lane & 31)];
-            Lr[nb] = sL[nb * 32 + (lane & 31)];
+            lamr[nb] = sLam[nb * 32 + (tid & 31)];
+            Lr[nb] = sL[nb * 32 + (tid & 31)];
         }
     };
     // this wave's 64 keys (A fragments a) against the query tile in LDS
@@ -556,7 +616,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
         // multiplied by the value prior.  The order of the additions over the tiles is not
         // fixed, so repeated calls may differ in the last bits.
         // wg_keys carries the number of parts a tile pair's key steps are cut into
-        const int nparts = wg_keys, part = blockIdx.x, pair = blockIdx.y;
+        const int nparts = wg_keys, part = wg_in_z % nparts, pair = wg_in_z / nparts;
         bf16x8 a1[kMB][D / 16];
         for (int seg = 0; seg < 2; ++seg) {
             const Segment sg = pair_segment(rm, S::ROWS, n_qtiles, pair, part, nparts, seg);
@@ -605,7 +665,7 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
                            hipStream_t st, hipEvent_t mid) {
     using S = TileSmem<D, NB>;
     char *w = (char *)ws;
-    float2 *partial = (float2 *)(w + pl.off_partial);
+    float *partial = (float *)(w + pl.off_partial);
     const float *gamma = (const float *)(w + pl.off_gamma);
     const float *gbm = (const float *)(w + pl.off_gblockmax);
     const float *lam_tab = (const float *)(w + pl.off_lam);
@@ -623,20 +683,21 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    dim3 g1(pl.nchunks, (pl.n_qtiles + 1) / 2, pl.Z);  // (part, tile pair, problem)
-    hipLaunchKernelGGL((bf16_pass1_kernel<D, NB>), g1, dim3(256), S::bytes, st, g, pl.n_qtiles,
-                       pl.nchunks, lam_tab, partial);
+    // (part, tile pair, problem), part fastest
+    const int64_t wgs1 = (int64_t)pl.nchunks * ((pl.n_qtiles + 1) / 2) * pl.Z;
+    // windowed pass 2: (key range, problem)
+    const int64_t wgs2 = (int64_t)((g.n + pl.p2_keys - 1) / pl.p2_keys) * pl.Z;
+    hipLaunchKernelGGL((bf16_pass1_kernel<D, NB>), xcd_grid(wgs1), dim3(256), S::bytes, st, g,
+                       pl.n_qtiles, pl.nchunks, (int)wgs1, lam_tab, partial);
     if (mid) (void)hipEventRecord(mid, st);
-    dim3 g2((g.n + pl.p2_keys - 1) / pl.p2_keys, pl.Z);
-    dim3 g2m(pl.nchunks, (pl.n_qtiles + 1) / 2, pl.Z);
     if (pl.n_qtiles == 1)
-        hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, true>), g2, dim3(256), S::bytes, st, g,
-                           pl.n_qtiles, pl.p2_keys, pl.nchunks, lam_tab, partial, gamma, gbm,
-                           pl.n_vtiles, scores);
+        hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, true>), xcd_grid(wgs2), dim3(256), S::bytes,
+                           st, g, pl.n_qtiles, (int)wgs2, pl.p2_keys, pl.nchunks, lam_tab, partial,
+                           gamma, gbm, pl.n_vtiles, scores);
     else
-        hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, false>), g2m, dim3(256), S::bytes, st, g,
-                           pl.n_qtiles, pl.nchunks, pl.nchunks, lam_tab, partial, gamma, gbm,
-                           pl.n_vtiles, scores);
+        hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, false>), xcd_grid(wgs1), dim3(256), S::bytes,
+                           st, g, pl.n_qtiles, (int)wgs1, pl.nchunks, pl.nchunks, lam_tab, partial,
+                           gamma, gbm, pl.n_vtiles, scores);
     return hipGetLastError();
 }
 
