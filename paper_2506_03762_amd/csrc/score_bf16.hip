@@ -221,9 +221,13 @@ static inline dim3 xcd_grid(int64_t total) {
 
 // Work split shared by pass 1 and by pass 2 in full accumulation.  Query tile `pair` is
 // teamed with tile T-1-pair: a tile of late rows sees many keys, its partner few, together
-// about the same as any other pair.  The 256-key steps of the pair (first tile's, then the
-// partner's) are cut into `nparts` equal ranges; segment `seg` (0: first tile, 1: partner)
-// of a workgroup is the part of its range that falls on that tile.
+// about the same as any other pair.  The pair's work is laid out on a line - the first
+// tile's 256-key steps, the set-up of the partner (loading a query tile costs about one
+// step; every workgroup pays one set-up anyway, only a second one counts), the partner's
+// steps - and the line is cut into `nparts` equal ranges.  Segment `seg` (0: first tile,
+// 1: partner) of a workgroup is the part of its range that falls on that tile's steps.
+// A single tile (windowed scores, or the middle tile of an odd count) is cut into equal
+// ranges of steps.
 struct Segment {
     int qt;          // query tile, -1: no such segment
     int kbeg, kend;  // keys [kbeg, kend); empty when kbeg >= kend
@@ -231,20 +235,22 @@ struct Segment {
 __device__ __forceinline__ Segment pair_segment(const RowMap &rm, int rows, int T, int pair,
                                                 int part, int nparts, int seg) {
     const int tA = pair, tB = T - 1 - pair;
+    const bool two = tB != tA;
     const int endA = rm.max_pos(tA * rows, (tA + 1) * rows) + 1;
-    const int endB = tB != tA ? rm.max_pos(tB * rows, (tB + 1) * rows) + 1 : 0;
+    const int endB = two ? rm.max_pos(tB * rows, (tB + 1) * rows) + 1 : 0;
     const int sA = (endA + kWgKeys - 1) / kWgKeys, sB = (endB + kWgKeys - 1) / kWgKeys;
-    const int total = sA + sB, per = (total + nparts - 1) / nparts;
-    const int s0 = part * per, s1 = min(total, s0 + per);
+    // positions on the line: first tile's steps start at oA, the partner's at oB
+    const int oA = 0, oB = sA + 1, V = two ? sA + sB + 1 : sA;
+    const int v0 = (int)((int64_t)part * V / nparts), v1 = (int)((int64_t)(part + 1) * V / nparts);
     Segment r;
     if (seg == 0) {
         r.qt = tA;
-        r.kbeg = min(s0, sA) * kWgKeys;
-        r.kend = min(endA, min(s1, sA) * kWgKeys);
+        r.kbeg = (max(v0, oA) - oA) * kWgKeys;
+        r.kend = min(endA, (min(v1, oA + sA) - oA) * kWgKeys);
     } else {
-        r.qt = tB != tA ? tB : -1;
-        r.kbeg = (max(s0, sA) - sA) * kWgKeys;
-        r.kend = min(endB, (max(s1, sA) - sA) * kWgKeys);
+        r.qt = two ? tB : -1;
+        r.kbeg = (max(v0, oB) - oB) * kWgKeys;
+        r.kend = min(endB, (min(v1, oB + sB) - oB) * kWgKeys);
     }
     return r;
 }
@@ -331,12 +337,16 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
                     stats_update<false>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb]);
             }
         };
+        // The prefetch is issued unconditionally (past the range it re-reads clamped rows
+        // that are never used): behind a branch the compiler can no longer tell how many
+        // loads are in flight and would wait for the prefetch itself before the current
+        // step.
         for (int kb = kb_first; kb < key_end; kb += 2 * kWgKeys) {
             const int k1 = kb + kWgKeys, k2 = k1 + kWgKeys;
-            if (k1 < key_end) load_a<D>(kbase, g.ks[2], k1, g.n, lane, a1);
+            load_a<D>(kbase, g.ks[2], k1, g.n, lane, a1);
             step(a0, kb);
             if (k1 >= key_end) break;
-            if (k2 < key_end) load_a<D>(kbase, g.ks[2], k2, g.n, lane, a0);
+            load_a<D>(kbase, g.ks[2], k2, g.n, lane, a0);
             step(a1, k1);
         }
 
@@ -601,12 +611,13 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             tile_times_keys(a, kb, 0, col);
             write_scores(col, kb, gam);
         };
+        // (unconditional prefetch, as in pass 1)
         for (int kb0 = key_begin; kb0 < key_end; kb0 += 2 * kWgKeys) {
             const int k1 = kb0 + kWgKeys, k2 = k1 + kWgKeys;
-            if (k1 < key_end) load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, g.n, lane, a1);
+            load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, g.n, lane, a1);
             step(a0, kb0);
             if (k1 >= key_end) break;
-            if (k2 < key_end) load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, g.n, lane, a0);
+            load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, g.n, lane, a0);
             step(a1, k1);
         }
     } else {
@@ -649,10 +660,10 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             };
             for (int kb0 = key_begin; kb0 < key_end; kb0 += 2 * kWgKeys) {
                 const int k1 = kb0 + kWgKeys, k2 = k1 + kWgKeys;
-                if (k1 < key_end) load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, g.n, lane, a1);
+                load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, g.n, lane, a1);
                 step(a0, kb0);
                 if (k1 >= key_end) break;
-                if (k2 < key_end) load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, g.n, lane, a0);
+                load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, g.n, lane, a0);
                 step(a1, k1);
             }
         }
