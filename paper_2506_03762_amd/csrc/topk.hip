@@ -17,6 +17,8 @@
 // An ordered compaction (one block-wide scan) then writes the indices in
 // ascending order.  Sequences too long for the register file (more than 64
 // keys per thread) re-read the scores from memory in every pass.
+#include <type_traits>
+
 #include "aha_dev.h"
 #include "aha_host.h"
 
@@ -80,6 +82,10 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
     if (k == 0) return;
 
     constexpr int R = ITEMS > 0 ? ITEMS : 1;
+    // one bit per register-resident key
+    using Mask = std::conditional_t<(ITEMS > 32), unsigned long long, unsigned>;
+    auto lowest = [](Mask m) { return sizeof(Mask) == 8 ? __ffsll((unsigned long long)m) - 1 : __ffs((unsigned)m) - 1; };
+    auto popcount = [](Mask m) { return sizeof(Mask) == 8 ? __popcll((unsigned long long)m) : __popc((unsigned)m); };
     const int ipt = ITEMS > 0 ? ITEMS : (n_cand + kTopkThreads - 1) / kTopkThreads;
     const int j0 = min(tid * ipt, n_cand), j1 = min(j0 + ipt, n_cand);
     uint32_t key[R];
@@ -164,12 +170,31 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
             // 3a. exact rank among the keys of the threshold bin
             if (tid == 0) sm.ncand = 0;
             __syncthreads();
-            for_keys([&](uint32_t u, int j) {
-                if (((u - kmin) >> sh) == bin) {
-                    const int slot = atomicAdd(&sm.ncand, 1);
-                    sm.cand[slot] = ((unsigned long long)u << 32) | (uint32_t)(~j);
+            if (ITEMS > 0) {
+                // mark the thread's keys of that bin, reserve their slots with one atomic
+                Mask cm = 0;
+#pragma unroll
+                for (int t = 0; t < R; ++t)
+                    cm |= (Mask)(key[t] != 0u && ((key[t] - kmin) >> sh) == bin) << t;
+                if (cm) {
+                    int slot = atomicAdd(&sm.ncand, popcount(cm));
+                    while (cm) {
+                        const int t = lowest(cm);
+                        cm &= cm - 1;
+                        uint32_t u = 0;
+#pragma unroll
+                        for (int q = 0; q < R; ++q) u = q == t ? key[q] : u;
+                        sm.cand[slot++] = ((unsigned long long)u << 32) | (uint32_t)(~(j0 + t));
+                    }
                 }
-            });
+            } else {
+                for_keys([&](uint32_t u, int j) {
+                    if (((u - kmin) >> sh) == bin) {
+                        const int slot = atomicAdd(&sm.ncand, 1);
+                        sm.cand[slot] = ((unsigned long long)u << 32) | (uint32_t)(~j);
+                    }
+                });
+            }
             __syncthreads();
             if (tid < nc) {
                 const unsigned long long mine = sm.cand[tid];
@@ -212,12 +237,36 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
 
     // ordered compaction
     int gt = 0, eq = 0;
-    for_keys([&](uint32_t u, int) { gt += u > T; eq += u == T; });
-    int gi = gt, ei = eq;  // inclusive scans over the wave
+    Mask gtm = 0, eqm = 0;  // register-resident keys above / equal to T (padding keys are 0 < T)
+    if (ITEMS > 0) {
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int a = __shfl_up(gi, o), b = __shfl_up(ei, o);
-        if (lane >= o) { gi += a; ei += b; }
+        for (int t = 0; t < R; ++t) {
+            gtm |= (Mask)(key[t] > T) << t;
+            eqm |= (Mask)(key[t] == T) << t;
+        }
+        gt = popcount(gtm);
+        eq = popcount(eqm);
+    } else {
+        for_keys([&](uint32_t u, int) { gt += u > T; eq += u == T; });
+    }
+    // inclusive scans over the wave; with keys in registers both counts (at most 64 per
+    // thread, 4096 per wave) share one word
+    int gi = gt, ei = eq;
+    if (ITEMS > 0) {
+        int pk = gt | (eq << 16);
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int a = __shfl_up(pk, o);
+            if (lane >= o) pk += a;
+        }
+        gi = pk & 0xffff;
+        ei = pk >> 16;
+    } else {
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int a = __shfl_up(gi, o), b = __shfl_up(ei, o);
+            if (lane >= o) { gi += a; ei += b; }
+        }
     }
     __syncthreads();
     if (lane == 63) { sm.scan[0][wave] = gi; sm.scan[1][wave] = ei; }
@@ -234,19 +283,36 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
     // thread writes its own
     int *stage = &sm.hist[0][0];
     const bool staged = k <= kHistCopies * kBins;
-    int32_t *dst = staged ? stage : out;
-    for_keys([&](uint32_t u, int j) {
-        if (u > T) {
-            dst[gtc + min(eqc, need)] = j;
-            ++gtc;
-        } else if (u == T) {
-            if (eqc < need) dst[gtc + eqc] = j;
-            ++eqc;
+    auto emit = [&](auto *dst) {
+        if (ITEMS > 0) {
+            // selected keys of this thread: all above T and, among those equal to T, the
+            // ones within the first `need` of the problem; visited in position order
+            Mask sel = gtm;
+            int quota = need - eqc;
+            for (Mask m = eqm; m != 0 && quota > 0; m &= m - 1, --quota) sel |= m & (~m + 1);
+            int o = gtc + min(eqc, need);
+            while (sel) {
+                dst[o++] = j0 + lowest(sel);
+                sel &= sel - 1;
+            }
+        } else {
+            for_keys([&](uint32_t u, int j) {
+                if (u > T) {
+                    dst[gtc + min(eqc, need)] = j;
+                    ++gtc;
+                } else if (u == T) {
+                    if (eqc < need) dst[gtc + eqc] = j;
+                    ++eqc;
+                }
+            });
         }
-    });
+    };
     if (staged) {
+        emit(stage);
         __syncthreads();
         for (int t = tid; t < k; t += kTopkThreads) out[t] = stage[t];
+    } else {
+        emit(out);
     }
 }
 
