@@ -169,7 +169,7 @@ static DecodePlan plan_decode(const aha_params *p) {
         nsplit = (256 + Z - 1) / Z;
         const int max_by_size = (live + 63) / 64;  // at least 64 slots per workgroup
         if (nsplit > max_by_size) nsplit = max_by_size;
-        if (nsplit > 64) nsplit = 64;
+        if (nsplit > kMaxDecodeSplit) nsplit = kMaxDecodeSplit;
     }
     pl.nsplit = nsplit < 1 ? 1 : nsplit;
     pl.sps = (live + pl.nsplit - 1) / pl.nsplit;

@@ -69,6 +69,8 @@ struct DecodeGeom {
 };
 // With few (batch, KV head) problems the slots of a head are split over nsplit workgroups
 // (two launches, partials in the workspace); otherwise one workgroup handles a head.
+constexpr int kMaxDecodeSplit = 64;  // most workgroups a head's slots are split over
+
 struct DecodePlan {
     int nsplit;      // 1: single-launch path
     int sps;         // slots per split

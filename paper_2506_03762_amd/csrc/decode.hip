@@ -222,6 +222,7 @@ template <int ESIZE, int D, int G>
 __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsplit, int sps,
                                                            float *ws_w, float *ws_part) {
     constexpr int CH = 16 / ESIZE, LPR = D / CH, RP = 256 / LPR, ROWB = D * ESIZE;
+    constexpr int PF = 6;  // sweeps of the range whose K and V rows are requested at the start
     extern __shared__ __attribute__((aligned(16))) float dsm[];
     float *s_p = dsm;                 // [G][sps] dots, then unnormalised probabilities
     float *s_o = dsm + G * sps;       // [4 waves][G][D]
@@ -230,28 +231,42 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
     const int split = blockIdx.x, z = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int live = g.budget + 1;
-    const int fs = g.free_slot[z];
     const int s0 = split * sps, s1 = min(live, s0 + sps);
     const int rg = tid / LPR, sub = tid % LPR;
     char *kcz = (char *)g.kc + (int64_t)z * g.slots * ROWB;
     char *vcz = (char *)g.vc + (int64_t)z * g.slots * ROWB;
-    const char *knew = (const char *)g.k_new + (int64_t)z * ROWB;
-    const char *vnew = (const char *)g.v_new + (int64_t)z * ROWB;
 
+    // With so few workgroups the step is bound by memory latency, not bandwidth: everything
+    // the first PF sweeps need is requested before anything is used - the free slot, the
+    // queries, the new token's rows, the cached K and V rows (the row of the free slot is
+    // read like any other and replaced afterwards) - so that the kernel waits for memory
+    // once instead of once per dependent step.
+    const int fs = g.free_slot[z];
+    u32x4 qw[G];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi)
+        qw[gi] = *(const u32x4 *)((const char *)g.q + ((int64_t)(b * g.Hq + h * G + gi)) * ROWB + sub * 16);
+    const u32x4 knw = *(const u32x4 *)((const char *)g.k_new + (int64_t)z * ROWB + sub * 16);
+    const u32x4 vnw = *(const u32x4 *)((const char *)g.v_new + (int64_t)z * ROWB + sub * 16);
+    u32x4 kpf[PF], vpf[PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+        const int sc = min(s0 + rg + u * RP, s1 - 1);  // past the range: a row that is there
+        kpf[u] = *(const u32x4 *)(kcz + (int64_t)sc * ROWB + sub * 16);
+        vpf[u] = *(const u32x4 *)(vcz + (int64_t)sc * ROWB + sub * 16);
+    }
     float qr[G][CH];
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) {
-        const char *qp = (const char *)g.q + ((int64_t)(b * g.Hq + h * G + gi)) * ROWB + sub * 16;
-        unpack<ESIZE>(*(const u32x4 *)qp, qr[gi]);
-    }
+    for (int gi = 0; gi < G; ++gi) unpack<ESIZE>(qw[gi], qr[gi]);
+
     float mloc[G];
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) mloc[gi] = -INFINITY;
-#pragma unroll 4
-    for (int s = s0 + rg; s < s1; s += RP) {
-        const char *src = (s == fs) ? knew : kcz + (int64_t)s * ROWB;
-        const u32x4 kw = *(const u32x4 *)(src + sub * 16);
-        if (s == fs) *(u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16) = kw;
+    auto dots = [&](int s, u32x4 kw) {
+        if (s == fs) {
+            kw = knw;
+            *(u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16) = kw;
+        }
         float kf[CH];
         unpack<ESIZE>(kw, kf);
 #pragma unroll
@@ -267,7 +282,15 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
             }
             mloc[gi] = fmaxf(mloc[gi], w);
         }
+    };
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+        const int s = s0 + rg + u * RP;
+        if (s < s1) dots(s, kpf[u]);
     }
+#pragma unroll 4
+    for (int s = s0 + rg + PF * RP; s < s1; s += RP)
+        dots(s, *(const u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16));
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) {
         const float m = wave_max(mloc[gi]);
@@ -302,11 +325,11 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
     for (int gi = 0; gi < G; ++gi)
 #pragma unroll
         for (int c = 0; c < CH; ++c) o[gi][c] = 0.f;
-#pragma unroll 4
-    for (int s = s0 + rg; s < s1; s += RP) {
-        const char *src = (s == fs) ? vnew : vcz + (int64_t)s * ROWB;
-        const u32x4 vw = *(const u32x4 *)(src + sub * 16);
-        if (s == fs) *(u32x4 *)(vcz + (int64_t)s * ROWB + sub * 16) = vw;
+    auto weigh = [&](int s, u32x4 vw) {
+        if (s == fs) {
+            vw = vnw;
+            *(u32x4 *)(vcz + (int64_t)s * ROWB + sub * 16) = vw;
+        }
         float vf[CH];
         unpack<ESIZE>(vw, vf);
 #pragma unroll
@@ -315,7 +338,15 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
 #pragma unroll
             for (int c = 0; c < CH; ++c) o[gi][c] = fmaf(p, vf[c], o[gi][c]);
         }
+    };
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+        const int s = s0 + rg + u * RP;
+        if (s < s1) weigh(s, vpf[u]);
     }
+#pragma unroll 4
+    for (int s = s0 + rg + PF * RP; s < s1; s += RP)
+        weigh(s, *(const u32x4 *)(vcz + (int64_t)s * ROWB + sub * 16));
 #pragma unroll
     for (int gi = 0; gi < G; ++gi)
 #pragma unroll
@@ -346,14 +377,15 @@ template <int ESIZE, int D, int G>
 __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom g, int nsplit,
                                                            const float *ws_w,
                                                            const float *ws_part) {
-    __shared__ float s_mx[G], s_scale[64][G];
+    static_assert(G * D <= kMergeThreads, "one output element per thread");
+    static_assert(kMaxDecodeSplit * G <= kMergeThreads, "one (split, head) statistic per thread");
+    __shared__ float s_pm[kMaxDecodeSplit][G], s_pz[kMaxDecodeSplit][G];
     __shared__ float s_red[kMergeThreads / 64][G];
     __shared__ unsigned long long s_key[kMergeThreads / 64];
     __shared__ int s_victim;
     const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int live = g.budget + 1;
-    const int fs = g.free_slot[z];
     float *fcz = g.fc + (int64_t)z * g.slots;
     int32_t *posz = g.pos + (int64_t)z * g.slots;
     const float *part = ws_part + (int64_t)z * nsplit * G * (D + 2);
@@ -362,57 +394,20 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
                                                        g.logical_pos, g.budget, D)
                                   : row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor,
                                                    g.logical_pos, g.budget, D);
-    // maxima of the splits: one (split, head) pair per thread, then a short LDS fold
-    __shared__ float s_pm[64][G], s_pz[64][G];
-    for (int t = tid; t < nsplit * G; t += kMergeThreads) {
-        const int sp = t / G, gi = t % G;
-        s_pm[sp][gi] = part[(sp * G + gi) * (D + 2) + D];
-        s_pz[sp][gi] = part[(sp * G + gi) * (D + 2) + D + 1];
+    constexpr int NT = kMergeThreads, U = 4, XB = 32;
+
+    // Latency-bound like stage 1: every first-use load is requested here, before any result
+    // is needed - the free slot, the splits' statistics, the first batch of stored dots with
+    // their scores and positions (the free slot's stale entries are read like any other and
+    // replaced afterwards), and this thread's output element of the first XB splits.
+    const int fs = g.free_slot[z];
+    float my_pm = -INFINITY, my_pz = 0.f;
+    if (tid < nsplit * G) {
+        my_pm = part[tid * (D + 2) + D];  // tid = split * G + head
+        my_pz = part[tid * (D + 2) + D + 1];
     }
-    __syncthreads();
-    if (tid < G) {
-        float m = -INFINITY;
-        for (int sp = 0; sp < nsplit; ++sp) m = fmaxf(m, s_pm[sp][tid]);
-        s_mx[tid] = m;
-    }
-    __syncthreads();
-    for (int t = tid; t < nsplit * G; t += kMergeThreads) {
-        const int sp = t / G, gi = t % G;
-        s_scale[sp][gi] = exp2f((s_pm[sp][gi] - s_mx[gi]) * c_out);
-    }
-    __syncthreads();
-    for (int t = tid; t < G * D; t += kMergeThreads) {
-        const int gi = t / D, c = t % D;
-        float num = 0.f, den = 0.f;
-        for (int sp0 = 0; sp0 < nsplit; sp0 += 8) {
-            float x[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                x[u] = sp0 + u < nsplit ? part[((sp0 + u) * G + gi) * (D + 2) + c] : 0.f;
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (sp0 + u < nsplit) {
-                    const float sc = s_scale[sp0 + u][gi];
-                    num = fmaf(x[u], sc, num);
-                    den = fmaf(s_pz[sp0 + u][gi], sc, den);
-                }
-        }
-        const float v = num / den;
-        const int64_t oi = ((int64_t)(b * g.Hq + h * G + gi)) * D + c;
-        if constexpr (ESIZE == 2)
-            ((uint16_t *)g.out)[oi] = (uint16_t)f32_to_bf16_rne(v);
-        else
-            ((float *)g.out)[oi] = v;
-    }
-    // score softmax over all live slots, from the stored raw dots; four slots per thread
-    // and batch are fetched together so that the loads overlap
-    constexpr int NT = kMergeThreads, U = 4;
-    float mx[G], zs[G];
-#pragma unroll
-    for (int gi = 0; gi < G; ++gi) { mx[gi] = s_mx[gi]; zs[gi] = 0.f; }
     float wr[U][G], fr[U];
     int pr[U];
-    const bool one_batch = live <= U * NT;  // then the values stay in registers for pass two
     auto fetch = [&](int base) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -421,12 +416,64 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
 #pragma unroll
             for (int gi = 0; gi < G; ++gi)
                 wr[u][gi] = ok ? ws_w[((int64_t)z * G + gi) * live + s] : -INFINITY;
-            fr[u] = ok && s != fs ? fcz[s] : 0.f;
-            pr[u] = ok ? (s == fs ? g.logical_pos - 1 : posz[s]) : 0x7fffffff;
+            fr[u] = ok ? fcz[s] : 0.f;
+            pr[u] = ok ? posz[s] : 0x7fffffff;
         }
     };
+    auto patch_free_slot = [&](int base) {  // the new token: score 0, position logical_pos - 1
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (base + tid + u * NT == fs) {
+                fr[u] = 0.f;
+                pr[u] = g.logical_pos - 1;
+            }
+    };
+    fetch(0);
+    const int ogi = tid / D, oc = tid % D;  // this thread's output element (tid < G * D)
+    float x[XB];
+#pragma unroll
+    for (int u = 0; u < XB; ++u)
+        x[u] = (tid < G * D && u < nsplit) ? part[(u * G + ogi) * (D + 2) + oc] : 0.f;
+
+    if (tid < nsplit * G) {
+        s_pm[tid / G][tid % G] = my_pm;
+        s_pz[tid / G][tid % G] = my_pz;
+    }
+    __syncthreads();
+    // every wave folds the splits' maxima by itself (one split per lane)
+    float mx[G];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) mx[gi] = wave_max(lane < nsplit ? s_pm[lane][gi] : -INFINITY);
+
+    if (tid < G * D) {
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int u = 0; u < XB; ++u)
+            if (u < nsplit) {
+                const float sc = exp2f((s_pm[u][ogi] - mx[ogi]) * c_out);
+                num = fmaf(x[u], sc, num);
+                den = fmaf(s_pz[u][ogi], sc, den);
+            }
+        for (int sp = XB; sp < nsplit; ++sp) {
+            const float sc = exp2f((s_pm[sp][ogi] - mx[ogi]) * c_out);
+            num = fmaf(part[(sp * G + ogi) * (D + 2) + oc], sc, num);
+            den = fmaf(s_pz[sp][ogi], sc, den);
+        }
+        const float v = num / den;
+        const int64_t oi = ((int64_t)(b * g.Hq + h * G + ogi)) * D + oc;
+        if constexpr (ESIZE == 2)
+            ((uint16_t *)g.out)[oi] = (uint16_t)f32_to_bf16_rne(v);
+        else
+            ((float *)g.out)[oi] = v;
+    }
+    // score softmax over all live slots, from the stored raw dots; four slots per thread
+    // and batch are fetched together so that the loads overlap
+    float zs[G];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) zs[gi] = 0.f;
+    const bool one_batch = live <= U * NT;  // then the values stay in registers for pass two
     for (int base = 0; base < live; base += U * NT) {
-        fetch(base);
+        if (base) fetch(base);
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -449,6 +496,7 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
     int best_slot = -1;
     for (int base = 0; base < live; base += U * NT) {
         if (!one_batch) fetch(base);
+        patch_free_slot(base);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int s = base + tid + u * NT;

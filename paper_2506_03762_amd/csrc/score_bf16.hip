@@ -206,12 +206,15 @@ __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirs
 
 // Workgroups are handed to the eight XCDs (each with an L2 of its own) round-robin by
 // their linear index.  The score kernels are launched on a one-dimensional grid of
-// 8 * ceil(total / 8) workgroups and work on the logical index returned here, which runs
-// contiguously over an XCD's share: the workgroups of one (batch, KV head) problem, which
-// read the same keys, query tiles and row statistics, then meet in one L2.
-// Indices >= total have no work.
+// 8 * ceil(total / 8) workgroups and work on the logical index returned here; indices
+// >= total have no work.  In full accumulation (`contiguous`) the logical index runs
+// contiguously over an XCD's share, so that the workgroups of one (batch, KV head)
+// problem, which re-read the same keys many times, meet in one L2 (measured 4 % faster).
+// The windowed scores stream every key once; there the plain order, which spreads a
+// problem over all XCDs, is the faster one (measured 5 - 15 %).
 constexpr int kXcds = 8;
-__device__ __forceinline__ int xcd_contiguous_index(int total) {
+__device__ __forceinline__ int logical_wg_index(int total, bool contiguous) {
+    if (!contiguous) return (int)blockIdx.x;
     const int per = (total + kXcds - 1) / kXcds;
     return ((int)blockIdx.x % kXcds) * per + (int)blockIdx.x / kXcds;
 }
@@ -269,7 +272,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
     float2 *sRed = (float2 *)smem;  // reuses the query tile after the main loop
 
     // logical workgroup index -> (part, tile pair, problem)
-    const int wg = xcd_contiguous_index(total_wgs);
+    const int wg = logical_wg_index(total_wgs, n_qtiles > 1);
     if (wg >= total_wgs) return;
     const int npairs = (n_qtiles + 1) / 2;
     const int part = wg % nparts, pair = (wg / nparts) % npairs, z = wg / (nparts * npairs);
@@ -425,26 +428,40 @@ __device__ __forceinline__ float fold16_over32(const f32x16 &xv, int lane) {
 // Log2-sum-exp2 of one query row from the per-chunk log2-sum-exp2 values that pass 1 left.
 // A batch of values is requested at once (request), so that it travels together with the
 // other loads of the tile set-up, and merged later (merge) into the running (M, sum) with
-// sum = sum over chunks of exp2(value - M).
+// sum = sum over chunks of exp2(value - M).  Both go by groups of eight and skip the
+// groups past the last chunk.
 template <int BATCH>
 __device__ __forceinline__ void chunk_request(const float *src, int stride, int c0, int nchunks,
                                               float (&e)[BATCH]) {
-    // entries past the last chunk re-read it (branch-free, back-to-back loads) and are
-    // neutralised in the merge
+    static_assert(BATCH % 8 == 0, "groups of eight");
 #pragma unroll
-    for (int t = 0; t < BATCH; ++t) e[t] = src[(int64_t)min(c0 + t, nchunks - 1) * stride];
+    for (int g8 = 0; g8 < BATCH; g8 += 8) {
+        if (c0 + g8 >= nchunks) break;  // uniform
+        // entries past the last chunk re-read it (branch-free, back-to-back loads) and are
+        // neutralised in the merge
+#pragma unroll
+        for (int t = g8; t < g8 + 8; ++t) e[t] = src[(int64_t)min(c0 + t, nchunks - 1) * stride];
+    }
 }
 template <int BATCH>
 __device__ __forceinline__ void chunk_merge(const float (&e)[BATCH], int count, float &M,
                                             float &sum) {
     float bm = -INFINITY;
 #pragma unroll
-    for (int t = 0; t < BATCH; ++t) bm = fmaxf(bm, t < count ? e[t] : -INFINITY);
+    for (int g8 = 0; g8 < BATCH; g8 += 8) {
+        if (g8 >= count) break;  // uniform
+#pragma unroll
+        for (int t = g8; t < g8 + 8; ++t) bm = fmaxf(bm, t < count ? e[t] : -INFINITY);
+    }
     const float mn = fmaxf(M, bm);
     const float mref = mn == -INFINITY ? 0.f : mn;
     sum *= fast_exp2(M - mref);
 #pragma unroll
-    for (int t = 0; t < BATCH; ++t) sum += t < count ? fast_exp2(e[t] - mref) : 0.f;
+    for (int g8 = 0; g8 < BATCH; g8 += 8) {
+        if (g8 >= count) break;
+#pragma unroll
+        for (int t = g8; t < g8 + 8; ++t) sum += t < count ? fast_exp2(e[t] - mref) : 0.f;
+    }
     M = mn;
 }
 
@@ -471,7 +488,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     __shared__ float s_gmax[4];
 
     // logical workgroup index -> SINGLE: (key range, problem); else (part, tile pair, problem)
-    const int wg = xcd_contiguous_index(total_wgs);
+    const int wg = logical_wg_index(total_wgs, !SINGLE);
     if (wg >= total_wgs) return;
     const int per_problem = total_wgs / (g.batch * g.Hkv);
     const int z = wg / per_problem, wg_in_z = wg % per_problem;
