@@ -69,16 +69,69 @@ __device__ __forceinline__ float row_scale_log2_f32(int scale_mode, float fixed_
 // 2^x on the transcendental unit (v_exp_f32): no denormal results, exp2(-inf) = 0.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+// ---- exchanges between lanes inside the vector ALU ----
+// (a shuffle built on ds_bpermute goes through the LDS crossbar and costs its latency at
+// every step of a reduction; the forms below are plain vector instructions)
+// Data-parallel primitive with a fixed control word: a value from lane ^ 1, ^ 2, ^ 4, ^ 8.
+template <int CTRL, int BANKS = 0xf>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t old, uint32_t x) {
+    return __builtin_amdgcn_update_dpp(old, x, CTRL, 0xf, BANKS, false);
 }
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+template <int M>
+__device__ __forceinline__ uint32_t from_lane_xor(uint32_t x) {
+    static_assert(M == 1 || M == 2 || M == 4 || M == 8, "within a row of 16 lanes");
+    if constexpr (M == 1) return dpp_move<0xb1>(0u, x);       // quad_perm [1,0,3,2]
+    else if constexpr (M == 2) return dpp_move<0x4e>(0u, x);  // quad_perm [2,3,0,1]
+    else if constexpr (M == 4)  // row_shl:4 where bit 2 of the lane is clear (banks 0, 2), row_shr:4 elsewhere
+        return dpp_move<0x114, 0xa>(dpp_move<0x104, 0x5>(0u, x), x);
+    else return dpp_move<0x128>(0u, x);                       // row_ror:8
 }
+template <int M>
+__device__ __forceinline__ float from_lane_xor(float x) {
+    return __uint_as_float(from_lane_xor<M>(__float_as_uint(x)));
+}
+// op(x, x of lane ^ M) for any power of two M < 64.  Lanes ^ 16 and ^ 32 use
+// v_permlane16_swap / v_permlane32_swap: applied to (x, x) they return the own and the
+// partner's value in an order that depends on the lane, which a symmetric op does not mind.
+template <int M, class T, class Op>
+__device__ __forceinline__ T combine_lane_xor(T x, Op op) {
+    static_assert(sizeof(T) == 4, "32-bit values");
+    uint32_t bits;
+    __builtin_memcpy(&bits, &x, 4);
+    uint32_t o0, o1;
+    if constexpr (M == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(bits, bits, false, false);
+        o0 = r[0]; o1 = r[1];
+    } else if constexpr (M == 32) {
+        const auto r = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+        o0 = r[0]; o1 = r[1];
+    } else {
+        o0 = bits; o1 = from_lane_xor<M>(bits);
+    }
+    T a, b;
+    __builtin_memcpy(&a, &o0, 4);
+    __builtin_memcpy(&b, &o1, 4);
+    return op(a, b);
+}
+// Reduction with a symmetric op over the lanes that differ in the bits LO <= bit < HI
+// (powers of two): LO = 1, HI = 64 is the whole wave, LO = 1, HI = 16 an aligned group of
+// 16 lanes, LO = 16, HI = 64 the four lanes with the same position in their row.
+template <int LO, int HI, class T, class Op>
+__device__ __forceinline__ T reduce_lanes(T v, Op op) {
+    if constexpr (LO < HI) {
+        v = combine_lane_xor<LO>(v, op);
+        return reduce_lanes<LO * 2, HI>(v, op);
+    } else {
+        return v;
+    }
+}
+struct OpMax { __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); } };
+struct OpSum { __device__ __forceinline__ float operator()(float a, float b) const { return a + b; } };
+struct OpMinU { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a < b ? a : b; } };
+struct OpMaxU { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a > b ? a : b; } };
+
+__device__ __forceinline__ float wave_max(float v) { return reduce_lanes<1, 64>(v, OpMax{}); }
+__device__ __forceinline__ float wave_sum(float v) { return reduce_lanes<1, 64>(v, OpSum{}); }
 
 // Loads that bypass the per-CU cache (for data another workgroup of the same
 // launch has just written and fenced).

@@ -77,8 +77,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
             float w = 0.f;
 #pragma unroll
             for (int c = 0; c < CH; ++c) w = fmaf(qr[gi][c], kf[c], w);
-#pragma unroll
-            for (int o = LPR / 2; o > 0; o >>= 1) w += __shfl_xor(w, o);
+            w = reduce_lanes<1, LPR>(w, OpSum{});  // over the lanes of the row
             if (sub == 0) s_w[gi * live + s] = w;
             mloc[gi] = fmaxf(mloc[gi], w);
         }
@@ -191,8 +190,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
             float v = o[gi][c];
-#pragma unroll
-            for (int off = LPR; off < 64; off <<= 1) v += __shfl_xor(v, off);
+            v = reduce_lanes<LPR, 64>(v, OpSum{});  // over the rows of the wave
             if (lane < LPR) s_o[(wave * G + gi) * D + sub * CH + c] = v;
         }
     __syncthreads();
@@ -274,8 +272,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
             float w = 0.f;
 #pragma unroll
             for (int c = 0; c < CH; ++c) w = fmaf(qr[gi][c], kf[c], w);
-#pragma unroll
-            for (int o = LPR / 2; o > 0; o >>= 1) w += __shfl_xor(w, o);
+            w = reduce_lanes<1, LPR>(w, OpSum{});  // over the lanes of the row
             if (sub == 0) {
                 s_p[gi * sps + s - s0] = w;
                 ws_w[((int64_t)z * G + gi) * live + s] = w;
@@ -352,8 +349,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
             float v = o[gi][c];
-#pragma unroll
-            for (int off = LPR; off < 64; off <<= 1) v += __shfl_xor(v, off);
+            v = reduce_lanes<LPR, 64>(v, OpSum{});  // over the rows of the wave
             if (lane < LPR) s_o[(wave * G + gi) * D + sub * CH + c] = v;
         }
     __syncthreads();

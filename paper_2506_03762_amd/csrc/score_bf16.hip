@@ -386,21 +386,6 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
 }
 
 // ---------------------------------------------------------------- pass 2 --
-// Lane exchanges inside the vector ALU (no trip through the LDS crossbar): data-parallel
-// primitives with a fixed control word move a value from lane ^ 1, ^ 2, ^ 4 or ^ 8.
-template <int CTRL, int BANKS = 0xf>
-__device__ __forceinline__ float dpp_move(float old, float x) {
-    return __uint_as_float(__builtin_amdgcn_update_dpp(__float_as_uint(old), __float_as_uint(x),
-                                                       CTRL, 0xf, BANKS, false));
-}
-__device__ __forceinline__ float from_lane_xor1(float x) { return dpp_move<0xb1>(0.f, x); }  // quad_perm [1,0,3,2]
-__device__ __forceinline__ float from_lane_xor2(float x) { return dpp_move<0x4e>(0.f, x); }  // quad_perm [2,3,0,1]
-__device__ __forceinline__ float from_lane_xor4(float x) {
-    // row_shl:4 for the lanes whose bit 2 is clear (banks 0 and 2), row_shr:4 for the others
-    return dpp_move<0x114, 0xa>(dpp_move<0x104, 0x5>(0.f, x), x);
-}
-__device__ __forceinline__ float from_lane_xor8(float x) { return dpp_move<0x128>(0.f, x); }  // row_ror:8
-
 // Sum of 16 per-lane values over the 32 lanes of each half-wave by recursive
 // halving: after the call lane l holds the total of element
 // v = 8*bit4(l) + 4*bit3(l) + 2*bit2(l) + bit1(l)   (both lanes of a pair hold it).
@@ -428,18 +413,18 @@ __device__ __forceinline__ float fold16_over32(const f32x16 &xv, int lane) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const float send = hi ? a[t] : a[t + 4], keep = hi ? a[t + 4] : a[t];
-        b4[t] = keep + from_lane_xor8(send);
+        b4[t] = keep + from_lane_xor<8>(send);
     }
     hi = lane & 4;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         const float send = hi ? b4[t] : b4[t + 2], keep = hi ? b4[t + 2] : b4[t];
-        c2[t] = keep + from_lane_xor4(send);
+        c2[t] = keep + from_lane_xor<4>(send);
     }
     hi = lane & 2;
     const float send = hi ? c2[0] : c2[1], keep = hi ? c2[1] : c2[0];
-    float d = keep + from_lane_xor2(send);
-    d += from_lane_xor1(d);
+    float d = keep + from_lane_xor<2>(send);
+    d += from_lane_xor<1>(d);
     return d;
 }
 

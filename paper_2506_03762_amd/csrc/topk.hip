@@ -117,11 +117,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
     // 1. range of the keys
     uint32_t kmin = 0xffffffffu, kmax = 0u;
     for_keys([&](uint32_t u, int) { kmin = min(kmin, u); kmax = max(kmax, u); });
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
-        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
-    }
+    kmin = reduce_lanes<1, 64>(kmin, OpMinU{});
+    kmax = reduce_lanes<1, 64>(kmax, OpMaxU{});
     if (lane == 0) { sm.red[0][wave] = kmin; sm.red[1][wave] = kmax; }
     for (int t = tid; t < kHistCopies * kBins; t += kTopkThreads) (&sm.hist[0][0])[t] = 0;
     if (tid == 0) sm.ncand = 0;

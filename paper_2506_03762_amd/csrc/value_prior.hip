@@ -46,9 +46,10 @@ __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, 
     const int rows_per_pass = 256 / lpr;
     const int sub = tid % lpr, rloc = tid / lpr;
 
-    // eight independent 16-byte loads in flight per lane (more in flight measured slower at
-    // the large shapes)
-    constexpr int U = 8;
+    // nine independent 16-byte loads in flight per lane: with 16 lanes per row a tile and
+    // its pooling halo (256 + 6 rows) then take two batches, not three (many more in flight
+    // measured slower at the large shapes)
+    constexpr int U = 9;
     for (int row0 = lo + rloc; row0 < hi; row0 += U * rows_per_pass) {
         u32x4 w[U];
 #pragma unroll
@@ -73,7 +74,10 @@ __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, 
                     s = fmaf(a, a, s);
                 }
             }
-            for (int o = lpr >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o);
+            // over the lanes of the row (8, 16 or 32 of them)
+            s = reduce_lanes<1, 8>(s, OpSum{});
+            if (lpr >= 16) s = combine_lane_xor<8>(s, OpSum{});
+            if (lpr >= 32) s = combine_lane_xor<16>(s, OpSum{});
             const int row = row0 + u * rows_per_pass;
             if (sub == 0 && row < hi) s_nu[row - lo] = s;
         }
