@@ -28,6 +28,15 @@ __device__ __forceinline__ void unpack(const u32x4 &w, float (&f)[16 / ESIZE]) {
     }
 }
 
+// Smallest (score bits << 32 | ~position) key of the wave, in two 32-bit reductions: the
+// smallest score, then the smallest ~position among the lanes that hold it.
+__device__ __forceinline__ unsigned long long wave_min_key(unsigned long long key) {
+    const uint32_t hi = (uint32_t)(key >> 32), lo = (uint32_t)key;
+    const uint32_t whi = reduce_lanes<1, 64>(hi, OpMinU{});
+    const uint32_t wlo = reduce_lanes<1, 64>(hi == whi ? lo : 0xffffffffu, OpMinU{});
+    return ((unsigned long long)whi << 32) | wlo;
+}
+
 template <int ESIZE, int D, int G>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w_floats) {
     constexpr int CH = 16 / ESIZE;       // channels per 16-byte chunk
@@ -151,12 +160,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
             if (key < best) { best = key; best_slot = s; }
         }
     }
-    unsigned long long wbest = best;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const unsigned long long t = __shfl_xor(wbest, o);
-        wbest = t < wbest ? t : wbest;
-    }
+    const unsigned long long wbest = wave_min_key(best);  // every lane takes part
     if (lane == 0) s_key[wave] = wbest;
     __syncthreads();  // also: s_w is free from here on
     unsigned long long gbest = s_key[0];
@@ -378,7 +382,6 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
     __shared__ float s_pm[kMaxDecodeSplit][G], s_pz[kMaxDecodeSplit][G];
     __shared__ float s_red[kMergeThreads / 64][G];
     __shared__ unsigned long long s_key[kMergeThreads / 64];
-    __shared__ int s_victim;
     const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int live = g.budget + 1;
@@ -511,23 +514,16 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
             }
         }
     }
-    unsigned long long wbest = best;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const unsigned long long t = __shfl_xor(wbest, o);
-        wbest = t < wbest ? t : wbest;
-    }
+    const unsigned long long wbest = wave_min_key(best);  // every lane takes part
     if (lane == 0) s_key[wave] = wbest;
     __syncthreads();
     unsigned long long gbest = s_key[0];
 #pragma unroll
     for (int w = 1; w < kMergeThreads / 64; ++w) gbest = s_key[w] < gbest ? s_key[w] : gbest;
-    if (best_slot >= 0 && best == gbest) s_victim = best_slot;
-    __syncthreads();
-    if (tid == 0) {
-        const int victim = s_victim;
-        posz[victim] = -1;
-        g.free_slot[z] = victim;
+    // positions are unique, so exactly one thread holds the victim: it retires the slot
+    if (best_slot >= 0 && best == gbest) {
+        posz[best_slot] = -1;
+        g.free_slot[z] = best_slot;
     }
 }
 
