@@ -7,7 +7,9 @@ compaction -> one decode step with running eviction on the fresh cache.  The
 workload is the 32K-context GQA layer (batch 1, 32 query / 8 KV heads,
 head_dim 128, bf16, window 64, budget 2048).
 
-Prints ONE JSON line (see the design doc for the meaning of every field).
+Prints ONE JSON line: the step time and throughput, per-kernel times from HIP events,
+the roofline of the dominant kernel, side measurements of the other configurations and the
+CPU oracle timed on a bounded sample of the same step.
 """
 from __future__ import annotations
 

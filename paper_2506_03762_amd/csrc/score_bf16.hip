@@ -116,14 +116,16 @@ __device__ __forceinline__ void q_tile_meta(const ScoreGeom &g, const RowMap &rm
 }
 
 // A fragments of a wave's key block: lane holds row kb + mb*32 + lane%32,
-// channels ks*16 + (lane/32)*8 .. +8.  Rows past the sequence are clamped
-// (their results are masked or never written).
+// channels ks*16 + (lane/32)*8 .. +8.  Rows at or past `end` (the end of the
+// workgroup's key range, at most the sequence length) read row end - 1 instead:
+// their results are masked or never written, and a prefetch past the range then
+// costs one row, not a block of somebody else's keys.
 template <int D>
-__device__ __forceinline__ void load_a(const __bf16 *kbase, int64_t k_tstride, int kb, int n,
+__device__ __forceinline__ void load_a(const __bf16 *kbase, int64_t k_tstride, int kb, int end,
                                        int lane, bf16x8 (&a)[kMB][D / 16]) {
 #pragma unroll
     for (int mb = 0; mb < kMB; ++mb) {
-        const int row = min(kb + mb * 32 + (lane & 31), n - 1);
+        const int row = min(kb + mb * 32 + (lane & 31), end - 1);
         const __bf16 *p = kbase + (int64_t)row * k_tstride + (lane >> 5) * 8;
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) a[mb][ks] = *(const bf16x8 *)(p + ks * 16);
@@ -296,7 +298,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
         // the first key block is requested before the query tile, so both latencies overlap
         const int kb_first = key_begin + wave * kWaveKeys;
         bf16x8 a0[kMB][D / 16], a1[kMB][D / 16];  // the next key block loads while one multiplies
-        load_a<D>(kbase, g.ks[2], min(kb_first, g.n - 1), g.n, lane, a0);
+        load_a<D>(kbase, g.ks[2], kb_first, key_end, lane, a0);
         {
             QTileRegs<D, NB> qt_regs;
             q_tile_request<D, NB>(g, b, h, rho0, tid, qt_regs);
@@ -346,10 +348,10 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
         // step.
         for (int kb = kb_first; kb < key_end; kb += 2 * kWgKeys) {
             const int k1 = kb + kWgKeys, k2 = k1 + kWgKeys;
-            load_a<D>(kbase, g.ks[2], k1, g.n, lane, a1);
+            load_a<D>(kbase, g.ks[2], k1, key_end, lane, a1);
             step(a0, kb);
             if (k1 >= key_end) break;
-            load_a<D>(kbase, g.ks[2], k2, g.n, lane, a0);
+            load_a<D>(kbase, g.ks[2], k2, key_end, lane, a0);
             step(a1, k1);
         }
 
@@ -505,7 +507,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
 
     // the first key block is requested before everything else: its latency is the longest
     bf16x8 a0[kMB][D / 16];
-    if (SINGLE) load_a<D>(kbase, g.ks[2], key_begin + wave * kWaveKeys, g.n, lane, a0);
+    if (SINGLE) load_a<D>(kbase, g.ks[2], key_begin + wave * kWaveKeys, key_end, lane, a0);
 
     // this thread's share of the value prior's per-tile maxima (requested here, reduced
     // during the first tile set-up)
@@ -634,10 +636,10 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
         // (unconditional prefetch, as in pass 1)
         for (int kb0 = key_begin; kb0 < key_end; kb0 += 2 * kWgKeys) {
             const int k1 = kb0 + kWgKeys, k2 = k1 + kWgKeys;
-            load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, g.n, lane, a1);
+            load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, key_end, lane, a1);
             step(a0, kb0);
             if (k1 >= key_end) break;
-            load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, g.n, lane, a0);
+            load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, key_end, lane, a0);
             step(a1, k1);
         }
     } else {
@@ -657,7 +659,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             if (key_begin >= key_end) continue;  // workgroup-uniform
             const int rho0 = sg.qt * S::ROWS;
             if (seg) __syncthreads();  // the previous tile is done with
-            load_a<D>(kbase, g.ks[2], key_begin + wave * kWaveKeys, g.n, lane, a0);
+            load_a<D>(kbase, g.ks[2], key_begin + wave * kWaveKeys, key_end, lane, a0);
             load_tile(sg.qt);
             float ginv = 1.f;
             if (g.value_prior)
@@ -680,10 +682,10 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             };
             for (int kb0 = key_begin; kb0 < key_end; kb0 += 2 * kWgKeys) {
                 const int k1 = kb0 + kWgKeys, k2 = k1 + kWgKeys;
-                load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, g.n, lane, a1);
+                load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, key_end, lane, a1);
                 step(a0, kb0);
                 if (k1 >= key_end) break;
-                load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, g.n, lane, a0);
+                load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, key_end, lane, a0);
                 step(a1, k1);
             }
         }
