@@ -121,6 +121,36 @@ def prefill_scores(Q, K, V, cfg: Config):
     return S
 
 
+def row_lse(Q, K, cfg: Config):
+    """Natural-log softmax denominators of the observed rows [batch, n_q_heads, window]."""
+    Q, K = _f64(Q), _f64(K)
+    b, hq, n, d = Q.shape
+    hk = K.shape[1]
+    assert hq % hk == 0 and K.shape == (b, hk, n, d) and 1 <= cfg.window <= n
+    L = np.empty((b, hq, cfg.window), dtype=np.float64)
+    _load().aha_oracle_row_lse(
+        _p(Q), _p(K), _I64(b), _I64(hq), _I64(hk), _I64(n), _I64(d), _I64(cfg.window),
+        _I64(cfg.budget), ctypes.c_int(cfg.scale_mode), ctypes.c_double(cfg.fixed_scale),
+        ctypes.c_double(cfg.lambda_floor), _p(L))
+    return L
+
+
+def prefill_scores_lse(Q, K, V, lse, cfg: Config):
+    """Refined eviction scores [batch, n_kv_heads, n] from given row normalisers."""
+    Q, K, V, lse = _f64(Q), _f64(K), _f64(V), _f64(lse)
+    b, hq, n, d = Q.shape
+    hk = K.shape[1]
+    assert hq % hk == 0 and K.shape == V.shape == (b, hk, n, d)
+    assert 1 <= cfg.window <= n and lse.shape == (b, hq, cfg.window)
+    S = np.empty((b, hk, n), dtype=np.float64)
+    _load().aha_oracle_prefill_scores_lse(
+        _p(Q), _p(K), _p(V), _p(lse), _I64(b), _I64(hq), _I64(hk), _I64(n), _I64(d),
+        _I64(cfg.window), _I64(cfg.budget), ctypes.c_int(cfg.scale_mode),
+        ctypes.c_double(cfg.fixed_scale), ctypes.c_double(cfg.lambda_floor),
+        ctypes.c_int(1 if cfg.value_prior else 0), _I64(cfg.pool), _p(S))
+    return S
+
+
 def select_topk(scores, budget: int, recent: int):
     """Ascending retained token indices [..., budget] (int32)."""
     scores = _f64(scores)

@@ -200,6 +200,96 @@ void aha_oracle_prefill_scores(const double *Q, const double *K, const double *V
 }
 
 /* ------------------------------------------------------------------------
+ * Row normalisers of the observed rows, as an attention forward pass emits
+ * them (App. on compatibility with FlashAttention: the score is computed
+ * beside a forward pass that keeps, per query row, the logarithm of the
+ * softmax denominator):
+ *     lse_i = log sum_{j <= i} exp(s w_ij),   natural logarithm, s = the row's scale.
+ *
+ * Q: [batch, n_q_heads, n, d], K: [batch, n_kv_heads, n, d]
+ * lse: [batch, n_q_heads, window]; entry ii is query position n-window+ii.
+ * ---------------------------------------------------------------------- */
+void aha_oracle_row_lse(const double *Q, const double *K,
+                        int64_t batch, int64_t n_q_heads, int64_t n_kv_heads,
+                        int64_t n, int64_t d, int64_t window, int64_t budget,
+                        int scale_mode, double fixed_scale, double lambda_floor,
+                        double *lse)
+{
+    int64_t G = n_q_heads / n_kv_heads;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int64_t b = 0; b < batch; ++b) {
+        for (int64_t hq = 0; hq < n_q_heads; ++hq) {
+            const double *Kh = K + ((b * n_kv_heads + hq / G) * n) * d;
+            for (int64_t ii = 0; ii < window; ++ii) {
+                int64_t i = n - window + ii, c = i + 1;
+                const double *q = Q + (((b * n_q_heads + hq) * n) + i) * d;
+                double s = row_scale(scale_mode, fixed_scale, lambda_floor, c, budget, d);
+                double m = -INFINITY;
+                for (int64_t j = 0; j < c; ++j) {
+                    double w = 0.0;
+                    for (int64_t t = 0; t < d; ++t) w += q[t] * Kh[j * d + t];
+                    if (s * w > m) m = s * w;
+                }
+                double z = 0.0;
+                for (int64_t j = 0; j < c; ++j) {
+                    double w = 0.0;
+                    for (int64_t t = 0; t < d; ++t) w += q[t] * Kh[j * d + t];
+                    z += exp(s * w - m);
+                }
+                lse[((b * n_q_heads + hq) * window) + ii] = m + log(z);
+            }
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * Prefill eviction scores from given row normalisers: the same sum as
+ * aha_oracle_prefill_scores, with p_ij = exp(s w_ij - lse_i) taken from the
+ * caller's lse instead of normalising the row here.  With the lse of
+ * aha_oracle_row_lse for the same scale the two functions agree up to
+ * rounding; a different lse scales row i's contribution by exp(true - given).
+ *
+ * lse: [batch, n_q_heads, window]; other layouts as aha_oracle_prefill_scores.
+ * ---------------------------------------------------------------------- */
+void aha_oracle_prefill_scores_lse(const double *Q, const double *K, const double *V,
+                                   const double *lse,
+                                   int64_t batch, int64_t n_q_heads, int64_t n_kv_heads,
+                                   int64_t n, int64_t d, int64_t window, int64_t budget,
+                                   int scale_mode, double fixed_scale, double lambda_floor,
+                                   int value_prior, int64_t pool, double *S)
+{
+    int64_t G = n_q_heads / n_kv_heads;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int64_t b = 0; b < batch; ++b) {
+        for (int64_t hk = 0; hk < n_kv_heads; ++hk) {
+            const double *Kh = K + ((b * n_kv_heads + hk) * n) * d;
+            double *Sh = S + (b * n_kv_heads + hk) * n;
+            for (int64_t j = 0; j < n; ++j) Sh[j] = 0.0;
+            for (int64_t g = 0; g < G; ++g) {
+                int64_t hq = hk * G + g;
+                for (int64_t ii = 0; ii < window; ++ii) {
+                    int64_t i = n - window + ii, c = i + 1;
+                    const double *q = Q + (((b * n_q_heads + hq) * n) + i) * d;
+                    double s = row_scale(scale_mode, fixed_scale, lambda_floor, c, budget, d);
+                    double L = lse[((b * n_q_heads + hq) * window) + ii];
+                    for (int64_t j = 0; j < c; ++j) {
+                        double w = 0.0;
+                        for (int64_t t = 0; t < d; ++t) w += q[t] * Kh[j * d + t];
+                        Sh[j] += exp(s * w - L);
+                    }
+                }
+            }
+        }
+    }
+    if (value_prior) {
+        double *gb = (double *)malloc(sizeof(double) * (size_t)(batch * n_kv_heads * n));
+        aha_oracle_value_prior(V, batch, n_kv_heads, n, d, pool, gb);
+        for (int64_t t = 0; t < batch * n_kv_heads * n; ++t) S[t] *= gb[t];
+        free(gb);
+    }
+}
+
+/* ------------------------------------------------------------------------
  * Selection (Alg. 1: recent set, TopK, union).
  * READING: the TopK runs over the non-recent tokens j < n - recent, on the
  * value-refined score; ties go to the lower index; the result is the union

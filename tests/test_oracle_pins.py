@@ -141,6 +141,53 @@ def test_adaptive_windowed_matches_library_route():
     np.testing.assert_allclose(S, want, rtol=1e-11)
 
 
+def test_row_lse_matches_library_logsumexp():
+    """The row normalisers against scipy's logsumexp of the scaled causal logits (fixed and
+    adaptive scale, grouped heads)."""
+    from scipy.special import logsumexp
+    b, hq, hk, n, d, r, B = 2, 4, 2, 90, 16, 12, 20
+    Q, K = rnd(40, b, hq, n, d), rnd(41, b, hk, n, d)
+    for cfg, scale_of in (
+            (Config(window=r, budget=B, recent=4, scale_mode=SCALE_FIXED, fixed_scale=0.3),
+             lambda i: 0.3),
+            (Config(window=r, budget=B, recent=4, lambda_floor=0.0),
+             lambda i: math.sqrt(2 * max(math.log((i + 1) / B), 0.0) / d))):
+        L = oracle.row_lse(Q, K, cfg)
+        assert L.shape == (b, hq, r)
+        for bi in range(b):
+            for h in range(hq):
+                for ii in range(r):
+                    i = n - r + ii
+                    w = K[bi, h // (hq // hk), :i + 1] @ Q[bi, h, i]
+                    assert abs(L[bi, h, ii] - logsumexp(scale_of(i) * w)) < 1e-11
+
+
+def test_scores_from_row_lse():
+    """Scores from given normalisers: with the true normalisers they are the scores; the
+    normaliser enters as exp(-lse), row by row (a shifted lse rescales that row's share)."""
+    b, hq, hk, n, d, r = 1, 4, 2, 80, 16, 8
+    Q, K, V = rnd(42, b, hq, n, d), rnd(43, b, hk, n, d), rnd(44, b, hk, n, d)
+    for vp in (False, True):
+        cfg = Config(window=r, budget=16, recent=4, scale_mode=SCALE_FIXED,
+                     fixed_scale=1 / math.sqrt(d), value_prior=vp)
+        L = oracle.row_lse(Q, K, cfg)
+        S = oracle.prefill_scores(Q, K, V, cfg)
+        np.testing.assert_allclose(oracle.prefill_scores_lse(Q, K, V, L, cfg), S, rtol=1e-11)
+    # shift the normaliser of one query head's rows by log 2: that head's share halves
+    cfg = Config(window=r, budget=16, recent=4, scale_mode=SCALE_FIXED,
+                 fixed_scale=1 / math.sqrt(d), value_prior=False)
+    L = oracle.row_lse(Q, K, cfg)
+    S = oracle.prefill_scores(Q, K, V, cfg)
+    share = oracle.prefill_scores(Q[:, 1:2], K[:, 0:1], V[:, 0:1], cfg)  # head 1 alone on KV head 0
+    L2 = L.copy()
+    L2[:, 1] += math.log(2.0)
+    S2 = oracle.prefill_scores_lse(Q, K, V, L2, cfg)
+    np.testing.assert_allclose(S2[:, 0], S[:, 0] - 0.5 * share[:, 0], rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(S2[:, 1], S[:, 1], rtol=1e-12)
+    # rows still sum to one: the column sums total the number of rows
+    np.testing.assert_allclose(S.sum(-1), (hq // hk) * r, rtol=1e-12)
+
+
 def test_transposed_or_swapped_operands_would_fail():
     """Q and K are not interchangeable: scoring with them swapped differs."""
     b, h, n, d = 1, 1, 40, 8
