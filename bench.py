@@ -186,6 +186,7 @@ def main():
         result["decode_c4"] = bench_decode_c4(torch, B, synth, H, K_STEPS)
         result["full_accumulation_c2"] = bench_full_c2(torch, B, synth, H, max(5, K_STEPS // 5))
         result["prefill_c5_layer"] = bench_c5_layer(torch, B, synth, H, max(5, K_STEPS // 5))
+        result["scores_from_lse_c3"] = bench_lse_c3(torch, B, H, w, p, q, k, v, scores, ws, K_STEPS)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, (Q, K, V), synth, H)
     print(json.dumps(result))
@@ -284,6 +285,41 @@ def bench_full_c2(torch, B, synth, H, steps):
                          "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS},
             "pass1_TFLOPs": flops_pass / (p1 * 1e-3) / 1e12,
             "pass2_TFLOPs": flops_pass / (p2 * 1e-3) / 1e12}
+
+
+def bench_lse_c3(torch, B, H, w, p, q, k, v, scores, ws, steps):
+    """The score stage on the C3 layer with the standard scale 1/sqrt(d): two passes, against
+    one pass when the caller hands over the rows' log-sum-exp (as an attention forward pass
+    keeps it).  The log-sum-exp fed here is formed with torch from the same Q and K."""
+    import dataclasses
+    n, d, r, G = w.seq_len, w.head_dim, w.window, w.group
+    scale = 1.0 / math.sqrt(d)
+    pf = dataclasses.replace(p, scale_mode=B.AHA_SCALE_FIXED, fixed_scale=scale)
+    qw = q[:, :, n - r:, :].float()                                    # [b, Hq, r, d]
+    kf = k.float().repeat_interleave(G, dim=1)                         # [b, Hq, n, d]
+    logits = torch.einsum("bhrd,bhnd->bhrn", qw, kf) * scale
+    causal = torch.arange(n, device="cuda")[None, :] <= (n - r + torch.arange(r, device="cuda"))[:, None]
+    lse = torch.logsumexp(logits.masked_fill(~causal, float("-inf")), dim=-1).contiguous()
+    del logits, kf
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        evs = []
+        for _ in range(steps):
+            e0 = torch.cuda.Event(enable_timing=True); e0.record()
+            fn()
+            e1 = torch.cuda.Event(enable_timing=True); e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        return avg_ms(evs) * 1e3
+
+    two = timed(lambda: B.aha_prefill_scores(pf, q, k, v, scores, ws))
+    ref = scores.clone()
+    one = timed(lambda: B.aha_prefill_scores_lse(pf, q, k, v, lse, scores, ws))
+    err = float(((scores - ref).abs() / (ref.abs() + 1e-6)).max())
+    return {"workload": w.name + " fixed scale 1/sqrt(d)", "two_pass_us": two, "from_lse_us": one,
+            "max_rel_diff": err}
 
 
 def bench_c5_layer(torch, B, synth, H, steps):

@@ -117,6 +117,29 @@ int32_t aha_prefill_scores(const aha_params *p, const void *q, const void *k,
                            size_t workspace_bytes, void *stream);
 
 /*
+ * Prefill eviction scores beside an attention forward pass that has already
+ * normalised the observed rows (appendix on compatibility with
+ * FlashAttention: the score is an extra product of a forward pass, which keeps
+ * the logarithm of every row's softmax denominator).  Same result and
+ * arguments as aha_prefill_scores, except that the row-statistics pass is
+ * skipped and
+ *
+ *  lse     fp32 dense [batch, n_q_heads, window]: for window row ii (query
+ *          position seq_len - window + ii) the natural logarithm of
+ *          sum_{j <= i} exp(s_i * Q_i . K_j), s_i being the scale that
+ *          p->scale_mode gives that row - with AHA_SCALE_FIXED and
+ *          fixed_scale = 1/sqrt(d) this is the forward pass's log-sum-exp.
+ *
+ * The probabilities are formed as exp(s_i * Q_i . K_j - lse_i): a normaliser
+ * that does not belong to the row scales that row's contribution and is not
+ * detected.  The stage events of aha_profile_events are recorded as for
+ * aha_prefill_scores (events[1] and [2] then bracket nothing).
+ */
+int32_t aha_prefill_scores_lse(const aha_params *p, const void *q, const void *k,
+                               const void *v, const float *lse, float *scores,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Selection (Alg. 1: recent set, TopK, union).
  *
  *  scores  fp32 [batch, n_kv_heads, seq_len], non-negative and finite.

@@ -27,8 +27,10 @@ AHA_ERR_HIP = -4
 AHA_F32, AHA_BF16 = 0, 1
 AHA_SCALE_FIXED, AHA_SCALE_ADAPTIVE = 0, 1
 
-EXPORTS = ("aha_workspace_bytes", "aha_prefill_scores", "aha_select_topk", "aha_compact_kv",
-           "aha_decode_step", "aha_profile_events", "aha_last_error", "aha_version")
+# entry points returning an int32 status first, then the two that return strings
+EXPORTS = ("aha_workspace_bytes", "aha_prefill_scores", "aha_prefill_scores_lse", "aha_select_topk",
+           "aha_compact_kv", "aha_decode_step", "aha_profile_events", "aha_last_error",
+           "aha_version")
 
 
 class AhaError(RuntimeError):
@@ -67,11 +69,12 @@ def load() -> ctypes.CDLL:
     pp = ctypes.POINTER(aha_params)
     lib.aha_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
     lib.aha_prefill_scores.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
+    lib.aha_prefill_scores_lse.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.aha_select_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.aha_compact_kv.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     lib.aha_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
     lib.aha_profile_events.argtypes = [ctypes.POINTER(vp), i32]
-    for name in EXPORTS[:6]:
+    for name in EXPORTS[:-2]:
         getattr(lib, name).restype = i32
     lib.aha_last_error.restype = ctypes.c_char_p
     lib.aha_version.restype = ctypes.c_char_p
@@ -158,6 +161,16 @@ def aha_prefill_scores(p: Params, q, k, v, scores, workspace):
     _check(load().aha_prefill_scores(ctypes.byref(cp), _ptr(q), _ptr(k), _ptr(v), _ptr(scores),
                                      _ptr(workspace), workspace.numel() if workspace is not None else 0,
                                      _stream()))
+
+
+def aha_prefill_scores_lse(p: Params, q, k, v, lse, scores, workspace):
+    """As aha_prefill_scores, with the rows' natural-log softmax denominators lse[b, Hq, window]
+    (fp32) given, e.g. by the attention forward pass: the row-statistics pass is skipped."""
+    cp = p.c()
+    _check(load().aha_prefill_scores_lse(ctypes.byref(cp), _ptr(q), _ptr(k), _ptr(v), _ptr(lse),
+                                         _ptr(scores), _ptr(workspace),
+                                         workspace.numel() if workspace is not None else 0,
+                                         _stream()))
 
 
 def aha_select_topk(p: Params, scores, idx, workspace=None):

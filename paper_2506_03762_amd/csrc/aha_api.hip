@@ -210,13 +210,16 @@ int32_t aha_workspace_bytes(const aha_params *p, size_t *out_bytes) {
     return AHA_OK;
 }
 
-int32_t aha_prefill_scores(const aha_params *p, const void *q, const void *k, const void *v,
-                           float *scores, void *workspace, size_t workspace_bytes, void *stream) {
+// Shared by aha_prefill_scores (lse == nullptr) and aha_prefill_scores_lse.
+static int32_t prefill_scores_impl(const aha_params *p, const void *q, const void *k,
+                                   const void *v, const float *lse, bool with_lse, float *scores,
+                                   void *workspace, size_t workspace_bytes, void *stream) {
     int32_t rc = check_prefill(p, true);
     if (rc) return rc;
     if ((rc = check_ptr("q", q, 16)) || (rc = check_ptr("k", k, 16)) ||
         (rc = check_ptr("scores", scores, 4)))
         return rc;
+    if (with_lse && (rc = check_ptr("lse", lse, 4))) return rc;
     if (p->value_prior && (rc = check_ptr("v", v, 16))) return rc;
     const PrefillPlan pl = plan_prefill(p);
     if ((rc = check_ws(workspace, workspace_bytes, pl.bytes))) return rc;
@@ -225,15 +228,30 @@ int32_t aha_prefill_scores(const aha_params *p, const void *q, const void *k, co
     const ScoreGeom g = make_geom(p, q, k, v);
     hipStream_t st = (hipStream_t)stream;
     if ((rc = hip_result(stage(0, st), "stage event"))) return rc;
-    if ((rc = hip_result(launch_value_prior(g, pl, workspace, scores, st), "value-prior kernel"))) return rc;
+    if ((rc = hip_result(launch_value_prior(g, pl, workspace, scores, lse, st), "value-prior kernel")))
+        return rc;
     if ((rc = hip_result(stage(1, st), "stage event"))) return rc;
     hipEvent_t mid = g_stage_on ? g_stage_ev[2] : nullptr;
     if (p->dtype == AHA_BF16)
-        rc = hip_result(launch_score_bf16(g, pl, workspace, scores, st, mid), "bf16 score kernels");
+        rc = hip_result(launch_score_bf16(g, pl, workspace, scores, st, mid, with_lse),
+                        "bf16 score kernels");
     else
-        rc = hip_result(launch_score_f32(g, pl, workspace, scores, st, mid), "fp32 score kernels");
+        rc = hip_result(launch_score_f32(g, pl, workspace, scores, st, mid, with_lse),
+                        "fp32 score kernels");
     if (rc) return rc;
     return hip_result(stage(3, st), "stage event");
+}
+
+int32_t aha_prefill_scores(const aha_params *p, const void *q, const void *k, const void *v,
+                           float *scores, void *workspace, size_t workspace_bytes, void *stream) {
+    return prefill_scores_impl(p, q, k, v, nullptr, false, scores, workspace, workspace_bytes,
+                               stream);
+}
+
+int32_t aha_prefill_scores_lse(const aha_params *p, const void *q, const void *k, const void *v,
+                               const float *lse, float *scores, void *workspace,
+                               size_t workspace_bytes, void *stream) {
+    return prefill_scores_impl(p, q, k, v, lse, true, scores, workspace, workspace_bytes, stream);
 }
 
 int32_t aha_select_topk(const aha_params *p, const float *scores, int32_t *idx, void *workspace,

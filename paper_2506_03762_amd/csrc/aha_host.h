@@ -41,15 +41,19 @@ constexpr int kVTileRows = 256;   // rows per value-prior workgroup
 constexpr int kP2Keys = 256;      // keys per pass-2 workgroup (4 waves x 64)
 
 // value_prior.hip
+// `lse`, when not null, holds the caller's natural-log row normalisers
+// [batch, Hq, window]; the launch then also writes them, in the log2 domain, where pass 2
+// expects the row statistics (and the score launchers skip pass 1).
 hipError_t launch_value_prior(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
-                              float *scores, hipStream_t st);
+                              float *scores, const float *lse, hipStream_t st);
 // score_f32.hip
-// `mid`, when not null, is recorded between the two passes.
+// `mid`, when not null, is recorded between the two passes; `have_lse`: the row statistics
+// are already in the workspace, pass 1 is skipped.
 hipError_t launch_score_f32(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
-                            float *scores, hipStream_t st, hipEvent_t mid);
+                            float *scores, hipStream_t st, hipEvent_t mid, bool have_lse);
 // score_bf16.hip
 hipError_t launch_score_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
-                             float *scores, hipStream_t st, hipEvent_t mid);
+                             float *scores, hipStream_t st, hipEvent_t mid, bool have_lse);
 // topk.hip
 hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent,
                        int32_t *idx, hipStream_t st);

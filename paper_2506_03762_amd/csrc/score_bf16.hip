@@ -695,7 +695,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
 // ---------------------------------------------------------------- launch --
 template <int D, int NB>
 static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
-                           hipStream_t st, hipEvent_t mid) {
+                           hipStream_t st, hipEvent_t mid, bool have_lse) {
     using S = TileSmem<D, NB>;
     char *w = (char *)ws;
     float *partial = (float *)(w + pl.off_partial);
@@ -720,35 +720,38 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     const int64_t wgs1 = (int64_t)pl.nchunks * ((pl.n_qtiles + 1) / 2) * pl.Z;
     // windowed pass 2: (key range, problem)
     const int64_t wgs2 = (int64_t)((g.n + pl.p2_keys - 1) / pl.p2_keys) * pl.Z;
-    hipLaunchKernelGGL((bf16_pass1_kernel<D, NB>), xcd_grid(wgs1), dim3(256), S::bytes, st, g,
-                       pl.n_qtiles, pl.nchunks, (int)wgs1, lam_tab, partial);
+    // with the caller's row normalisers already in place (one "chunk" per row) pass 1 is skipped
+    if (!have_lse)
+        hipLaunchKernelGGL((bf16_pass1_kernel<D, NB>), xcd_grid(wgs1), dim3(256), S::bytes, st, g,
+                           pl.n_qtiles, pl.nchunks, (int)wgs1, lam_tab, partial);
+    const int stat_chunks = have_lse ? 1 : pl.nchunks;
     if (mid) (void)hipEventRecord(mid, st);
     if (pl.n_qtiles == 1)
         hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, true>), xcd_grid(wgs2), dim3(256), S::bytes,
-                           st, g, pl.n_qtiles, (int)wgs2, pl.p2_keys, pl.nchunks, lam_tab, partial,
+                           st, g, pl.n_qtiles, (int)wgs2, pl.p2_keys, stat_chunks, lam_tab, partial,
                            gamma, gbm, pl.n_vtiles, scores);
     else
         hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, false>), xcd_grid(wgs1), dim3(256), S::bytes,
-                           st, g, pl.n_qtiles, (int)wgs1, pl.nchunks, pl.nchunks, lam_tab, partial,
+                           st, g, pl.n_qtiles, (int)wgs1, pl.nchunks, stat_chunks, lam_tab, partial,
                            gamma, gbm, pl.n_vtiles, scores);
     return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_d(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
-                           hipStream_t st, hipEvent_t mid) {
+                           hipStream_t st, hipEvent_t mid, bool have_lse) {
     switch (pl.NB) {
-        case 1: return launch_t<D, 1>(g, pl, ws, scores, st, mid);
-        case 2: return launch_t<D, 2>(g, pl, ws, scores, st, mid);
-        case 4: return launch_t<D, 4>(g, pl, ws, scores, st, mid);
-        default: return launch_t<D, 8>(g, pl, ws, scores, st, mid);
+        case 1: return launch_t<D, 1>(g, pl, ws, scores, st, mid, have_lse);
+        case 2: return launch_t<D, 2>(g, pl, ws, scores, st, mid, have_lse);
+        case 4: return launch_t<D, 4>(g, pl, ws, scores, st, mid, have_lse);
+        default: return launch_t<D, 8>(g, pl, ws, scores, st, mid, have_lse);
     }
 }
 
 hipError_t launch_score_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
-                             hipStream_t st, hipEvent_t mid) {
-    return g.d == 64 ? launch_d<64>(g, pl, ws, scores, st, mid)
-                     : launch_d<128>(g, pl, ws, scores, st, mid);
+                             hipStream_t st, hipEvent_t mid, bool have_lse) {
+    return g.d == 64 ? launch_d<64>(g, pl, ws, scores, st, mid, have_lse)
+                     : launch_d<128>(g, pl, ws, scores, st, mid, have_lse);
 }
 
 }  // namespace aha

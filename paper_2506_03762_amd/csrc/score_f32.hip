@@ -132,19 +132,19 @@ __global__ __launch_bounds__(256) void f32_pass2_kernel(ScoreGeom g, const float
 }
 
 hipError_t launch_score_f32(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
-                            hipStream_t st, hipEvent_t mid) {
+                            hipStream_t st, hipEvent_t mid, bool have_lse) {
     char *w = (char *)ws;
     float *rowL = (float *)(w + pl.off_rowL);
     const float *gamma = (const float *)(w + pl.off_gamma);
     const float *gbm = (const float *)(w + pl.off_gblockmax);
     dim3 g1(g.R, pl.Z), g2((g.n + 255) / 256, pl.Z);
     if (g.d == 64) {
-        hipLaunchKernelGGL(f32_pass1_kernel<64>, g1, dim3(256), 0, st, g, rowL);
+        if (!have_lse) hipLaunchKernelGGL(f32_pass1_kernel<64>, g1, dim3(256), 0, st, g, rowL);
         if (mid) (void)hipEventRecord(mid, st);
         hipLaunchKernelGGL(f32_pass2_kernel<64>, g2, dim3(256), 0, st, g, rowL, gamma, gbm,
                            pl.n_vtiles, scores);
     } else {
-        hipLaunchKernelGGL(f32_pass1_kernel<128>, g1, dim3(256), 0, st, g, rowL);
+        if (!have_lse) hipLaunchKernelGGL(f32_pass1_kernel<128>, g1, dim3(256), 0, st, g, rowL);
         if (mid) (void)hipEventRecord(mid, st);
         hipLaunchKernelGGL(f32_pass2_kernel<128>, g2, dim3(256), 0, st, g, rowL, gamma, gbm,
                            pl.n_vtiles, scores);

@@ -15,8 +15,22 @@ namespace aha {
 template <int ESIZE>
 __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, float *gamma,
                                                      float *gblockmax, float *lam_tab,
-                                                     float *zero_scores) {
+                                                     float *zero_scores, const float *lse,
+                                                     float *row_stats, int rows_pad) {
     const int z = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
+    if (lse) {
+        // the caller's row normalisers (natural log, [batch, Hq, window]) -> log2 domain, in
+        // the order of the flattened query rows of each KV head (padding rows: unused)
+        const int b = z / g.Hkv, h = z % g.Hkv;
+        for (int rho = tile * 256 + tid; rho < rows_pad; rho += gridDim.x * 256) {
+            float L = 0.f;
+            if (rho < g.R) {
+                const int gi = rho / g.r, ii = rho - gi * g.r;
+                L = lse[((int64_t)b * g.Hq + h * g.G + gi) * g.r + ii] * kLog2e;
+            }
+            row_stats[(int64_t)z * rows_pad + rho] = L;
+        }
+    }
     if (zero_scores && tile < n_vtiles) {
         // full accumulation adds tile contributions atomically: the scores start from zero
         const int j = tile * kVTileRows + tid;
@@ -101,7 +115,7 @@ __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, 
 }
 
 hipError_t launch_value_prior(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
-                              float *scores, hipStream_t st) {
+                              float *scores, const float *lse, hipStream_t st) {
     char *w = (char *)ws;
     float *gamma = (float *)(w + pl.off_gamma);
     float *gbm = (float *)(w + pl.off_gblockmax);
@@ -111,12 +125,16 @@ hipError_t launch_value_prior(const ScoreGeom &g, const PrefillPlan &pl, void *w
     float *zero_scores = (g.dtype == AHA_BF16 && pl.n_qtiles > 1) ? scores : nullptr;
     const int vt = (g.value_prior || zero_scores) ? pl.n_vtiles : 1;
     dim3 grid(vt > lam_blocks ? vt : lam_blocks, pl.Z);
+    // where pass 2 reads the row statistics: one chunk per (problem, tile, row) on the bf16
+    // path (rows padded to whole tiles), one value per row on the fp32 path
+    float *row_stats = (float *)(w + (g.dtype == AHA_BF16 ? pl.off_partial : pl.off_rowL));
+    const int rows_pad = g.dtype == AHA_BF16 ? pl.n_qtiles * pl.qtile : g.R;
     if (g.dtype == AHA_BF16)
         hipLaunchKernelGGL(vprior_kernel<2>, grid, dim3(256), 0, st, g, pl.n_vtiles, gamma, gbm,
-                           lam_tab, zero_scores);
+                           lam_tab, zero_scores, lse, row_stats, rows_pad);
     else
         hipLaunchKernelGGL(vprior_kernel<4>, grid, dim3(256), 0, st, g, pl.n_vtiles, gamma, gbm,
-                           lam_tab, zero_scores);
+                           lam_tab, zero_scores, lse, row_stats, rows_pad);
     return hipGetLastError();
 }
 

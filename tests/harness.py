@@ -112,6 +112,24 @@ def run_prefill_gpu(w: synth.Workload, opts: Opts = Opts(), inputs=None, layer=0
                   extra=dict(p=p, q=q, k=k, v=v, scores=scores, idx=idx, ws=ws))
 
 
+def run_scores_from_lse_gpu(w: synth.Workload, opts: Opts, inputs, lse) -> np.ndarray:
+    """aha_prefill_scores_lse through the C ABI: scores [b, Hkv, n] as float64.  `lse` is the
+    [b, Hq, window] float32 array handed to the library."""
+    import torch
+    from paper_2506_03762_amd import binding as B
+    Q, K, V = inputs
+    q, k, v = (to_device(a, w.dtype) for a in (Q, K, V))
+    p = gpu_params(w, opts).with_strides(q, k, v)
+    ws = B.alloc_workspace(p)
+    ws.fill_(0xA5)
+    scores = torch.full((w.batch, w.n_kv_heads, w.seq_len), float("nan"), dtype=torch.float32,
+                        device="cuda")
+    lse_d = torch.from_numpy(np.ascontiguousarray(lse, dtype=np.float32)).cuda()
+    B.aha_prefill_scores_lse(p, q, k, v, lse_d, scores, ws)
+    torch.cuda.synchronize()
+    return scores.cpu().numpy().astype(np.float64)
+
+
 # ----------------------------------------------------------------- compare --
 def max_rel_err(got, want, w, opts: Opts = Opts()) -> float:
     atol = atol_of(w, opts)

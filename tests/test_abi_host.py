@@ -98,6 +98,25 @@ def test_bad_pointers_and_workspace(lib):
     assert lib.aha_workspace_bytes(None, ctypes.byref(ctypes.c_size_t())) == B.AHA_ERR_INVALID_ARG
 
 
+def test_prefill_with_given_normalisers_validates(lib):
+    """aha_prefill_scores_lse: same checks as aha_prefill_scores, plus the lse pointer."""
+    p = good()
+    cp = p.c()
+    big = 1 << 40
+    call = lambda **kw: lib.aha_prefill_scores_lse(
+        ctypes.byref(cp), kw.get("q", DUMMY), DUMMY, DUMMY, kw.get("lse", DUMMY), DUMMY,
+        kw.get("ws", DUMMY), kw.get("nbytes", big), None)
+    assert call(lse=None) == B.AHA_ERR_INVALID_ARG
+    assert b"lse" in lib.aha_last_error()
+    assert call(lse=ctypes.c_void_p(0x1002)) == B.AHA_ERR_INVALID_ARG   # not 4-byte aligned
+    assert call(q=None) == B.AHA_ERR_INVALID_ARG
+    assert call(ws=None) == B.AHA_ERR_WORKSPACE
+    assert call(nbytes=B.workspace_bytes(p) - 1) == B.AHA_ERR_WORKSPACE
+    bad = good(window=0).c()
+    assert lib.aha_prefill_scores_lse(ctypes.byref(bad), DUMMY, DUMMY, DUMMY, DUMMY, DUMMY, DUMMY,
+                                      big, None) == B.AHA_ERR_INVALID_ARG
+
+
 def test_other_entry_points_validate(lib):
     p = good()
     cp = p.c()

@@ -29,6 +29,23 @@ def test_c3_long_context_gqa_layer(w):
     assert flips == 0
 
 
+def test_c3_scores_from_forward_lse():
+    """The 32K-context layer scored with the standard scale from row normalisers given by the
+    caller (the oracle's, rounded to float32): same scores and retained sets as the oracle."""
+    w = synth.C3
+    print("case", w.name, "scores from lse", flush=True)
+    inputs = synth.make_prefill(w, threads=16)
+    opts = Opts(scale_mode=oracle.SCALE_FIXED, fixed_scale=w.head_dim ** -0.5)
+    cfg = H.oracle_cfg(w, opts)
+    lse32 = oracle.row_lse(inputs[0], inputs[1], cfg).astype(np.float32)
+    got = H.run_scores_from_lse_gpu(w, opts, inputs, lse32)
+    want = oracle.prefill_scores_lse(*inputs, lse32.astype(np.float64), cfg)
+    H.assert_scores_close(got, want, w, opts)
+    gpu = H.run_prefill_gpu(w, opts, inputs)          # the two-pass entry point, same switches
+    H.assert_scores_close(gpu.scores, got, w, opts)
+    H.assert_sets_match(gpu.idx, oracle.select_topk(want, w.budget, w.recent), want, w)
+
+
 def test_full_accumulation_mfma_path_against_oracle():
     """window = n (the n x n contraction, the plain accumulated score) at a size the oracle
     still finishes: 16 query / 8 KV heads x 4096."""

@@ -104,6 +104,70 @@ def test_c2_llama2_7b_layer():
     print("C2 excused near-ties:", excused)
 
 
+# ------------------------------------------- scores from given normalisers --
+def check_scores_from_lse(w, opts, layer=0):
+    """The row normalisers come from the oracle, rounded to float32 as a forward pass would
+    hand them over; the expected scores are the oracle's for exactly those normalisers."""
+    print("lse case", w.name, w.dtype, "n", w.seq_len, "Hq/Hkv", w.n_q_heads, w.n_kv_heads,
+          opts, flush=True)
+    inputs = synth.make_prefill(w, layer)
+    cfg = H.oracle_cfg(w, opts)
+    lse32 = oracle.row_lse(inputs[0], inputs[1], cfg).astype(np.float32)
+    got = H.run_scores_from_lse_gpu(w, opts, inputs, lse32)
+    want = oracle.prefill_scores_lse(*inputs, lse32.astype(np.float64), cfg)
+    H.assert_scores_close(got, want, w, opts)
+    # and they are the scores of the two-pass entry point (float32 rounding of lse aside)
+    full = oracle.prefill_scores(*inputs, cfg)
+    np.testing.assert_allclose(got, full, rtol=max(H.rtol_of(w), 1e-4), atol=H.atol_of(w, opts))
+    return inputs, cfg, lse32, got
+
+
+@pytest.mark.parametrize("opts", [
+    Opts(scale_mode=SCALE_FIXED, fixed_scale=0.125),                       # the forward's scale
+    Opts(scale_mode=SCALE_FIXED, fixed_scale=0.125, value_prior=False),
+    Opts(window=512, scale_mode=SCALE_FIXED, fixed_scale=0.125, value_prior=False),  # H2O
+    Opts(),                                                                # adaptive-scale lse
+])
+def test_scores_from_lse_fp32(opts):
+    check_scores_from_lse(synth.C1, opts)
+
+
+@pytest.mark.parametrize("opts", [
+    Opts(scale_mode=SCALE_FIXED, fixed_scale=1 / math.sqrt(128)),
+    Opts(scale_mode=SCALE_FIXED, fixed_scale=1 / math.sqrt(128), value_prior=False),
+    Opts(window=1536, scale_mode=SCALE_FIXED, fixed_scale=1 / math.sqrt(128), value_prior=False),
+    Opts(window=1536, scale_mode=SCALE_FIXED, fixed_scale=1 / math.sqrt(128)),
+    Opts(window=100, pool=31),
+])
+def test_scores_from_lse_bf16(opts):
+    check_scores_from_lse(BF, opts)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(seq_len=1573, window=37, budget=211, recent=19),                      # ragged tail
+    dict(seq_len=640, n_q_heads=16, n_kv_heads=2, window=48, budget=100, recent=10),  # G=8
+    dict(seq_len=520, head_dim=64, n_q_heads=4, n_kv_heads=2, window=20, budget=64, recent=8),
+    dict(seq_len=300, batch=3, n_q_heads=2, n_kv_heads=1, window=300, budget=50, recent=5),
+    dict(seq_len=31, n_q_heads=2, n_kv_heads=2, window=31, budget=8, recent=8),       # below one tile
+])
+def test_scores_from_lse_bf16_shapes(kw):
+    w = synth.scaled(BF, name="bf16_lse_variant", **kw)
+    check_scores_from_lse(w, Opts(scale_mode=SCALE_FIXED, fixed_scale=w.head_dim ** -0.5))
+
+
+def test_scores_from_lse_follow_the_given_normaliser():
+    """A normaliser shifted by log 2 for one query head halves that head's share: the library
+    uses the caller's values, it does not renormalise."""
+    opts = Opts(scale_mode=SCALE_FIXED, fixed_scale=1 / math.sqrt(128), value_prior=False)
+    inputs, cfg, lse32, _ = check_scores_from_lse(BF, opts)
+    shifted = lse32.copy()
+    shifted[:, 1] += np.float32(math.log(2.0))
+    got = H.run_scores_from_lse_gpu(BF, opts, inputs, shifted)
+    want = oracle.prefill_scores_lse(*inputs, shifted.astype(np.float64), cfg)
+    H.assert_scores_close(got, want, BF, opts)
+    assert np.max(np.abs(got[:, 0] - oracle.prefill_scores(*inputs, cfg)[:, 0])) > 1e-3
+
+
 def test_strided_inputs_token_major_layout():
     """Q/K/V stored [b, n, h, d] and passed by strides give the same result."""
     import torch
