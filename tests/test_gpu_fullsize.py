@@ -90,6 +90,43 @@ def test_full_accumulation_at_32k_by_closed_form_and_invariant():
             np.testing.assert_allclose(got.sum(-1), G * n, rtol=1e-4)
 
 
+def test_windowed_scores_at_128k_by_closed_form_and_invariant():
+    """A 131072-token context (beyond the oracle in reasonable time): with scale 0 every row
+    is uniform, so S_j = G (H_n - H_max(j, n-r)) exactly; with the adaptive scale the scores
+    total G * r; and the retained set of the closed-form scores is the oracle's."""
+    import torch
+    from paper_2506_03762_amd import binding as B
+    n, r, G, hk, d = 131072, 64, 4, 2, 128
+    w = synth.scaled(synth.C3, name="c3_128k", seq_len=n, n_q_heads=G * hk, n_kv_heads=hk,
+                     budget=4096)
+    g = torch.Generator(device="cuda"); g.manual_seed(77)
+    q, k, v = (torch.randn((1, hh, n, d), device="cuda", generator=g).to(torch.bfloat16)
+               for hh in (G * hk, hk, hk))
+    harm = np.concatenate([[0.0], np.cumsum(1.0 / np.arange(1, n + 1))])
+    want = G * (harm[n] - harm[np.maximum(np.arange(n), n - r)])
+    for scale_mode, scale, check in ((oracle.SCALE_FIXED, 0.0, "closed"),
+                                     (oracle.SCALE_ADAPTIVE, 0.0, "total")):
+        opts = Opts(scale_mode=scale_mode, fixed_scale=scale, value_prior=False)
+        p = H.gpu_params(w, opts).with_strides(q, k, v)
+        ws = B.alloc_workspace(p)
+        ws.fill_(0xA5)
+        sc = torch.full((1, hk, n), float("nan"), dtype=torch.float32, device="cuda")
+        B.aha_prefill_scores(p, q, k, v, sc, ws)
+        got = sc.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got))
+        if check == "closed":
+            for h in range(hk):
+                np.testing.assert_allclose(got[0, h], want, rtol=2e-5, atol=1e-9)
+            idx = torch.empty((1, hk, w.budget), dtype=torch.int32, device="cuda")
+            B.aha_select_topk(p, sc, idx)
+            # the scores decrease with the position before the window: the first B_s tokens
+            # (ties between equal float32 values go to the lower position) and the recents
+            ref = oracle.select_topk(got, w.budget, w.recent)
+            assert np.array_equal(idx.cpu().numpy(), ref)
+        else:
+            np.testing.assert_allclose(got.sum(-1), G * r, rtol=1e-4)
+
+
 def test_c4_batched_decode_256_steps():
     w = synth.C4
     print("case", w.name, flush=True)

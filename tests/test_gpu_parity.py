@@ -207,6 +207,9 @@ def topk_both(scores32, budget, recent):
 @pytest.mark.parametrize("n,budget,recent", [
     (32768, 2048, 64), (32768, 1024, 64), (16384, 3276, 64), (4096, 512, 64), (1000, 1000, 10),
     (777, 1, 0), (777, 1, 1), (5, 3, 1), (1, 1, 0), (40000, 5000, 100),
+    (65600, 4096, 64),      # the last length whose keys still fit the register file
+    (100000, 9000, 100),    # beyond it: keys are re-read in every pass
+    (131072, 8192, 128),
 ])
 def test_topk_bit_exact_on_random_and_tied_scores(n, budget, recent):
     rng = np.random.default_rng(n + budget)
