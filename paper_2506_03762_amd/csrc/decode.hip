@@ -369,8 +369,9 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
     }
 }
 
-// Stage 2, one workgroup per (batch, KV head): merge the partial outputs,
-// update the running scores from the stored dots and pick the victim.
+// Stage 2, two workgroups per (batch, KV head) that share nothing but their inputs: one
+// merges the partial outputs, the other updates the running scores from the stored dots
+// and picks the victim (side by side they take the time of the longer one).
 constexpr int kMergeThreads = 1024;
 
 template <int ESIZE, int D, int G>
@@ -427,12 +428,13 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
                 pr[u] = g.logical_pos - 1;
             }
     };
-    fetch(0);
+    const bool output_role = blockIdx.y == 0;  // workgroup-uniform
+    if (!output_role) fetch(0);
     const int ogi = tid / D, oc = tid % D;  // this thread's output element (tid < G * D)
     float x[XB];
 #pragma unroll
     for (int u = 0; u < XB; ++u)
-        x[u] = (tid < G * D && u < nsplit) ? part[(u * G + ogi) * (D + 2) + oc] : 0.f;
+        x[u] = (output_role && tid < G * D && u < nsplit) ? part[(u * G + ogi) * (D + 2) + oc] : 0.f;
 
     if (tid < nsplit * G) {
         s_pm[tid / G][tid % G] = my_pm;
@@ -444,7 +446,8 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) mx[gi] = wave_max(lane < nsplit ? s_pm[lane][gi] : -INFINITY);
 
-    if (tid < G * D) {
+    if (output_role) {
+        if (tid >= G * D) return;
         float num = 0.f, den = 0.f;
 #pragma unroll
         for (int u = 0; u < XB; ++u)
@@ -464,6 +467,7 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
             ((uint16_t *)g.out)[oi] = (uint16_t)f32_to_bf16_rne(v);
         else
             ((float *)g.out)[oi] = v;
+        return;
     }
     // score softmax over all live slots, from the stored raw dots; four slots per thread
     // and batch are fetched together so that the loads overlap
@@ -534,7 +538,7 @@ static hipError_t launch_g(const DecodeGeom &g, const DecodePlan &pl, void *ws, 
         float *ws_w = (float *)ws;
         float *ws_part = (float *)((char *)ws + pl.off_part);
         const size_t smem1 = (size_t)(g.G * pl.sps + 4 * g.G * D) * sizeof(float);
-        dim3 g1(pl.nsplit, g.batch * g.Hkv), g2(g.batch * g.Hkv);
+        dim3 g1(pl.nsplit, g.batch * g.Hkv), g2(g.batch * g.Hkv, 2);
 #define AHA_DECS(GG)                                                                             \
     {                                                                                            \
         hipLaunchKernelGGL((decode_split_kernel<ESIZE, D, GG>), g1, dim3(256), smem1, st, g,     \
