@@ -507,7 +507,9 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
 
     // the first key block is requested before everything else: its latency is the longest
     bf16x8 a0[kMB][D / 16];
-    if (SINGLE) load_a<D>(kbase, g.ks[2], key_begin + wave * kWaveKeys, key_end, lane, a0);
+    // (the windowed pass walks its key range from the last step to the first)
+    const int last_step = key_begin + (key_end - key_begin - 1) / kWgKeys * kWgKeys;
+    if (SINGLE) load_a<D>(kbase, g.ks[2], last_step + wave * kWaveKeys, key_end, lane, a0);
 
     // this thread's share of the value prior's per-tile maxima (requested here, reduced
     // during the first tile set-up)
@@ -634,12 +636,15 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             write_scores(col, kb, gam);
         };
         // (unconditional prefetch, as in pass 1)
-        for (int kb0 = key_begin; kb0 < key_end; kb0 += 2 * kWgKeys) {
-            const int k1 = kb0 + kWgKeys, k2 = k1 + kWgKeys;
-            load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, key_end, lane, a1);
+        for (int kb0 = last_step; kb0 >= key_begin; kb0 -= 2 * kWgKeys) {
+            const int k1 = kb0 - kWgKeys, k2 = k1 - kWgKeys;
+            // before the range: kb = key_end makes every row read the range's last one
+            load_a<D>(kbase, g.ks[2], k1 >= key_begin ? k1 + wave * kWaveKeys : key_end, key_end,
+                      lane, a1);
             step(a0, kb0);
-            if (k1 >= key_end) break;
-            load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, key_end, lane, a0);
+            if (k1 < key_begin) break;
+            load_a<D>(kbase, g.ks[2], k2 >= key_begin ? k2 + wave * kWaveKeys : key_end, key_end,
+                      lane, a0);
             step(a1, k1);
         }
     } else {
