@@ -97,17 +97,26 @@ __device__ __forceinline__ void q_tile_commit(const QTileRegs<D, NB> &t, int tid
     }
 }
 
+// Per-row scale and position of the tile (one row per thread: a tile has at most 256 rows).
+// The scale is requested here and stored by q_tile_meta, so that other loads can be issued
+// in between.
+template <int D, int NB>
+__device__ __forceinline__ float q_tile_scale_request(const ScoreGeom &g, int rho0, int tid,
+                                                      const float *lam_tab) {
+    static_assert(TileSmem<D, NB>::ROWS <= 256, "one tile row per thread");
+    const int rho = rho0 + min(tid, TileSmem<D, NB>::ROWS - 1);
+    return lam_tab[rho < g.R ? rho % g.r : 0];
+}
 template <int D, int NB>
 __device__ __forceinline__ void q_tile_meta(const ScoreGeom &g, const RowMap &rm, int rho0,
-                                            int tid, const float *lam_tab, float *sLam, int *sPos,
+                                            int tid, float lam_requested, float *sLam, int *sPos,
                                             int *sBlk) {
     using S = TileSmem<D, NB>;
-    for (int rr = tid; rr < S::ROWS; rr += 256) {
-        const int rho = rho0 + rr;
+    if (tid < S::ROWS) {
+        const int rho = rho0 + tid;
         const bool ok = rho < g.R;
-        const int ii = ok ? rho % g.r : 0;
-        sPos[rr] = ok ? g.n - g.r + ii : -1;
-        sLam[rr] = ok ? lam_tab[ii] : 0.f;
+        sPos[tid] = ok ? g.n - g.r + rho % g.r : -1;
+        sLam[tid] = ok ? lam_requested : 0.f;
     }
     if (tid < NB) {
         sBlk[tid] = rm.max_pos(rho0 + tid * 32, rho0 + tid * 32 + 32);
@@ -295,15 +304,25 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
             continue;
         }
         if (seg) __syncthreads();  // the previous tile (and its reduction buffer) is done with
-        // the first key block is requested before the query tile, so both latencies overlap
+        // The query tile (served by the L2 after its first touch) is requested first and the
+        // first key block (from HBM, behind every other workgroup's) right after it: loads
+        // return in order, so the tile is in LDS and the barrier passed while the keys are
+        // still on their way.
         const int kb_first = key_begin + wave * kWaveKeys;
         bf16x8 a0[kMB][D / 16], a1[kMB][D / 16];  // the next key block loads while one multiplies
-        load_a<D>(kbase, g.ks[2], kb_first, key_end, lane, a0);
         {
+            // (the thread index goes through an opaque move: the set-up's addresses are then
+            // recomputed per tile instead of being kept across the main loop, where they
+            // would be spilled and their reload would wait for every load in flight)
+            int tid_s = tid;
+            asm volatile("" : "+v"(tid_s));
             QTileRegs<D, NB> qt_regs;
-            q_tile_request<D, NB>(g, b, h, rho0, tid, qt_regs);
-            q_tile_meta<D, NB>(g, rm, rho0, tid, lam_tab, sLam, sPos, sBlk);
-            q_tile_commit<D, NB>(qt_regs, tid, sQ);
+            q_tile_request<D, NB>(g, b, h, rho0, tid_s, qt_regs);
+            const float lam_req = q_tile_scale_request<D, NB>(g, rho0, tid_s, lam_tab);
+            __builtin_amdgcn_sched_barrier(0);  // the key block is requested last
+            load_a<D>(kbase, g.ks[2], kb_first, key_end, lane, a0);
+            q_tile_meta<D, NB>(g, rm, rho0, tid_s, lam_req, sLam, sPos, sBlk);
+            q_tile_commit<D, NB>(qt_regs, tid_s, sQ);
         }
         __syncthreads();
 
@@ -505,11 +524,9 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     int key_begin = wg_in_z * wg_keys;
     int key_end = min(g.n, key_begin + wg_keys);
 
-    // the first key block is requested before everything else: its latency is the longest
     bf16x8 a0[kMB][D / 16];
     // (the windowed pass walks its key range from the last step to the first)
     const int last_step = key_begin + (key_end - key_begin - 1) / kWgKeys * kWgKeys;
-    if (SINGLE) load_a<D>(kbase, g.ks[2], last_step + wave * kWaveKeys, key_end, lane, a0);
 
     // this thread's share of the value prior's per-tile maxima (requested here, reduced
     // during the first tile set-up)
@@ -519,7 +536,9 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
 
     // query tile qt -> LDS, with the log-sum-exp of its rows folded from pass 1's chunks
     static_assert(S::ROWS <= 256, "one thread folds the statistics of one tile row");
-    auto load_tile = [&](int qt) {
+    // `first_kb`: the wave's first key block of the tile, requested right behind the tile's
+    // own (L2-served) loads so that those are not queued behind the keys coming from HBM
+    auto load_tile = [&](int qt, int first_kb) {
         const int rho0 = qt * S::ROWS;
         // Full accumulation sets up a tile per segment: there the thread index and the chunk
         // count go through an opaque move, so that the set-up's address arithmetic is
@@ -543,7 +562,10 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
                                  (tid < S::ROWS ? tid : 0);
             q_tile_request<D, NB>(g, b, h, rho0, tid, qt_regs);
             chunk_request(psrc, S::ROWS, 0, nchunks_t, ch);
-            q_tile_meta<D, NB>(g, rm, rho0, tid, lam_tab, sLam, sPos, sBlk);
+            const float lam_req = q_tile_scale_request<D, NB>(g, rho0, tid, lam_tab);
+            __builtin_amdgcn_sched_barrier(0);  // the key block is requested last
+            load_a<D>(kbase, g.ks[2], first_kb, key_end, lane, a0);
+            q_tile_meta<D, NB>(g, rm, rho0, tid, lam_req, sLam, sPos, sBlk);
             if (gmax_pending) {
                 for (int t = tid + 256; t < n_vtiles; t += 256)
                     gm = fmaxf(gm, gblockmax[z * n_vtiles + t]);
@@ -623,7 +645,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     };
 
     if constexpr (SINGLE) {
-        load_tile(0);
+        load_tile(0, last_step + wave * kWaveKeys);
         bf16x8 a1[kMB][D / 16];
         auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb0) {
             const int kb = kb0 + wave * kWaveKeys;
@@ -664,8 +686,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             if (key_begin >= key_end) continue;  // workgroup-uniform
             const int rho0 = sg.qt * S::ROWS;
             if (seg) __syncthreads();  // the previous tile is done with
-            load_a<D>(kbase, g.ks[2], key_begin + wave * kWaveKeys, key_end, lane, a0);
-            load_tile(sg.qt);
+            load_tile(sg.qt, key_begin + wave * kWaveKeys);
             float ginv = 1.f;
             if (g.value_prior)
                 ginv = 1.f / fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3]));
