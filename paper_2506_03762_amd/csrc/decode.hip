@@ -58,27 +58,38 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     const int rg = tid / LPR, sub = tid % LPR;
     char *kcz = (char *)g.kc + (int64_t)z * g.slots * ROWB;
     char *vcz = (char *)g.vc + (int64_t)z * g.slots * ROWB;
-    const char *knew = (const char *)g.k_new + (int64_t)z * ROWB;
-    const char *vnew = (const char *)g.v_new + (int64_t)z * ROWB;
     float *fcz = g.fc + (int64_t)z * g.slots;
     int32_t *posz = g.pos + (int64_t)z * g.slots;
 
-    float qr[G][CH];
+    // The new token's rows and the queries are requested together with the first cache rows:
+    // the row of the free slot is read like any other and replaced afterwards, so no load
+    // waits for the free-slot index.
+    const u32x4 knw = *(const u32x4 *)((const char *)g.k_new + (int64_t)z * ROWB + sub * 16);
+    const u32x4 vnw = *(const u32x4 *)((const char *)g.v_new + (int64_t)z * ROWB + sub * 16);
+    u32x4 qw[G];
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) {
-        const char *qp = (const char *)g.q + ((int64_t)(b * g.Hq + h * G + gi)) * ROWB + sub * 16;
-        unpack<ESIZE>(*(const u32x4 *)qp, qr[gi]);
-    }
+    for (int gi = 0; gi < G; ++gi)
+        qw[gi] = *(const u32x4 *)((const char *)g.q + ((int64_t)(b * g.Hq + h * G + gi)) * ROWB + sub * 16);
 
     // ---- raw dots over the live slots (the new key stands in for slot fs) ----
+    // cache rows per thread requested before the first is used (fewer for wide groups,
+    // whose queries and outputs fill the 128 registers a thread of this workgroup has)
+    constexpr int PF = G <= 2 ? 8 : G <= 4 ? 4 : 2;
+    u32x4 kpf[PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+        kpf[u] = *(const u32x4 *)(kcz + (int64_t)min(rg + u * RP, live - 1) * ROWB + sub * 16);
+    float qr[G][CH];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) unpack<ESIZE>(qw[gi], qr[gi]);
     float mloc[G];
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) mloc[gi] = -INFINITY;
-#pragma unroll 4
-    for (int s = rg; s < live; s += RP) {
-        const char *src = (s == fs) ? knew : kcz + (int64_t)s * ROWB;
-        const u32x4 kw = *(const u32x4 *)(src + sub * 16);
-        if (s == fs) *(u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16) = kw;
+    auto dots = [&](int s, u32x4 kw) {
+        if (s == fs) {
+            kw = knw;
+            *(u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16) = kw;
+        }
         float kf[CH];
         unpack<ESIZE>(kw, kf);
 #pragma unroll
@@ -90,7 +101,18 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
             if (sub == 0) s_w[gi * live + s] = w;
             mloc[gi] = fmaxf(mloc[gi], w);
         }
-    }
+    };
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+        if (rg + u * RP < live) dots(rg + u * RP, kpf[u]);
+#pragma unroll 8
+    for (int s = rg + PF * RP; s < live; s += RP)
+        dots(s, *(const u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16));
+    // the first value rows travel while the softmax statistics are formed
+    u32x4 vpf[PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+        vpf[u] = *(const u32x4 *)(vcz + (int64_t)min(rg + u * RP, live - 1) * ROWB + sub * 16);
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) {
         const float m = wave_max(mloc[gi]);
@@ -174,11 +196,11 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     for (int gi = 0; gi < G; ++gi)
 #pragma unroll
         for (int c = 0; c < CH; ++c) o[gi][c] = 0.f;
-#pragma unroll 4
-    for (int s = rg; s < live; s += RP) {
-        const char *src = (s == fs) ? vnew : vcz + (int64_t)s * ROWB;
-        const u32x4 vw = *(const u32x4 *)(src + sub * 16);
-        if (s == fs) *(u32x4 *)(vcz + (int64_t)s * ROWB + sub * 16) = vw;
+    auto weigh = [&](int s, u32x4 vw) {
+        if (s == fs) {
+            vw = vnw;
+            *(u32x4 *)(vcz + (int64_t)s * ROWB + sub * 16) = vw;
+        }
         float vf[CH];
         unpack<ESIZE>(vw, vf);
 #pragma unroll
@@ -187,7 +209,13 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
 #pragma unroll
             for (int c = 0; c < CH; ++c) o[gi][c] = fmaf(p, vf[c], o[gi][c]);
         }
-    }
+    };
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+        if (rg + u * RP < live) weigh(rg + u * RP, vpf[u]);
+#pragma unroll 8
+    for (int s = rg + PF * RP; s < live; s += RP)
+        weigh(s, *(const u32x4 *)(vcz + (int64_t)s * ROWB + sub * 16));
     float *s_o = s_w;  // [waves][G][D]
 #pragma unroll
     for (int gi = 0; gi < G; ++gi)
