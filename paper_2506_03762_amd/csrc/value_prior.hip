@@ -60,6 +60,9 @@ __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, 
     const int rows_per_pass = 256 / lpr;
     const int sub = tid % lpr, rloc = tid / lpr;
 
+    // V is read exactly once, with streaming loads: kept out of the caches it leaves them to
+    // the keys, which the two score passes read twice (pass 1 ran 5 % faster at the
+    // full-depth shape; the same hint on pass 2's key loads made that pass 35 % slower).
     // nine independent 16-byte loads in flight per lane: with 16 lanes per row a tile and
     // its pooling halo (256 + 6 rows) then take two batches, not three (many more in flight
     // measured slower at the large shapes)
@@ -69,7 +72,7 @@ __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int row = min(row0 + u * rows_per_pass, hi - 1);
-            w[u] = *(const u32x4 *)(vbase + (int64_t)ESIZE * row * g.vs[2] + sub * 16);
+            w[u] = __builtin_nontemporal_load((const u32x4 *)(vbase + (int64_t)ESIZE * row * g.vs[2] + sub * 16));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
