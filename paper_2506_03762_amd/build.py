@@ -17,7 +17,7 @@ SOURCES = ["aha_api.hip", "value_prior.hip", "score_f32.hip", "score_bf16.hip", 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wno-unused-value", "-Wno-unknown-attributes", "-Wno-pass-failed",
+    "-Wno-unused-value", "-Wno-unknown-attributes",
 ]
 
 

@@ -105,9 +105,16 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
 #pragma unroll
     for (int u = 0; u < PF; ++u)
         if (rg + u * RP < live) dots(rg + u * RP, kpf[u]);
-#pragma unroll 8
-    for (int s = rg + PF * RP; s < live; s += RP)
-        dots(s, *(const u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16));
+    // the rest in batches of PF rows per thread, requested together (written out by hand:
+    // a loop with lane exchanges in its body is not unrolled by the compiler)
+    for (int sb = rg + PF * RP; sb < live; sb += PF * RP) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u)
+            kpf[u] = *(const u32x4 *)(kcz + (int64_t)min(sb + u * RP, live - 1) * ROWB + sub * 16);
+#pragma unroll
+        for (int u = 0; u < PF; ++u)
+            if (sb + u * RP < live) dots(sb + u * RP, kpf[u]);
+    }
     // the first value rows travel while the softmax statistics are formed
     u32x4 vpf[PF];
 #pragma unroll
@@ -317,9 +324,16 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
         const int s = s0 + rg + u * RP;
         if (s < s1) dots(s, kpf[u]);
     }
-#pragma unroll 4
-    for (int s = s0 + rg + PF * RP; s < s1; s += RP)
-        dots(s, *(const u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16));
+    // (the rest in batches written out by hand: a loop with lane exchanges in its body is
+    // not unrolled by the compiler)
+    for (int sb = s0 + rg + PF * RP; sb < s1; sb += PF * RP) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u)
+            kpf[u] = *(const u32x4 *)(kcz + (int64_t)min(sb + u * RP, s1 - 1) * ROWB + sub * 16);
+#pragma unroll
+        for (int u = 0; u < PF; ++u)
+            if (sb + u * RP < s1) dots(sb + u * RP, kpf[u]);
+    }
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) {
         const float m = wave_max(mloc[gi]);
