@@ -183,16 +183,18 @@ __device__ __forceinline__ void stats_update(const f32x16 (&acc)[kMB], float lam
     const float tmax = amax == -INFINITY ? -INFINITY : amax * lam;
     const float mn = fmaxf(m, tmax);
     const float mref = mn == -INFINITY ? 0.f : mn;
-    float sum = 0.f;
+    // four partial sums: independent chains, so that the exponentials' result latency is
+    // covered by other work instead of wait states
+    float sum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int mb = 0; mb < kMB; ++mb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             float e = fast_exp2(fmaf(acc[mb][v], lam, -mref));
             if (MASK && acc_key(kb, mb, v, lane) > pos) e = 0.f;
-            sum += e;
+            sum[v & 3] += e;
         }
-    s = s * fast_exp2(m - mref) + sum;
+    s = s * fast_exp2(m - mref) + ((sum[0] + sum[1]) + (sum[2] + sum[3]));
     m = mn;
 }
 
