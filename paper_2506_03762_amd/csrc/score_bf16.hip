@@ -310,7 +310,16 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
         // first key block (from HBM, behind every other workgroup's) right after it: loads
         // return in order, so the tile is in LDS and the barrier passed while the keys are
         // still on their way.
-        const int kb_first = key_begin + wave * kWaveKeys;
+        // The first tile of a pair walks its 256-key steps upwards, the partner downwards.
+        // Step i of the pair's common clock is then key step i for every workgroup still on
+        // its first tile and key step (steps of a full sequence) - i for every workgroup on
+        // its partner tile, whatever the pair: the workgroups of a problem, which share an
+        // XCD, read the same two key blocks at any time and find them in the L2.
+        const int nsteps = (key_end - key_begin + kWgKeys - 1) / kWgKeys;
+        const int kdir = seg ? -kWgKeys : kWgKeys;
+        const int k_at0 = (seg ? key_begin + (nsteps - 1) * kWgKeys : key_begin) + wave * kWaveKeys;
+        // this wave's key block of step i; past the last step: rows clamped to the range's end
+        auto kb_of = [&](int i) { return i < nsteps ? k_at0 + i * kdir : key_end; };
         bf16x8 a0[kMB][D / 16], a1[kMB][D / 16];  // the next key block loads while one multiplies
         {
             // (the thread index goes through an opaque move: the set-up's addresses are then
@@ -322,7 +331,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
             q_tile_request<D, NB>(g, b, h, rho0, tid_s, qt_regs);
             const float lam_req = q_tile_scale_request<D, NB>(g, rho0, tid_s, lam_tab);
             __builtin_amdgcn_sched_barrier(0);  // the key block is requested last
-            load_a<D>(kbase, g.ks[2], kb_first, key_end, lane, a0);
+            load_a<D>(kbase, g.ks[2], kb_of(0), key_end, lane, a0);
             q_tile_meta<D, NB>(g, rm, rho0, tid_s, lam_req, sLam, sPos, sBlk);
             q_tile_commit<D, NB>(qt_regs, tid_s, sQ);
         }
@@ -342,6 +351,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
 
         const int tile_min = rm.min_pos(rho0, rho0 + S::ROWS);
         auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb) {
+            if (kb >= key_end) return;  // (a wave past the range's ragged end)
             if (kb + kWaveKeys - 1 <= tile_min) {
                 // every row of the tile sees all 64 keys: no masks, no skipped blocks
 #pragma unroll
@@ -367,13 +377,12 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
         // that are never used): behind a branch the compiler can no longer tell how many
         // loads are in flight and would wait for the prefetch itself before the current
         // step.
-        for (int kb = kb_first; kb < key_end; kb += 2 * kWgKeys) {
-            const int k1 = kb + kWgKeys, k2 = k1 + kWgKeys;
-            load_a<D>(kbase, g.ks[2], k1, key_end, lane, a1);
-            step(a0, kb);
-            if (k1 >= key_end) break;
-            load_a<D>(kbase, g.ks[2], k2, key_end, lane, a0);
-            step(a1, k1);
+        for (int i = 0; i < nsteps; i += 2) {
+            load_a<D>(kbase, g.ks[2], kb_of(i + 1), key_end, lane, a1);
+            step(a0, kb_of(i));
+            if (i + 1 >= nsteps) break;
+            load_a<D>(kbase, g.ks[2], kb_of(i + 2), key_end, lane, a0);
+            step(a1, kb_of(i + 1));
         }
 
         // fold the two half-waves (same query column, different key rows)
@@ -688,7 +697,13 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             if (key_begin >= key_end) continue;  // workgroup-uniform
             const int rho0 = sg.qt * S::ROWS;
             if (seg) __syncthreads();  // the previous tile is done with
-            load_tile(sg.qt, key_begin + wave * kWaveKeys);
+            // (first tile upwards, partner downwards: see pass 1)
+            const int nsteps = (key_end - key_begin + kWgKeys - 1) / kWgKeys;
+            const int kdir = seg ? -kWgKeys : kWgKeys;
+            const int k_at0 = seg ? key_begin + (nsteps - 1) * kWgKeys : key_begin;
+            auto kb0_of = [&](int i) { return k_at0 + i * kdir; };
+            auto load_kb_of = [&](int i) { return i < nsteps ? kb0_of(i) + wave * kWaveKeys : key_end; };
+            load_tile(sg.qt, load_kb_of(0));
             float ginv = 1.f;
             if (g.value_prior)
                 ginv = 1.f / fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3]));
@@ -708,13 +723,12 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
                         unsafeAtomicAdd(&scores[(int64_t)z * g.n + j], tot * (gam[mb] * ginv));
                 }
             };
-            for (int kb0 = key_begin; kb0 < key_end; kb0 += 2 * kWgKeys) {
-                const int k1 = kb0 + kWgKeys, k2 = k1 + kWgKeys;
-                load_a<D>(kbase, g.ks[2], k1 + wave * kWaveKeys, key_end, lane, a1);
-                step(a0, kb0);
-                if (k1 >= key_end) break;
-                load_a<D>(kbase, g.ks[2], k2 + wave * kWaveKeys, key_end, lane, a0);
-                step(a1, k1);
+            for (int i = 0; i < nsteps; i += 2) {
+                load_a<D>(kbase, g.ks[2], load_kb_of(i + 1), key_end, lane, a1);
+                step(a0, kb0_of(i));
+                if (i + 1 >= nsteps) break;
+                load_a<D>(kbase, g.ks[2], load_kb_of(i + 2), key_end, lane, a0);
+                step(a1, kb0_of(i + 1));
             }
         }
     }
