@@ -223,7 +223,10 @@ static int32_t prefill_scores_impl(const aha_params *p, const void *q, const voi
     if (p->value_prior && (rc = check_ptr("v", v, 16))) return rc;
     const PrefillPlan pl = plan_prefill(p);
     if ((rc = check_ws(workspace, workspace_bytes, pl.bytes))) return rc;
-    if (pl.nchunks > 65535 || pl.n_qtiles > 2 * 65535 || pl.Z > 65535)
+    // the problem index is a grid's y dimension in the value-prior and fp32 launches; the bf16
+    // score launches are one-dimensional over all their workgroups
+    const int64_t score_wgs = (int64_t)pl.Z * ((pl.n_qtiles + 1) / 2) * pl.nchunks;
+    if (pl.Z > 65535 || score_wgs > (int64_t)1 << 30)
         return fail(AHA_ERR_UNSUPPORTED, "problem exceeds the launch grid limits");
     const ScoreGeom g = make_geom(p, q, k, v);
     hipStream_t st = (hipStream_t)stream;
