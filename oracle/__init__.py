@@ -164,6 +164,25 @@ def select_topk(scores, budget: int, recent: int):
     return idx.reshape(lead + (budget,))
 
 
+def pool_scores(scores, pool: int):
+    """Average-pooled scores (single-precision sums, as the selection ranks them)."""
+    scores = _f64(scores)
+    n = scores.shape[-1]
+    assert pool >= 1 and pool % 2 == 1
+    lead = scores.shape[:-1]
+    problems = int(np.prod(lead)) if lead else 1
+    out = np.empty((problems, n), dtype=np.float64)
+    _load().aha_oracle_pool_scores(_p(scores), _I64(problems), _I64(n), _I64(pool), _p(out))
+    return out.reshape(scores.shape)
+
+
+def select_topk_pooled(scores, budget: int, recent: int, score_pool: int):
+    """Selection that ranks the candidates by their pooled scores (score_pool = 1: select_topk)."""
+    if score_pool <= 1:
+        return select_topk(scores, budget, recent)
+    return select_topk(pool_scores(scores, score_pool), budget, recent)
+
+
 @dataclass
 class Cache:
     """Compact cache state; leading dims [batch, n_kv_heads]."""

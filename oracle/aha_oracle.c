@@ -337,6 +337,39 @@ void aha_oracle_select_topk(const double *scores, int64_t problems, int64_t n,
 }
 
 /* ------------------------------------------------------------------------
+ * Smoothing of the eviction scores before the selection (caption of the
+ * method's overview figure: pooling is applied to the refined scores so that
+ * the retained text is not sparsified excessively).
+ * READING: a 1-D average pool over tokens with the conventions of the value
+ * prior's pool (stride 1, odd width, mean over the taps inside [0, n)),
+ * applied to the refined scores of ALL n tokens; the pooled values only rank
+ * the candidates, the running scores F_0 stay the unpooled ones (Alg. 1).
+ * The pooled value decides an index set, so it is formed in the precision the
+ * GPU path uses for it: the scores rounded to single precision, summed left
+ * to right in single precision, divided by the number of taps.
+ *
+ * scores: [problems, n];  pooled: [problems, n]
+ * ---------------------------------------------------------------------- */
+void aha_oracle_pool_scores(const double *scores, int64_t problems, int64_t n,
+                            int64_t pool, double *pooled)
+{
+    int64_t half = (pool - 1) / 2;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t pr = 0; pr < problems; ++pr) {
+        const double *s = scores + pr * n;
+        double *o = pooled + pr * n;
+        for (int64_t j = 0; j < n; ++j) {
+            int64_t lo = j - half < 0 ? 0 : j - half;
+            int64_t hi = j + half > n - 1 ? n - 1 : j + half;
+            volatile float acc = 0.0f;  /* volatile: no widening or reassociation */
+            for (int64_t t = lo; t <= hi; ++t) acc = acc + (float)s[t];
+            volatile float q = acc / (float)(hi - lo + 1);
+            o[j] = (double)q;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------
  * Compaction (Alg. 1, Generation: K_S, V_S; F_0 = refined prefill score).
  * Slot s of the compact cache holds token idx[s]; slot `budget` is left free
  * for the first generated token (free_slot = budget).  Slots >= budget get

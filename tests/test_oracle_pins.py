@@ -329,6 +329,35 @@ def test_topk_ties_keep_lower_index():
 
 
 # -------------------------------------------------------- compaction ----
+def test_pooled_score_selection():
+    """Score smoothing before the selection: the pool against numpy (float32, left to right),
+    width 1 is the identity, a constant stays constant, and the selection is the plain
+    selection of the pooled array."""
+    rng = np.random.default_rng(50)
+    s = rng.random((3, 97)).astype(np.float32)
+    for pool in (1, 3, 7, 15):
+        h = (pool - 1) // 2
+        want = np.empty_like(s)
+        for pr in range(s.shape[0]):
+            for j in range(s.shape[1]):
+                lo, hi = max(0, j - h), min(s.shape[1] - 1, j + h)
+                acc = np.float32(0)
+                for t in range(lo, hi + 1):
+                    acc = np.float32(acc + s[pr, t])
+                want[pr, j] = np.float32(acc / np.float32(hi - lo + 1))
+        got = oracle.pool_scores(s.astype(np.float64), pool)
+        assert np.array_equal(got.astype(np.float32), want) and np.array_equal(got, want.astype(np.float64))
+        idx = oracle.select_topk_pooled(s.astype(np.float64), 20, 5, pool)
+        assert np.array_equal(idx, oracle.select_topk(want.astype(np.float64), 20, 5))
+    assert np.array_equal(oracle.pool_scores(s.astype(np.float64), 1), s.astype(np.float64))
+    c = np.full((1, 40), 0.375)
+    assert np.array_equal(oracle.pool_scores(c, 9), c)
+    # a lone spike spreads over its neighbours: with width 3 they outrank a slightly lower lone value
+    z = np.zeros((1, 30)); z[0, 10] = 3.0; z[0, 20] = 0.9
+    assert set(oracle.select_topk_pooled(z, 3, 0, 3)[0]) == {9, 10, 11}
+    assert set(oracle.select_topk(z, 3, 0)[0]) == {0, 10, 20}
+
+
 def test_compaction_is_a_gather():
     b, hk, n, d, B = 2, 3, 30, 4, 7
     K, V = rnd(35, b, hk, n, d), rnd(36, b, hk, n, d)
