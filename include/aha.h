@@ -71,6 +71,13 @@ enum { AHA_SCALE_FIXED = 0, AHA_SCALE_ADAPTIVE = 1 };
  *               maximum over the sequence of that (batch, KV head).
  *  n_q_heads    must be a multiple of n_kv_heads; the score of a KV head is
  *               the sum over the query heads that share it.
+ *  score_pool   smoothing of the scores before the selection (caption of the
+ *               method's overview figure): aha_select_topk ranks the
+ *               candidates by the average pool of the scores over tokens
+ *               (odd width score_pool, stride 1, edge-truncated mean over all
+ *               seq_len tokens, formed in fp32 left to right).  0 or 1: off.
+ *               The scores themselves, and with them the running scores that
+ *               aha_compact_kv seeds, are not changed.
  */
 typedef struct aha_params {
     int32_t batch;
@@ -90,6 +97,8 @@ typedef struct aha_params {
     int64_t q_stride[3];  /* elements: batch, head, token (prefill Q) */
     int64_t k_stride[3];  /* elements: batch, head, token (prefill K) */
     int64_t v_stride[3];  /* elements: batch, head, token (prefill V) */
+    int32_t score_pool;   /* 0 | odd, 1..255; used by aha_select_topk (and the workspace size) */
+    int32_t reserved;     /* must be 0 */
 } aha_params;
 
 /*
@@ -147,6 +156,10 @@ int32_t aha_prefill_scores_lse(const aha_params *p, const void *q, const void *k
  *          positions: the budget - recent highest-scoring tokens among
  *          positions < seq_len - recent (ties: lower position wins) followed
  *          by the `recent` last positions.
+ * With p->score_pool > 1 the candidates are ranked by their pooled scores,
+ * which are written to the workspace first (batch * n_kv_heads * seq_len
+ * floats; aha_workspace_bytes accounts for them); otherwise the workspace is
+ * not used and may be null.
  */
 int32_t aha_select_topk(const aha_params *p, const float *scores, int32_t *idx,
                         void *workspace, size_t workspace_bytes, void *stream);

@@ -49,6 +49,7 @@ class aha_params(ctypes.Structure):
         ("pool_kernel", ctypes.c_int32),
         ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
         ("v_stride", ctypes.c_int64 * 3),
+        ("score_pool", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -111,11 +112,12 @@ class Params:
     q_stride: tuple = (0, 0, 0)
     k_stride: tuple = (0, 0, 0)
     v_stride: tuple = (0, 0, 0)
+    score_pool: int = 0
 
     def c(self) -> aha_params:
         p = aha_params()
         for f in ("batch", "n_q_heads", "n_kv_heads", "head_dim", "seq_len", "window", "budget",
-                  "recent", "dtype", "scale_mode", "value_prior", "pool_kernel"):
+                  "recent", "dtype", "scale_mode", "value_prior", "pool_kernel", "score_pool"):
             setattr(p, f, int(getattr(self, f)))
         p.fixed_scale = float(self.fixed_scale)
         p.lambda_floor = float(self.lambda_floor)

@@ -78,6 +78,10 @@ static int32_t check_prefill(const aha_params *p, bool need_strides) {
                     p->pool_kernel);
     if ((int64_t)(p->n_q_heads / p->n_kv_heads) * p->window > (int64_t)1 << 30)
         return fail(AHA_ERR_UNSUPPORTED, "group * window is too large");
+    if (p->score_pool < 0 || p->score_pool > 255 || (p->score_pool > 1 && p->score_pool % 2 == 0))
+        return fail(AHA_ERR_INVALID_ARG, "score_pool (%d) must be 0 or odd and in [1, 255]",
+                    p->score_pool);
+    if (p->reserved != 0) return fail(AHA_ERR_INVALID_ARG, "reserved must be 0");
     if (need_strides) {
         if ((rc = check_stride("q", p->q_stride, p->dtype, p->head_dim))) return rc;
         if ((rc = check_stride("k", p->k_stride, p->dtype, p->head_dim))) return rc;
@@ -201,12 +205,18 @@ using namespace aha;
 
 extern "C" {
 
+// Selection: the pooled scores, when the scores are smoothed first.
+static size_t topk_ws_bytes(const aha_params *p) {
+    if (p->score_pool <= 1) return 0;
+    return align_up(sizeof(float) * (size_t)p->batch * p->n_kv_heads * p->seq_len, 256);
+}
+
 int32_t aha_workspace_bytes(const aha_params *p, size_t *out_bytes) {
     if (!out_bytes) return fail(AHA_ERR_INVALID_ARG, "out_bytes is null");
     int32_t rc = check_prefill(p, false);
     if (rc) return rc;
-    const size_t a = plan_prefill(p).bytes, d = plan_decode(p).bytes;
-    *out_bytes = a > d ? a : d;
+    const size_t a = plan_prefill(p).bytes, d = plan_decode(p).bytes, t = topk_ws_bytes(p);
+    *out_bytes = a > d ? (a > t ? a : t) : (d > t ? d : t);
     return AHA_OK;
 }
 
@@ -259,14 +269,14 @@ int32_t aha_prefill_scores_lse(const aha_params *p, const void *q, const void *k
 
 int32_t aha_select_topk(const aha_params *p, const float *scores, int32_t *idx, void *workspace,
                         size_t workspace_bytes, void *stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     int32_t rc = check_prefill(p, false);
     if (rc) return rc;
     if ((rc = check_ptr("scores", scores, 4)) || (rc = check_ptr("idx", idx, 4))) return rc;
+    const int pool = p->score_pool > 1 ? p->score_pool : 1;
+    if (pool > 1 && (rc = check_ws(workspace, workspace_bytes, topk_ws_bytes(p)))) return rc;
     return hip_result(launch_topk(scores, p->batch * p->n_kv_heads, p->seq_len, p->budget,
-                                  p->recent, idx, (hipStream_t)stream),
-                      "top-k kernel");
+                                  p->recent, pool, (float *)workspace, idx, (hipStream_t)stream),
+                      "top-k kernels");
 }
 
 int32_t aha_compact_kv(const aha_params *p, const void *k, const void *v, const float *scores,

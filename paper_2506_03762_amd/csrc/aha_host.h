@@ -55,8 +55,10 @@ hipError_t launch_score_f32(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
 hipError_t launch_score_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
                              float *scores, hipStream_t st, hipEvent_t mid, bool have_lse);
 // topk.hip
-hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent,
-                       int32_t *idx, hipStream_t st);
+// `pool` > 1: the candidates are ranked by the scores pooled over `pool` tokens, which are
+// written to `pooled` ([Z][n] floats) first.
+hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent, int pool,
+                       float *pooled, int32_t *idx, hipStream_t st);
 // compact.hip
 hipError_t launch_compact(const ScoreGeom &g, const float *scores, const int32_t *idx,
                           int budget, int slots, int dtype, void *kc, void *vc, float *fc,

@@ -320,9 +320,29 @@ static void launch_items(const float *scores, int Z, int n, int budget, int rece
                        n, budget, recent, idx);
 }
 
-hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent, int32_t *idx,
-                       hipStream_t st) {
+// Scores smoothed over tokens before the selection (caption of the method's overview
+// figure): average pool of odd width, stride 1, mean over the taps inside the sequence.
+// The pooled value decides which tokens are kept, so it is formed exactly as stated - the
+// taps added left to right in fp32, then one division - and not by a running sum.
+__global__ __launch_bounds__(256) void pool_scores_kernel(const float *__restrict__ scores, int n,
+                                                          int half, float *__restrict__ pooled) {
+    const int z = blockIdx.y, j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    const float *s = scores + (int64_t)z * n;
+    const int lo = max(0, j - half), hi = min(n - 1, j + half);
+    float acc = 0.f;
+    for (int t = lo; t <= hi; ++t) acc = __fadd_rn(acc, s[t]);
+    pooled[(int64_t)z * n + j] = __fdiv_rn(acc, (float)(hi - lo + 1));
+}
+
+hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent, int pool,
+                       float *pooled, int32_t *idx, hipStream_t st) {
     static_assert(sizeof(TopkSmem) < 64 * 1024, "top-k LDS must fit the default dynamic limit");
+    if (pool > 1) {
+        hipLaunchKernelGGL(pool_scores_kernel, dim3((n + 255) / 256, Z), dim3(256), 0, st, scores, n,
+                           (pool - 1) / 2, pooled);
+        scores = pooled;
+    }
     const int n_cand = n - recent;
     const int ipt = (n_cand + kTopkThreads - 1) / kTopkThreads;
     if (ipt <= 4) launch_items<4>(scores, Z, n, budget, recent, idx, st);

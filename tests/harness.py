@@ -28,6 +28,7 @@ class Opts:
     lambda_floor: float = -1.0
     value_prior: bool = True
     pool: int = 7
+    score_pool: int = 0                # > 1: the selection ranks pooled scores
 
 
 def rtol_of(w: synth.Workload) -> float:
@@ -59,10 +60,12 @@ def run_prefill_oracle(w: synth.Workload, opts: Opts = Opts(), inputs=None, laye
     Q, K, V = inputs if inputs is not None else synth.make_prefill(w, layer)
     cfg = oracle_cfg(w, opts)
     S = oracle.prefill_scores(Q, K, V, cfg)
-    idx = oracle.select_topk(S, w.budget, w.recent)
+    idx = oracle.select_topk_pooled(S, w.budget, w.recent, opts.score_pool)
     cache = oracle.compact_kv(K.astype(np.float64), V.astype(np.float64), S, idx,
                               slots=w.budget + 1)
-    return Result(S, idx, cache)
+    # the scores that ranked the candidates (near-ties are judged on these)
+    rank = oracle.pool_scores(S, opts.score_pool) if opts.score_pool > 1 else S
+    return Result(S, idx, cache, extra=dict(rank_scores=rank))
 
 
 # --------------------------------------------------------------------- GPU --
@@ -82,7 +85,7 @@ def gpu_params(w: synth.Workload, opts: Opts = Opts()):
                     dtype=B.AHA_BF16 if w.dtype == "bf16" else B.AHA_F32,
                     scale_mode=opts.scale_mode, fixed_scale=opts.fixed_scale,
                     lambda_floor=opts.lambda_floor, value_prior=1 if opts.value_prior else 0,
-                    pool_kernel=opts.pool)
+                    pool_kernel=opts.pool, score_pool=opts.score_pool)
 
 
 def run_prefill_gpu(w: synth.Workload, opts: Opts = Opts(), inputs=None, layer=0,

@@ -38,9 +38,10 @@ def test_header_symbols_are_exported(lib):
 
 
 def test_struct_layout_matches_header():
-    # 14 four-byte fields then nine int64 strides
-    assert ctypes.sizeof(B.aha_params) == 14 * 4 + 9 * 8
+    # 14 four-byte fields, nine int64 strides, two four-byte fields
+    assert ctypes.sizeof(B.aha_params) == 14 * 4 + 9 * 8 + 2 * 4
     assert B.aha_params.q_stride.offset == 56
+    assert B.aha_params.score_pool.offset == 56 + 72
 
 
 def test_workspace_bytes(lib):
@@ -77,6 +78,9 @@ def call_prefill(lib, p, q=DUMMY, k=DUMMY, v=DUMMY, s=DUMMY, ws=DUMMY, nbytes=1 
     (dict(k_stride=(0, 0, 100)), B.AHA_ERR_INVALID_ARG),   # not a multiple of 8 elements
     (dict(q_stride=(0, 0, 64)), B.AHA_ERR_INVALID_ARG),    # rows overlap
     (dict(batch=0), B.AHA_ERR_INVALID_ARG),
+    (dict(score_pool=4), B.AHA_ERR_INVALID_ARG),
+    (dict(score_pool=-1), B.AHA_ERR_INVALID_ARG),
+    (dict(score_pool=257), B.AHA_ERR_INVALID_ARG),
 ])
 def test_bad_params_are_rejected(lib, kw, code):
     assert call_prefill(lib, good(**kw)) == code
@@ -120,6 +124,14 @@ def test_prefill_with_given_normalisers_validates(lib):
 def test_other_entry_points_validate(lib):
     p = good()
     cp = p.c()
+    # selection on pooled scores keeps them in the workspace
+    pooled = good(score_pool=7)
+    cpp = pooled.c()
+    assert B.workspace_bytes(pooled) >= 4 * pooled.batch * pooled.n_kv_heads * pooled.seq_len
+    assert lib.aha_select_topk(ctypes.byref(cpp), DUMMY, DUMMY, None, 0, None) == B.AHA_ERR_WORKSPACE
+    assert lib.aha_select_topk(ctypes.byref(cpp), DUMMY, DUMMY, DUMMY, 1024, None) == B.AHA_ERR_WORKSPACE
+    cpp.reserved = 1
+    assert lib.aha_select_topk(ctypes.byref(cpp), DUMMY, DUMMY, DUMMY, 1 << 40, None) == B.AHA_ERR_INVALID_ARG
     assert lib.aha_select_topk(ctypes.byref(cp), None, DUMMY, None, 0, None) == B.AHA_ERR_INVALID_ARG
     assert lib.aha_compact_kv(ctypes.byref(cp), DUMMY, DUMMY, DUMMY, DUMMY, DUMMY, DUMMY, DUMMY,
                               DUMMY, DUMMY, 512, None) == B.AHA_ERR_INVALID_ARG  # slots < B+1

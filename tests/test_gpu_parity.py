@@ -22,7 +22,7 @@ def check_prefill(w, opts=Opts(), decode_steps=0, layer=0):
     gpu = H.run_prefill_gpu(w, opts, inputs)
     ref = H.run_prefill_oracle(w, opts, inputs)
     H.assert_scores_close(gpu.scores, ref.scores, w, opts)
-    excused = H.assert_sets_match(gpu.idx, ref.idx, ref.scores, w)
+    excused = H.assert_sets_match(gpu.idx, ref.idx, ref.extra["rank_scores"], w)
     H.assert_compact_matches(gpu, w, inputs[1], inputs[2])
     if decode_steps:
         flips = H.run_and_check_decode(w, gpu, ref, decode_steps, opts)
@@ -193,15 +193,18 @@ def test_repeat_calls_are_bit_identical():
 
 
 # ------------------------------------------------------------------ top-k --
-def topk_both(scores32, budget, recent):
+def topk_both(scores32, budget, recent, score_pool=0):
     import torch
     from paper_2506_03762_amd import binding as B
     b, h, n = scores32.shape
     p = B.Params(batch=b, n_q_heads=h, n_kv_heads=h, head_dim=128, seq_len=n, window=1,
-                 budget=budget, recent=recent)
+                 budget=budget, recent=recent, score_pool=score_pool)
     idx = torch.full((b, h, budget), -5, dtype=torch.int32, device="cuda")
-    B.aha_select_topk(p, torch.from_numpy(scores32).cuda(), idx)
-    return idx.cpu().numpy(), oracle.select_topk(scores32.astype(np.float64), budget, recent)
+    ws = B.alloc_workspace(p)
+    ws.fill_(0xA5)
+    B.aha_select_topk(p, torch.from_numpy(scores32).cuda(), idx, ws)
+    return idx.cpu().numpy(), oracle.select_topk_pooled(scores32.astype(np.float64), budget, recent,
+                                                        score_pool)
 
 
 @pytest.mark.parametrize("n,budget,recent", [
@@ -221,6 +224,32 @@ def test_topk_bit_exact_on_random_and_tied_scores(n, budget, recent):
     for s in (heavy, tied, const, zeros, narrow):
         got, want = topk_both(s, budget, recent)
         assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("n,budget,recent,pool", [
+    (32768, 2048, 64, 7), (4096, 512, 64, 3), (1000, 300, 10, 15), (100000, 9000, 100, 5),
+    (37, 9, 3, 7), (5, 3, 1, 255),
+])
+def test_topk_on_pooled_scores_bit_exact(n, budget, recent, pool):
+    """Selection on smoothed scores: the pooled values are float32 sums in a fixed order on both
+    sides, so the retained sets agree bit for bit, ties included."""
+    rng = np.random.default_rng(n + pool)
+    heavy = np.exp(rng.standard_normal((2, 3, n)) * 3).astype(np.float32)
+    tied = (rng.integers(0, 7, (2, 3, n)) / 8.0).astype(np.float32)
+    spikes = np.zeros((1, 2, n), np.float32)
+    spikes[..., rng.integers(0, n, max(1, n // 50))] = 1.0
+    for s in (heavy, tied, spikes):
+        got, want = topk_both(s, budget, recent, pool)
+        assert np.array_equal(got, want)
+
+
+def test_prefill_with_pooled_selection_end_to_end():
+    """Scores -> pooled selection -> compaction -> decode: the retained set follows the pooled
+    ranking, the cache is seeded with the unpooled scores."""
+    gpu, ref, excused = check_prefill(BF, Opts(score_pool=7), decode_steps=4)
+    plain = H.run_prefill_oracle(BF, Opts(), synth.make_prefill(BF, 0))
+    assert not np.array_equal(ref.idx, plain.idx)     # the smoothing changes what is kept
+    check_prefill(synth.C1, Opts(score_pool=5), decode_steps=3)
 
 
 # ----------------------------------------------------------------- decode --
