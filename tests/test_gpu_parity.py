@@ -104,6 +104,33 @@ def test_c2_llama2_7b_layer():
     print("C2 excused near-ties:", excused)
 
 
+def test_large_logits_do_not_overflow():
+    """Queries and keys 20x larger than usual (raw dots in the thousands, scaled logits in the
+    hundreds): both passes work relative to the row maximum, so nothing overflows and the
+    near-one-hot rows still match the oracle.  Most keys then score below the float32 range
+    (the oracle's float64 still tells them apart), so they count as ties in the selection."""
+    for w, opts in ((BF, Opts()), (BF, Opts(window=1536, scale_mode=SCALE_FIXED, fixed_scale=0.3,
+                                            value_prior=False)),
+                    (synth.C1, Opts(scale_mode=SCALE_FIXED, fixed_scale=1.0))):
+        Q, K, V = synth.make_prefill(w, 0)
+        big = (synth.round_bf16(Q * 20.0), synth.round_bf16(K * 20.0), V) if w.dtype == "bf16" \
+            else ((Q * 20.0).astype(np.float32).astype(np.float64),
+                  (K * 20.0).astype(np.float32).astype(np.float64), V)
+        gpu = H.run_prefill_gpu(w, opts, big)
+        ref = H.run_prefill_oracle(w, opts, big)
+        assert np.all(np.isfinite(gpu.scores))
+        if w.dtype == "bf16":
+            H.assert_scores_close(gpu.scores, ref.scores, w, opts)
+        else:
+            # the relative error of exp(x) is the absolute error of x, and a float32 dot
+            # product 400x larger carries a 400x larger absolute error: 1e-5 becomes 4e-3
+            np.testing.assert_allclose(gpu.scores, ref.scores, rtol=4e-3, atol=1e-6)
+            continue
+        # scores below the float32 range are zero on the kernel's side: equal keys there
+        flushed = np.where(ref.scores < 1.2e-38, 0.0, ref.scores)
+        H.assert_sets_match(gpu.idx, ref.idx, flushed, w, max_excused_frac=1.0)
+
+
 # ------------------------------------------- scores from given normalisers --
 def check_scores_from_lse(w, opts, layer=0):
     """The row normalisers come from the oracle, rounded to float32 as a forward pass would
