@@ -104,6 +104,36 @@ def test_c2_llama2_7b_layer():
     print("C2 excused near-ties:", excused)
 
 
+def random_case(seed):
+    """One shape and switch set drawn from the whole argument space (seeded)."""
+    rng = np.random.default_rng([77, seed])
+    bf = bool(rng.integers(2))
+    n = int(rng.choice([rng.integers(2, 80), rng.integers(80, 600), rng.integers(600, 2200)]))
+    G = int(rng.choice([1, 2, 3, 4, 8]))
+    Hkv = int(rng.integers(1, 4))
+    budget = int(rng.integers(1, n + 1))
+    recent = int(rng.integers(0, budget + 1))
+    window = int(rng.choice([1, rng.integers(1, min(n, 96) + 1), n])) if rng.integers(4) == 0 \
+        else int(rng.integers(1, min(n, 96) + 1))
+    w = synth.scaled(BF if bf else synth.C1, name="random_%d" % seed, seq_len=n,
+                     batch=int(rng.integers(1, 3)), n_q_heads=G * Hkv, n_kv_heads=Hkv,
+                     head_dim=int(rng.choice([64, 128])), window=window, budget=budget,
+                     recent=recent)
+    fixed = rng.integers(3) == 0
+    opts = Opts(scale_mode=SCALE_FIXED if fixed else SCALE_ADAPTIVE,
+                fixed_scale=float(rng.uniform(0.0, 0.3)) if fixed else 0.0,
+                lambda_floor=float(rng.choice([-1.0, 0.0, 0.05])),
+                value_prior=bool(rng.integers(2)), pool=int(2 * rng.integers(0, 8) + 1),
+                score_pool=int(rng.choice([0, 0, 3, 7])))
+    return w, opts
+
+
+@pytest.mark.parametrize("seed", range(64))
+def test_random_shapes_and_switches(seed):
+    w, opts = random_case(seed)
+    check_prefill(w, opts, decode_steps=2 if w.budget > w.recent or w.recent > 0 else 0)
+
+
 def test_large_logits_do_not_overflow():
     """Queries and keys 20x larger than usual (raw dots in the thousands, scaled logits in the
     hundreds): both passes work relative to the row maximum, so nothing overflows and the
