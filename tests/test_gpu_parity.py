@@ -131,7 +131,7 @@ def random_case(seed):
 @pytest.mark.parametrize("seed", range(64))
 def test_random_shapes_and_switches(seed):
     w, opts = random_case(seed)
-    check_prefill(w, opts, decode_steps=2 if w.budget > w.recent or w.recent > 0 else 0)
+    check_prefill(w, opts, decode_steps=24 if seed % 4 == 0 else 2)
 
 
 def test_large_logits_do_not_overflow():
