@@ -80,13 +80,13 @@ enum { AHA_SCALE_FIXED = 0, AHA_SCALE_ADAPTIVE = 1 };
  *               aha_compact_kv seeds, are not changed.
  */
 typedef struct aha_params {
-    int32_t batch;
+    int32_t batch;        /* batch * n_kv_heads <= 65535 */
     int32_t n_q_heads;
     int32_t n_kv_heads;
     int32_t head_dim;     /* 64 or 128 */
-    int32_t seq_len;      /* n (prefill) ; ignored by aha_decode_step */
+    int32_t seq_len;      /* n (prefill), <= 2^30 ; ignored by aha_decode_step */
     int32_t window;       /* r, 1..seq_len */
-    int32_t budget;       /* B */
+    int32_t budget;       /* B, <= 2^30 */
     int32_t recent;       /* B_r */
     int32_t dtype;        /* AHA_F32 | AHA_BF16: element type of Q, K, V, caches, out */
     int32_t scale_mode;   /* AHA_SCALE_FIXED | AHA_SCALE_ADAPTIVE */

@@ -35,11 +35,15 @@ static int32_t check_common(const aha_params *p) {
     if (p->n_q_heads % p->n_kv_heads != 0)
         return fail(AHA_ERR_INVALID_ARG, "n_q_heads (%d) is not a multiple of n_kv_heads (%d)",
                     p->n_q_heads, p->n_kv_heads);
+    if ((int64_t)p->batch * p->n_kv_heads > 65535)  // a grid's y dimension in several launches
+        return fail(AHA_ERR_UNSUPPORTED, "batch * n_kv_heads (%lld) exceeds 65535",
+                    (long long)p->batch * p->n_kv_heads);
     if (p->dtype != AHA_F32 && p->dtype != AHA_BF16)
         return fail(AHA_ERR_INVALID_ARG, "dtype %d is neither AHA_F32 nor AHA_BF16", p->dtype);
     if (p->head_dim != 64 && p->head_dim != 128)
         return fail(AHA_ERR_UNSUPPORTED, "head_dim %d: only 64 and 128 are built", p->head_dim);
     if (p->budget < 1) return fail(AHA_ERR_INVALID_ARG, "budget must be >= 1");
+    if (p->budget > 1 << 30) return fail(AHA_ERR_UNSUPPORTED, "budget beyond 2^30");
     if (p->recent < 0 || p->recent > p->budget)
         return fail(AHA_ERR_INVALID_ARG, "recent (%d) must lie in [0, budget=%d]", p->recent,
                     p->budget);
@@ -66,6 +70,7 @@ static int32_t check_prefill(const aha_params *p, bool need_strides) {
     int32_t rc = check_common(p);
     if (rc) return rc;
     if (p->seq_len < 1) return fail(AHA_ERR_INVALID_ARG, "seq_len must be >= 1");
+    if (p->seq_len > 1 << 30) return fail(AHA_ERR_UNSUPPORTED, "seq_len beyond 2^30");
     if (p->budget > p->seq_len)
         return fail(AHA_ERR_INVALID_ARG, "budget (%d) exceeds seq_len (%d)", p->budget, p->seq_len);
     if (p->window < 1 || p->window > p->seq_len)
@@ -233,10 +238,9 @@ static int32_t prefill_scores_impl(const aha_params *p, const void *q, const voi
     if (p->value_prior && (rc = check_ptr("v", v, 16))) return rc;
     const PrefillPlan pl = plan_prefill(p);
     if ((rc = check_ws(workspace, workspace_bytes, pl.bytes))) return rc;
-    // the problem index is a grid's y dimension in the value-prior and fp32 launches; the bf16
-    // score launches are one-dimensional over all their workgroups
+    // the bf16 score launches are one-dimensional over all their workgroups
     const int64_t score_wgs = (int64_t)pl.Z * ((pl.n_qtiles + 1) / 2) * pl.nchunks;
-    if (pl.Z > 65535 || score_wgs > (int64_t)1 << 30)
+    if (score_wgs > (int64_t)1 << 30)
         return fail(AHA_ERR_UNSUPPORTED, "problem exceeds the launch grid limits");
     const ScoreGeom g = make_geom(p, q, k, v);
     hipStream_t st = (hipStream_t)stream;

@@ -78,6 +78,9 @@ def call_prefill(lib, p, q=DUMMY, k=DUMMY, v=DUMMY, s=DUMMY, ws=DUMMY, nbytes=1 
     (dict(k_stride=(0, 0, 100)), B.AHA_ERR_INVALID_ARG),   # not a multiple of 8 elements
     (dict(q_stride=(0, 0, 64)), B.AHA_ERR_INVALID_ARG),    # rows overlap
     (dict(batch=0), B.AHA_ERR_INVALID_ARG),
+    (dict(seq_len=(1 << 30) + 8, budget=512), B.AHA_ERR_UNSUPPORTED),
+    (dict(batch=70000), B.AHA_ERR_UNSUPPORTED),            # batch * KV heads beyond a grid dimension
+    (dict(batch=1 << 30, n_q_heads=64, n_kv_heads=64), B.AHA_ERR_UNSUPPORTED),   # product overflows 32 bits
     (dict(score_pool=4), B.AHA_ERR_INVALID_ARG),
     (dict(score_pool=-1), B.AHA_ERR_INVALID_ARG),
     (dict(score_pool=257), B.AHA_ERR_INVALID_ARG),
