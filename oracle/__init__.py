@@ -165,7 +165,7 @@ def select_topk(scores, budget: int, recent: int):
 
 
 def pool_scores(scores, pool: int):
-    """Average-pooled scores (single-precision sums, as the selection ranks them)."""
+    """Average-pooled scores [..., n] (edge-truncated mean over `pool` tokens)."""
     scores = _f64(scores)
     n = scores.shape[-1]
     assert pool >= 1 and pool % 2 == 1

@@ -344,9 +344,6 @@ void aha_oracle_select_topk(const double *scores, int64_t problems, int64_t n,
  * prior's pool (stride 1, odd width, mean over the taps inside [0, n)),
  * applied to the refined scores of ALL n tokens; the pooled values only rank
  * the candidates, the running scores F_0 stay the unpooled ones (Alg. 1).
- * The pooled value decides an index set, so it is formed in the precision the
- * GPU path uses for it: the scores rounded to single precision, summed left
- * to right in single precision, divided by the number of taps.
  *
  * scores: [problems, n];  pooled: [problems, n]
  * ---------------------------------------------------------------------- */
@@ -361,10 +358,9 @@ void aha_oracle_pool_scores(const double *scores, int64_t problems, int64_t n,
         for (int64_t j = 0; j < n; ++j) {
             int64_t lo = j - half < 0 ? 0 : j - half;
             int64_t hi = j + half > n - 1 ? n - 1 : j + half;
-            volatile float acc = 0.0f;  /* volatile: no widening or reassociation */
-            for (int64_t t = lo; t <= hi; ++t) acc = acc + (float)s[t];
-            volatile float q = acc / (float)(hi - lo + 1);
-            o[j] = (double)q;
+            double acc = 0.0;
+            for (int64_t t = lo; t <= hi; ++t) acc += s[t];
+            o[j] = acc / (double)(hi - lo + 1);
         }
     }
 }

@@ -153,10 +153,14 @@ def assert_scores_close(got, want, w, opts: Opts = Opts()):
 
 def assert_sets_match(idx_gpu, idx_ref, scores_ref, w, max_excused_frac=0.01):
     """Retained sets equal, except indices whose oracle score is within rtol of
-    the oracle's threshold (the B_s-th largest candidate score).  Returns the
-    number of excused indices."""
-    rtol = rtol_of(w)
-    n, B, Br = w.seq_len, w.budget, w.recent
+    the oracle's threshold (the B_s-th largest candidate score).  `scores_ref` are the
+    oracle's float64 scores that ranked the candidates (the pooled ones when the selection
+    ranks pooled scores).  Returns the number of excused indices."""
+    return sets_match(idx_gpu, idx_ref, scores_ref, w.seq_len, w.budget, w.recent, rtol_of(w),
+                      max_excused_frac)
+
+
+def sets_match(idx_gpu, idx_ref, scores_ref, n, B, Br, rtol, max_excused_frac=0.01):
     assert idx_gpu.shape == idx_ref.shape
     excused = 0
     for p in np.ndindex(idx_ref.shape[:-1]):

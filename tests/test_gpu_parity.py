@@ -287,17 +287,25 @@ def test_topk_bit_exact_on_random_and_tied_scores(n, budget, recent):
     (32768, 2048, 64, 7), (4096, 512, 64, 3), (1000, 300, 10, 15), (100000, 9000, 100, 5),
     (37, 9, 3, 7), (5, 3, 1, 255),
 ])
-def test_topk_on_pooled_scores_bit_exact(n, budget, recent, pool):
-    """Selection on smoothed scores: the pooled values are float32 sums in a fixed order on both
-    sides, so the retained sets agree bit for bit, ties included."""
+def test_topk_on_pooled_scores(n, budget, recent, pool):
+    """Selection on smoothed scores.  The kernel pools in float32 (at most `pool` additions of
+    non-negative terms and one division: relative error <= (pool + 1) * 2^-24), the oracle in
+    float64, so the sets are equal except for candidates whose float64 pooled score lies
+    within that bound of the selection threshold; exactly representable inputs agree bit
+    for bit."""
     rng = np.random.default_rng(n + pool)
     heavy = np.exp(rng.standard_normal((2, 3, n)) * 3).astype(np.float32)
     tied = (rng.integers(0, 7, (2, 3, n)) / 8.0).astype(np.float32)
     spikes = np.zeros((1, 2, n), np.float32)
     spikes[..., rng.integers(0, n, max(1, n // 50))] = 1.0
-    for s in (heavy, tied, spikes):
+    rtol = (pool + 1) * 2.0 ** -24
+    for name, s in (("heavy", heavy), ("tied", tied), ("spikes", spikes)):
         got, want = topk_both(s, budget, recent, pool)
-        assert np.array_equal(got, want)
+        rank = oracle.pool_scores(s.astype(np.float64), pool)
+        excused = H.sets_match(got, want, rank, n, budget, recent, rtol)
+        print("pooled top-k", name, "excused near-ties:", excused, flush=True)
+        if name == "spikes":   # sums of ones are exact in both precisions
+            assert excused == 0
 
 
 def test_prefill_with_pooled_selection_end_to_end():
@@ -354,3 +362,53 @@ def test_decode_extra_slots_are_ignored():
     assert np.array_equal(gc.pos.cpu().numpy(), oc.pos)
     assert np.array_equal(gc.free_slot.cpu().numpy(), oc.free_slot)
     assert np.all(gc.pos.cpu().numpy()[:, :, w.budget + 1:] == -1)
+
+
+@pytest.mark.parametrize("base,batch,hq,hkv,budget,recent", [
+    (BF, 1, 8, 2, 300, 2),            # few heads: slots split over workgroups, merge launch
+    (BF, 16, 8, 8, 70, 3),            # 128 heads: one workgroup per head
+    (synth.C1, 1, 2, 2, 129, 1),      # fp32, split path
+    (synth.C1, 16, 8, 8, 40, 2),      # fp32, single launch
+])
+def test_decode_equal_minima_evict_the_highest_position(base, batch, hq, hkv, budget, recent):
+    """Tie rule of the generation step on both decode paths.  Scale 0 gives every slot the
+    same increment, so equal running scores stay equal and only the rule picks the victim:
+    positions and free slots must equal the oracle's exactly (no near-tie allowance), over
+    steps in which all, two, or none of the minima tie."""
+    import torch
+    from paper_2506_03762_amd import binding as B
+    w = synth.scaled(base, name="tie_break", batch=batch, n_q_heads=hq, n_kv_heads=hkv,
+                     budget=budget, recent=recent, seq_len=4 * budget, window=8)
+    opts = Opts(scale_mode=SCALE_FIXED, fixed_scale=0.0)
+    p, cfg = H.gpu_params(w, opts), H.oracle_cfg(w, opts)
+    d, slots = w.head_dim, budget + 1
+    rng = np.random.default_rng(budget)
+    K = synth.store_round(rng.standard_normal((batch, hkv, slots, d)), w.dtype).astype(np.float64)
+    V = synth.store_round(rng.standard_normal((batch, hkv, slots, d)), w.dtype).astype(np.float64)
+    pos = np.empty((batch, hkv, slots), np.int32)
+    F = np.full((batch, hkv, slots), 0.5)
+    fs = np.empty((batch, hkv), np.int32)
+    for pr in np.ndindex(batch, hkv):
+        perm = rng.permutation(slots)
+        held = np.sort(rng.choice(w.seq_len, budget, replace=False))
+        fs[pr] = perm[-1]
+        pos[pr][perm[:-1]] = held[rng.permutation(budget)]      # scrambled over the slots
+        pos[pr][perm[-1]] = -1
+        F[pr][perm[-1]] = 0.0
+        if pr[1] % 2:   # odd heads: a few equal minima below the rest
+            F[pr][perm[:5]] = 0.25
+    oc = oracle.Cache(K, V, F, pos, fs)
+    gc = H.upload_cache(oc, w, p)
+    ws = B.alloc_workspace(p)
+    out = torch.empty((batch, hq, d), dtype=B.torch_dtype(p.dtype), device="cuda")
+    for t in range(4):
+        q, k, v = synth.make_decode_inputs(w, t)
+        c_t = w.seq_len + t + 1
+        B.aha_decode_step(p, H.to_device(q, w.dtype), H.to_device(k, w.dtype),
+                          H.to_device(v, w.dtype), gc.k, gc.v, gc.scores, gc.pos, gc.free_slot,
+                          c_t, out, ws)
+        oracle.decode_step(oc, q, k, v, c_t, cfg)
+        torch.cuda.synchronize()
+        assert np.array_equal(gc.free_slot.cpu().numpy(), oc.free_slot), "victims differ at step %d" % t
+        assert np.array_equal(gc.pos.cpu().numpy(), oc.pos)
+        np.testing.assert_allclose(gc.scores.cpu().numpy()[oc.pos >= 0], oc.F[oc.pos >= 0], rtol=1e-6)

@@ -330,26 +330,29 @@ def test_topk_ties_keep_lower_index():
 
 # -------------------------------------------------------- compaction ----
 def test_pooled_score_selection():
-    """Score smoothing before the selection: the pool against numpy (float32, left to right),
-    width 1 is the identity, a constant stays constant, and the selection is the plain
-    selection of the pooled array."""
+    """Score smoothing before the selection (float64): the interior against numpy.convolve with
+    a box of 1/pool, the edges against the mean of the in-range slice, width 1 is the identity,
+    a constant stays constant, and the selection is the plain selection of the pooled array."""
     rng = np.random.default_rng(50)
-    s = rng.random((3, 97)).astype(np.float32)
+    s = rng.random((3, 97))
+    n = s.shape[1]
     for pool in (1, 3, 7, 15):
         h = (pool - 1) // 2
-        want = np.empty_like(s)
+        got = oracle.pool_scores(s, pool)
         for pr in range(s.shape[0]):
-            for j in range(s.shape[1]):
-                lo, hi = max(0, j - h), min(s.shape[1] - 1, j + h)
-                acc = np.float32(0)
-                for t in range(lo, hi + 1):
-                    acc = np.float32(acc + s[pr, t])
-                want[pr, j] = np.float32(acc / np.float32(hi - lo + 1))
-        got = oracle.pool_scores(s.astype(np.float64), pool)
-        assert np.array_equal(got.astype(np.float32), want) and np.array_equal(got, want.astype(np.float64))
-        idx = oracle.select_topk_pooled(s.astype(np.float64), 20, 5, pool)
-        assert np.array_equal(idx, oracle.select_topk(want.astype(np.float64), 20, 5))
-    assert np.array_equal(oracle.pool_scores(s.astype(np.float64), 1), s.astype(np.float64))
+            interior = np.convolve(s[pr], np.full(pool, 1.0 / pool), mode="valid")
+            np.testing.assert_allclose(got[pr, h:n - h], interior, rtol=1e-13)
+            for j in list(range(h)) + list(range(n - h, n)):
+                np.testing.assert_allclose(got[pr, j], s[pr, max(0, j - h):j + h + 1].mean(),
+                                           rtol=1e-13)
+        idx = oracle.select_topk_pooled(s, 20, 5, pool)
+        assert np.array_equal(idx, oracle.select_topk(got, 20, 5))
+    # an asymmetric input tells a shifted or one-sided window from the centred one
+    ramp = np.arange(12, dtype=np.float64)[None] ** 2
+    assert oracle.pool_scores(ramp, 3)[0, 5] == (16 + 25 + 36) / 3.0
+    assert oracle.pool_scores(ramp, 3)[0, 0] == (0 + 1) / 2.0
+    assert oracle.pool_scores(ramp, 5)[0, 11] == (81 + 100 + 121) / 3.0
+    assert np.array_equal(oracle.pool_scores(s, 1), s)
     c = np.full((1, 40), 0.375)
     assert np.array_equal(oracle.pool_scores(c, 9), c)
     # a lone spike spreads over its neighbours: with width 3 they outrank a slightly lower lone value
@@ -455,3 +458,52 @@ def test_decode_output_is_textbook_attention():
     Kf[B], Vf[B] = k[0, 0], v[0, 0]
     want = sp_softmax((q[0] @ Kf.T) / math.sqrt(d), axis=-1) @ Vf
     np.testing.assert_allclose(out[0], want, rtol=1e-12)
+
+
+def _tied_cache(positions, F, d, seed):
+    """Compact cache of one head whose slots hold `positions` (in that slot order, -1 = the
+    free slot) with running scores F; K and V random."""
+    rng = np.random.default_rng(seed)
+    slots = len(positions)
+    pos = np.array(positions, np.int32)[None, None].copy()
+    return oracle.Cache(rng.standard_normal((1, 1, slots, d)), rng.standard_normal((1, 1, slots, d)),
+                        np.array(F, np.float64)[None, None].copy(), pos,
+                        np.array([[positions.index(-1)]], np.int32))
+
+
+def test_decode_equal_minima_evict_the_highest_position():
+    """Tie rule of the generation step (a reading: the paper is silent).  With scale 0 every
+    slot receives the same increment G / (budget + 1), so equal running scores stay equal and
+    the rule alone picks the victim; the expected victims below are worked out by hand."""
+    d, G = 8, 2
+    rng = np.random.default_rng(43)
+    q, k, v = rng.standard_normal((1, G, d)), rng.standard_normal((1, 1, d)), rng.standard_normal((1, 1, d))
+    cfg = Config(window=4, budget=8, recent=2, scale_mode=SCALE_FIXED, fixed_scale=0.0)
+    # slots in scrambled position order; the new token gets position 20 (logical_pos 21).
+    # protected: positions 20 and 17; all others hold 0.5 -> victim = position 15 (slot 3)
+    positions = [4, 9, 17, 15, -1, 0, 11, 2, 7]
+    c = _tied_cache(positions, [0.5] * 9, d, 44)
+    oracle.decode_step(c, q, k, v, 21, cfg)
+    assert c.free_slot[0, 0] == 3 and c.pos[0, 0, 3] == -1
+    assert np.allclose(c.F[0, 0, [0, 1, 2, 5, 6, 7, 8]], 0.5 + G / 9.0)
+    # two equal minima (positions 2 and 11) below the rest -> victim = position 11 (slot 6)
+    F = [0.5, 0.5, 0.5, 0.5, 0.0, 0.5, 0.25, 0.25, 0.5]
+    c = _tied_cache(positions, F, d, 45)
+    oracle.decode_step(c, q, k, v, 21, cfg)
+    assert c.free_slot[0, 0] == 6
+    # a strictly smaller score beats a higher position
+    F = [0.5, 0.5, 0.5, 0.5, 0.0, 0.125, 0.25, 0.25, 0.5]
+    c = _tied_cache(positions, F, d, 46)
+    oracle.decode_step(c, q, k, v, 21, cfg)
+    assert c.free_slot[0, 0] == 5
+    # a protected slot is never the victim, whatever its score: recent = 3 protects 20, 17, 15
+    cfg3 = Config(window=4, budget=8, recent=3, scale_mode=SCALE_FIXED, fixed_scale=0.0)
+    F = [0.5, 0.5, 0.5, 0.0, 0.0, 0.5, 0.5, 0.5, 0.5]
+    c = _tied_cache(positions, F, d, 47)
+    oracle.decode_step(c, q, k, v, 21, cfg3)
+    assert c.free_slot[0, 0] == 6          # position 11, the highest unprotected one
+    # recent = 0: the new token itself (score 0 + increment) is the unique minimum
+    cfg0 = Config(window=4, budget=8, recent=0, scale_mode=SCALE_FIXED, fixed_scale=0.0)
+    c = _tied_cache(positions, [0.5] * 9, d, 48)
+    oracle.decode_step(c, q, k, v, 21, cfg0)
+    assert c.free_slot[0, 0] == 4
