@@ -20,8 +20,12 @@
  *     head_dim axis is contiguous.  Rows must be 16-byte aligned (base
  *     pointers 16-byte aligned, strides multiples of 8 elements for bf16 and
  *     4 for fp32).
- *   - Return value: AHA_OK or a negative status.  All argument checks happen
- *     on the host before anything is launched; on error nothing is enqueued.
+ *   - Return value: AHA_OK or a negative status.  All argument, size and
+ *     workspace checks happen on the host before anything is launched: with
+ *     AHA_ERR_INVALID_ARG, AHA_ERR_UNSUPPORTED or AHA_ERR_WORKSPACE nothing has
+ *     been enqueued.  AHA_ERR_HIP reports that the HIP runtime refused a
+ *     launch; earlier launches of the same call may already be enqueued and
+ *     the outputs are then undefined.
  *     aha_last_error() returns a thread-local, human readable reason.
  *   - No C++ exception crosses this boundary.
  */
@@ -68,7 +72,9 @@ enum { AHA_SCALE_FIXED = 0, AHA_SCALE_ADAPTIVE = 1 };
  *  value_prior  non-zero: scores are multiplied by gamma_bar of Sec. 4.3,
  *               gamma = average pool over tokens (odd width pool_kernel,
  *               stride 1, edge-truncated mean) of ||V_j||^2, divided by its
- *               maximum over the sequence of that (batch, KV head).
+ *               maximum over the sequence of that (batch, KV head).  If every
+ *               value row of a head is zero the quotient is undefined and
+ *               gamma_bar is taken as 1 (the scores stay unrefined).
  *  n_q_heads    must be a multiple of n_kv_heads; the score of a KV head is
  *               the sum over the query heads that share it.
  *  score_pool   smoothing of the scores before the selection (caption of the
@@ -84,7 +90,7 @@ typedef struct aha_params {
     int32_t n_q_heads;
     int32_t n_kv_heads;
     int32_t head_dim;     /* 64 or 128 */
-    int32_t seq_len;      /* n (prefill), <= 2^30 ; ignored by aha_decode_step */
+    int32_t seq_len;      /* n (prefill), 1..2^30 ; ignored by aha_decode_step */
     int32_t window;       /* r, 1..seq_len */
     int32_t budget;       /* B, <= 2^30 */
     int32_t recent;       /* B_r */
@@ -103,7 +109,9 @@ typedef struct aha_params {
 
 /*
  * Bytes of workspace that any of the calls below needs for `p` (the maximum
- * over the four operations, a multiple of 256).
+ * over the four operations, a multiple of 256).  With p->seq_len == 0 only
+ * aha_decode_step is counted and the prefill fields are not looked at (for a
+ * caller that holds a compact cache and no prompt).
  */
 int32_t aha_workspace_bytes(const aha_params *p, size_t *out_bytes);
 
@@ -166,6 +174,7 @@ int32_t aha_select_topk(const aha_params *p, const float *scores, int32_t *idx,
 
 /*
  * Compaction (Alg. 1 Generation: K_S, V_S, F_0 = refined prefill score).
+ * Of `p` only the shape, dtype, budget and the K / V strides are used.
  *
  *  k, v         as in aha_prefill_scores.
  *  scores, idx  as produced by the two calls above.
@@ -205,6 +214,11 @@ int32_t aha_compact_kv(const aha_params *p, const void *k, const void *v,
  * p->seq_len, window, value_prior, pool_kernel and the strides are ignored.
  * Exactly budget + 1 slots must be live on entry (budget occupied + the free
  * one), which aha_compact_kv and every previous step guarantee.
+ * The dots of a head's live slots are kept in on-chip memory: with fewer than
+ * 128 (batch, KV head) problems the slots are split over up to 64 workgroups
+ * (group * slots-per-split * 4 + 16 * group * head_dim bytes each, at most
+ * 64 KiB), otherwise one workgroup holds 8 * group * (budget + 1) bytes (at
+ * most 150 KiB); larger budgets return AHA_ERR_UNSUPPORTED.
  */
 int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_new,
                         const void *v_new, void *k_cache, void *v_cache,

@@ -117,6 +117,9 @@ void aha_oracle_attention_rows(const double *Q, const double *K,
  * length n; at the edges the mean is taken over the taps that fall inside
  * [0, n) (so a constant nu gives a constant gamma).  The maximum is per
  * (batch, KV head) over all n tokens.
+ * READING: a head whose value rows are all zero has max(gamma) = 0 and the
+ * quotient is undefined; the prior then carries no information and
+ * gamma_bar is 1 everywhere (the scores stay unrefined).
  *
  * V: [batch, n_kv_heads, n, d];  gamma_bar: [batch, n_kv_heads, n]
  * ---------------------------------------------------------------------- */
@@ -144,7 +147,7 @@ void aha_oracle_value_prior(const double *V, int64_t batch, int64_t n_kv_heads,
                 g[j] = s / (double)(hi - lo + 1);
                 if (g[j] > gmax) gmax = g[j];
             }
-            for (int64_t j = 0; j < n; ++j) g[j] /= gmax;
+            for (int64_t j = 0; j < n; ++j) g[j] = gmax > 0.0 ? g[j] / gmax : 1.0;
             free(nu);
         }
     }

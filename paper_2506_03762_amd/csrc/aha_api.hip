@@ -95,6 +95,18 @@ static int32_t check_prefill(const aha_params *p, bool need_strides) {
     return AHA_OK;
 }
 
+// Compaction reads K, V, the scores and the index list: only what those need is checked.
+static int32_t check_compact(const aha_params *p) {
+    int32_t rc = check_common(p);
+    if (rc) return rc;
+    if (p->seq_len < 1) return fail(AHA_ERR_INVALID_ARG, "seq_len must be >= 1");
+    if (p->seq_len > 1 << 30) return fail(AHA_ERR_UNSUPPORTED, "seq_len beyond 2^30");
+    if (p->budget > p->seq_len)
+        return fail(AHA_ERR_INVALID_ARG, "budget (%d) exceeds seq_len (%d)", p->budget, p->seq_len);
+    if ((rc = check_stride("k", p->k_stride, p->dtype, p->head_dim))) return rc;
+    return check_stride("v", p->v_stride, p->dtype, p->head_dim);
+}
+
 static int32_t check_ptr(const char *name, const void *ptr, size_t align) {
     if (!ptr) return fail(AHA_ERR_INVALID_ARG, "%s is null", name);
     if ((uintptr_t)ptr % align != 0)
@@ -169,16 +181,28 @@ static PrefillPlan plan_prefill(const aha_params *p) {
 }
 
 // Decode: split a head's slots over workgroups when there are too few heads to fill the GPU.
+// A split workgroup keeps group * (slots of its range) dots and 4 * group * head_dim partial
+// outputs in LDS; the number of splits is raised until that fits kDecodeSplitLds (the limit
+// a launch may ask for without an attribute), and `fits` says whether kMaxDecodeSplit
+// splits were enough.
 static DecodePlan plan_decode(const aha_params *p) {
     DecodePlan pl{};
     const int Z = p->batch * p->n_kv_heads, G = p->n_q_heads / p->n_kv_heads;
     const int live = p->budget + 1;
+    pl.fits = true;
     int nsplit = 1;
     if (Z < 128) {
         nsplit = (256 + Z - 1) / Z;
         const int max_by_size = (live + 63) / 64;  // at least 64 slots per workgroup
         if (nsplit > max_by_size) nsplit = max_by_size;
         if (nsplit > kMaxDecodeSplit) nsplit = kMaxDecodeSplit;
+        if (nsplit > 1) {
+            const int64_t room = (int64_t)kDecodeSplitLds / 4 - 4 * (int64_t)G * p->head_dim;
+            const int64_t max_sps = room / G;  // slots per split whose dots fit beside the outputs
+            const int64_t need = max_sps > 0 ? (live + max_sps - 1) / max_sps : kMaxDecodeSplit + 1;
+            if (need > nsplit) nsplit = need > kMaxDecodeSplit ? kMaxDecodeSplit : (int)need;
+            if (need > kMaxDecodeSplit) pl.fits = false;
+        }
     }
     pl.nsplit = nsplit < 1 ? 1 : nsplit;
     pl.sps = (live + pl.nsplit - 1) / pl.nsplit;
@@ -186,6 +210,10 @@ static DecodePlan plan_decode(const aha_params *p) {
     if (pl.nsplit > 1) {
         pl.off_part = align_up(sizeof(float) * (size_t)Z * G * live, 256);
         pl.bytes = align_up(pl.off_part + sizeof(float) * (size_t)Z * pl.nsplit * G * (p->head_dim + 2), 256);
+    } else {
+        // one workgroup per head: dots and output probabilities of all live slots in LDS
+        const size_t w_floats = (size_t)(G * live > 16 * G * p->head_dim ? G * live : 16 * G * p->head_dim);
+        if ((w_floats + (size_t)G * live) * 4 > kDecodeSingleLds) pl.fits = false;
     }
     return pl;
 }
@@ -218,6 +246,12 @@ static size_t topk_ws_bytes(const aha_params *p) {
 
 int32_t aha_workspace_bytes(const aha_params *p, size_t *out_bytes) {
     if (!out_bytes) return fail(AHA_ERR_INVALID_ARG, "out_bytes is null");
+    if (p && p->seq_len == 0) {  // a caller of aha_decode_step only
+        const int32_t rc = check_common(p);
+        if (rc) return rc;
+        *out_bytes = plan_decode(p).bytes;
+        return AHA_OK;
+    }
     int32_t rc = check_prefill(p, false);
     if (rc) return rc;
     const size_t a = plan_prefill(p).bytes, d = plan_decode(p).bytes, t = topk_ws_bytes(p);
@@ -286,7 +320,7 @@ int32_t aha_select_topk(const aha_params *p, const float *scores, int32_t *idx, 
 int32_t aha_compact_kv(const aha_params *p, const void *k, const void *v, const float *scores,
                        const int32_t *idx, void *k_cache, void *v_cache, float *scores_c,
                        int32_t *pos_c, int32_t *free_slot, int32_t cache_slots, void *stream) {
-    int32_t rc = check_prefill(p, true);
+    int32_t rc = check_compact(p);
     if (rc) return rc;
     if ((rc = check_ptr("k", k, 16)) || (rc = check_ptr("v", v, 16)) ||
         (rc = check_ptr("scores", scores, 4)) || (rc = check_ptr("idx", idx, 4)) ||
@@ -303,11 +337,13 @@ int32_t aha_compact_kv(const aha_params *p, const void *k, const void *v, const 
                       "compaction kernel");
 }
 
-int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_new,
-                        const void *v_new, void *k_cache, void *v_cache, float *scores_c,
-                        int32_t *pos_c, int32_t *free_slot, int32_t cache_slots,
-                        int32_t logical_pos, void *out, void *workspace, size_t workspace_bytes,
-                        void *stream) {
+// Checks and launch shared by aha_decode_step and its variant without a workspace argument
+// (`scratch_limit` > 0: the scratch is the library's own and that many bytes long).
+static int32_t decode_step_impl(const aha_params *p, const void *q_new, const void *k_new,
+                                const void *v_new, void *k_cache, void *v_cache, float *scores_c,
+                                int32_t *pos_c, int32_t *free_slot, int32_t cache_slots,
+                                int32_t logical_pos, void *out, void *workspace,
+                                size_t workspace_bytes, size_t scratch_limit, void *stream) {
     int32_t rc = check_common(p);
     if (rc) return rc;
     if ((rc = check_ptr("q_new", q_new, 16)) || (rc = check_ptr("k_new", k_new, 16)) ||
@@ -326,12 +362,18 @@ int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_ne
     if (G > 8)
         return fail(AHA_ERR_UNSUPPORTED, "decode is built for query groups of up to 8 heads, not %d", G);
     const DecodePlan dpl = plan_decode(p);
-    const int live = p->budget + 1;
-    const size_t w_floats = (size_t)(G * live > 16 * G * p->head_dim ? G * live : 16 * G * p->head_dim);
-    if (dpl.nsplit == 1 && (w_floats + (size_t)G * live) * 4 > 150 * 1024)
+    if (!dpl.fits)
         return fail(AHA_ERR_UNSUPPORTED,
-                    "decode keeps group * (budget + 1) dots in LDS; %d * %d does not fit", G, live);
-    if ((rc = check_ws(workspace, workspace_bytes, dpl.bytes))) return rc;
+                    "decode keeps group * (budget + 1) dots in LDS; %d * %d does not fit (%d splits)",
+                    G, p->budget + 1, dpl.nsplit);
+    if (scratch_limit) {
+        if (dpl.bytes > scratch_limit)
+            return fail(AHA_ERR_UNSUPPORTED,
+                        "this shape needs %zu bytes of scratch, the built-in buffer holds %zu: use "
+                        "aha_decode_step with a workspace", dpl.bytes, scratch_limit);
+    } else if ((rc = check_ws(workspace, workspace_bytes, dpl.bytes))) {
+        return rc;
+    }
     DecodeGeom g{};
     g.q = q_new; g.k_new = k_new; g.v_new = v_new; g.kc = k_cache; g.vc = v_cache; g.out = out;
     g.fc = scores_c; g.pos = pos_c; g.free_slot = free_slot;
@@ -340,6 +382,15 @@ int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_ne
     g.scale_mode = p->scale_mode; g.fixed_scale = p->fixed_scale; g.lambda_floor = p->lambda_floor;
     return hip_result(launch_decode(g, dpl, workspace, p->dtype, (hipStream_t)stream),
                       "decode kernel");
+}
+
+int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_new,
+                        const void *v_new, void *k_cache, void *v_cache, float *scores_c,
+                        int32_t *pos_c, int32_t *free_slot, int32_t cache_slots,
+                        int32_t logical_pos, void *out, void *workspace, size_t workspace_bytes,
+                        void *stream) {
+    return decode_step_impl(p, q_new, k_new, v_new, k_cache, v_cache, scores_c, pos_c, free_slot,
+                            cache_slots, logical_pos, out, workspace, workspace_bytes, 0, stream);
 }
 
 int32_t aha_profile_events(void *const *events, int32_t count) {

@@ -133,10 +133,12 @@ struct OpMaxU { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint3
 __device__ __forceinline__ float wave_max(float v) { return reduce_lanes<1, 64>(v, OpMax{}); }
 __device__ __forceinline__ float wave_sum(float v) { return reduce_lanes<1, 64>(v, OpSum{}); }
 
-// Loads that bypass the per-CU cache (for data another workgroup of the same
-// launch has just written and fenced).
-__device__ __forceinline__ float load_agent(const float *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Value prior gamma / max(gamma) (Sec. 4.3) as gamma * (1 / max).  A head whose value rows
+// are all zero has max(gamma) = 0: the prior is then 1 everywhere (the inverse is stored as
+// a negative number, which no real maximum produces, and tells the factor to be 1).
+__device__ __forceinline__ float prior_inverse(float gmax) { return gmax > 0.f ? 1.f / gmax : -1.f; }
+__device__ __forceinline__ float prior_factor(float gam, float ginv) {
+    return ginv < 0.f ? 1.f : gam * ginv;
 }
 
 // Softmax geometry of the flattened query rows of one KV head: row rho of the

@@ -5,9 +5,29 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/aha.h"
 
 namespace aha {
+
+// One-time set-up per device (function attributes, symbol addresses): `fn` runs once on
+// each device, with that device current, whatever thread gets there first; its result is
+// kept and returned to every later caller on that device.
+constexpr int kMaxDevices = 64;
+struct DeviceOnce {
+    std::once_flag flag[kMaxDevices];
+    hipError_t err[kMaxDevices];
+};
+template <class F>
+inline hipError_t device_once(DeviceOnce &o, F fn) {
+    int dev = 0;
+    const hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::call_once(o.flag[dev], [&] { o.err[dev] = fn(); });
+    return o.err[dev];
+}
 
 // Geometry of one prefill call, passed by value to the kernels.
 struct ScoreGeom {
@@ -76,12 +96,15 @@ struct DecodeGeom {
 // With few (batch, KV head) problems the slots of a head are split over nsplit workgroups
 // (two launches, partials in the workspace); otherwise one workgroup handles a head.
 constexpr int kMaxDecodeSplit = 64;  // most workgroups a head's slots are split over
+constexpr size_t kDecodeSplitLds = 64 * 1024;    // dynamic LDS of a split workgroup, at most
+constexpr size_t kDecodeSingleLds = 150 * 1024;  // dynamic LDS of the one-workgroup-per-head kernel, at most
 
 struct DecodePlan {
     int nsplit;      // 1: single-launch path
     int sps;         // slots per split
     size_t off_part; // partial outputs behind the raw dots
     size_t bytes;    // workspace bytes (0 when nsplit == 1)
+    bool fits;       // the LDS the chosen path needs is within its limit
 };
 hipError_t launch_decode(const DecodeGeom &g, const DecodePlan &pl, void *ws, int dtype,
                          hipStream_t st);

@@ -585,6 +585,9 @@ static hipError_t launch_g(const DecodeGeom &g, const DecodePlan &pl, void *ws, 
     {                                                                                            \
         hipLaunchKernelGGL((decode_split_kernel<ESIZE, D, GG>), g1, dim3(256), smem1, st, g,     \
                            pl.nsplit, pl.sps, ws_w, ws_part);                                    \
+        /* the merge rewrites the cache state: never after a refused first launch */             \
+        const hipError_t e1 = hipGetLastError();                                                 \
+        if (e1 != hipSuccess) return e1;                                                         \
         hipLaunchKernelGGL((decode_merge_kernel<ESIZE, D, GG>), g2, dim3(kMergeThreads), 0, st, g,         \
                            pl.nsplit, ws_w, ws_part);                                            \
     }
@@ -606,14 +609,14 @@ static hipError_t launch_g(const DecodeGeom &g, const DecodePlan &pl, void *ws, 
     dim3 grid(g.batch * g.Hkv);
 #define AHA_DEC(GG)                                                                              \
     {                                                                                            \
-        static size_t attr = 0;                                                                  \
-        if (smem > attr) {                                                                       \
-            hipError_t e = hipFuncSetAttribute((const void *)decode_kernel<ESIZE, D, GG>,        \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,       \
-                                               (int)smem);                                       \
-            if (e != hipSuccess) return e;                                                       \
-            attr = smem;                                                                         \
-        }                                                                                        \
+        /* the largest dynamic LDS any accepted shape asks for, set once per device */          \
+        static DeviceOnce once;                                                                  \
+        const hipError_t ea = device_once(once, [] {                                             \
+            return hipFuncSetAttribute((const void *)decode_kernel<ESIZE, D, GG>,                \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,               \
+                                       (int)kDecodeSingleLds);                                   \
+        });                                                                                      \
+        if (ea != hipSuccess) return ea;                                                         \
         hipLaunchKernelGGL((decode_kernel<ESIZE, D, GG>), grid, dim3(kDecThreads), smem, st, g,  \
                            w_floats);                                                            \
     }

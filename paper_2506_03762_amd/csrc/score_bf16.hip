@@ -640,12 +640,12 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     auto write_scores = [&](f32x16 (&col)[kMB], int kb, const float (&gam)[kMB]) {
         float ginv = 1.f;
         if (g.value_prior)  // s_gmax was published by the barrier of the first tile load
-            ginv = 1.f / fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3]));
+            ginv = prior_inverse(fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3])));
 #pragma unroll
         for (int mb = 0; mb < kMB; ++mb) {
             const float tot = fold16_over32(col[mb], lane);
             const int j = acc_key(kb, mb, my_v, lane);
-            if ((lane & 1) == 0 && j < g.n) scores[(int64_t)z * g.n + j] = tot * (gam[mb] * ginv);
+            if ((lane & 1) == 0 && j < g.n) scores[(int64_t)z * g.n + j] = tot * prior_factor(gam[mb], ginv);
         }
     };
     auto zero = [&](f32x16 (&col)[kMB]) {
@@ -706,7 +706,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             load_tile(sg.qt, load_kb_of(0));
             float ginv = 1.f;
             if (g.value_prior)
-                ginv = 1.f / fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3]));
+                ginv = prior_inverse(fmaxf(fmaxf(s_gmax[0], s_gmax[1]), fmaxf(s_gmax[2], s_gmax[3])));
             auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb0) {
                 const int kb = kb0 + wave * kWaveKeys;
                 if (kb >= key_end) return;
@@ -720,7 +720,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
                     const float tot = fold16_over32(col[mb], lane);
                     const int j = acc_key(kb, mb, my_v, lane);
                     if ((lane & 1) == 0 && j < key_end)
-                        unsafeAtomicAdd(&scores[(int64_t)z * g.n + j], tot * (gam[mb] * ginv));
+                        unsafeAtomicAdd(&scores[(int64_t)z * g.n + j], tot * prior_factor(gam[mb], ginv));
                 }
             };
             for (int i = 0; i < nsteps; i += 2) {
@@ -744,20 +744,19 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     const float *gamma = (const float *)(w + pl.off_gamma);
     const float *gbm = (const float *)(w + pl.off_gblockmax);
     const float *lam_tab = (const float *)(w + pl.off_lam);
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)bf16_pass1_kernel<D, NB>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)S::bytes);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void *)bf16_pass2_kernel<D, NB, true>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::bytes);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void *)bf16_pass2_kernel<D, NB, false>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::bytes);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static DeviceOnce once;
+    const hipError_t ea = device_once(once, [] {
+        const void *kernels[3] = {(const void *)bf16_pass1_kernel<D, NB>,
+                                  (const void *)bf16_pass2_kernel<D, NB, true>,
+                                  (const void *)bf16_pass2_kernel<D, NB, false>};
+        for (const void *kf : kernels) {
+            const hipError_t e = hipFuncSetAttribute(
+                kf, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::bytes);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    });
+    if (ea != hipSuccess) return ea;
     // (part, tile pair, problem), part fastest
     const int64_t wgs1 = (int64_t)pl.nchunks * ((pl.n_qtiles + 1) / 2) * pl.Z;
     // windowed pass 2: (key range, problem)

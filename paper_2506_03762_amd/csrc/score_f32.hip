@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void f32_pass2_kernel(ScoreGeom g, const float
         if (g.value_prior) {
             float gm = 0.f;
             for (int t = 0; t < n_vtiles; ++t) gm = fmaxf(gm, gblockmax[z * n_vtiles + t]);
-            out = acc * (gamma[(int64_t)z * g.n + j] / gm);
+            out = gm > 0.f ? acc * (gamma[(int64_t)z * g.n + j] / gm) : acc;  // all-zero values: no prior
         }
         scores[(int64_t)z * g.n + j] = out;
     }

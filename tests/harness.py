@@ -213,6 +213,30 @@ def upload_cache(ref: oracle.Cache, w: synth.Workload, p):
     return c
 
 
+def random_cache(w: synth.Workload, seed: int, F_fill=None) -> oracle.Cache:
+    """A compact cache that no prefill produced: random K/V rows (rounded to the storage
+    dtype), `budget` distinct positions below seq_len scattered over budget + 1 slots, one
+    free slot; running scores uniform in (0, 1) (float32-representable) or `F_fill`."""
+    rng = np.random.default_rng(seed)
+    b, hk, d, slots = w.batch, w.n_kv_heads, w.head_dim, w.budget + 1
+    K = synth.store_round(rng.standard_normal((b, hk, slots, d), dtype=np.float32), w.dtype).astype(np.float64)
+    V = synth.store_round(rng.standard_normal((b, hk, slots, d), dtype=np.float32), w.dtype).astype(np.float64)
+    pos = np.empty((b, hk, slots), np.int32)
+    fs = np.empty((b, hk), np.int32)
+    if F_fill is None:
+        F = rng.random((b, hk, slots), dtype=np.float32).astype(np.float64)
+    else:
+        F = np.full((b, hk, slots), float(F_fill))
+    for pr in np.ndindex(b, hk):
+        perm = rng.permutation(slots)
+        held = rng.choice(w.seq_len, w.budget, replace=False)
+        fs[pr] = perm[-1]
+        pos[pr][perm[:-1]] = held
+        pos[pr][perm[-1]] = -1
+        F[pr][perm[-1]] = 0.0
+    return oracle.Cache(K, V, F, pos, fs)
+
+
 def live_state(pos, F):
     """{position: score} of the occupied slots of one (batch, head)."""
     m = pos >= 0

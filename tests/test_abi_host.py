@@ -151,6 +151,25 @@ def test_other_entry_points_validate(lib):
     cpb = good(budget=4096, n_q_heads=16, batch=64).c()
     assert lib.aha_decode_step(ctypes.byref(cpb), *args, 4097, 5000, DUMMY, None, 0, None) \
         == B.AHA_ERR_UNSUPPORTED                                              # dots exceed LDS
+    # few heads, large budget: the splits' dots must fit 64 KiB of LDS each, or the call is
+    # refused before anything is launched (64 splits x 3584 slots at group 4, head_dim 128)
+    fits = good(batch=8, n_q_heads=32, n_kv_heads=8, seq_len=1 << 20, budget=229000).c()
+    assert lib.aha_decode_step(ctypes.byref(fits), *args, 229001, 229001, DUMMY, None, 0, None) \
+        == B.AHA_ERR_WORKSPACE                                                # accepted up to here
+    big = good(batch=8, n_q_heads=32, n_kv_heads=8, seq_len=1 << 20, budget=230000).c()
+    assert lib.aha_decode_step(ctypes.byref(big), *args, 230001, 230001, DUMMY, DUMMY, 1 << 40, None) \
+        == B.AHA_ERR_UNSUPPORTED
+    assert b"does not fit" in lib.aha_last_error()
+    # compaction looks at the K / V strides only
+    kv_only = good(q_stride=(0, 0, 0), window=0, pool_kernel=0).c()
+    assert lib.aha_compact_kv(ctypes.byref(kv_only), DUMMY, DUMMY, DUMMY, DUMMY, DUMMY, DUMMY,
+                              DUMMY, DUMMY, DUMMY, 512, None) == B.AHA_ERR_INVALID_ARG
+    assert b"cache_slots" in lib.aha_last_error()          # the only complaint left
+    # a decode-only caller sizes its workspace without a sequence length
+    dec_only = good(seq_len=0, window=0).c()
+    out = ctypes.c_size_t(0)
+    assert lib.aha_workspace_bytes(ctypes.byref(dec_only), ctypes.byref(out)) == B.AHA_OK
+    assert out.value > 0 and out.value % 256 == 0
     # few heads: the slots are split over workgroups and the partials need the workspace
     assert lib.aha_decode_step(ctypes.byref(cp), *args, 513, 4097, DUMMY, None, 0, None) \
         == B.AHA_ERR_WORKSPACE

@@ -381,23 +381,12 @@ def test_decode_equal_minima_evict_the_highest_position(base, batch, hq, hkv, bu
                      budget=budget, recent=recent, seq_len=4 * budget, window=8)
     opts = Opts(scale_mode=SCALE_FIXED, fixed_scale=0.0)
     p, cfg = H.gpu_params(w, opts), H.oracle_cfg(w, opts)
-    d, slots = w.head_dim, budget + 1
-    rng = np.random.default_rng(budget)
-    K = synth.store_round(rng.standard_normal((batch, hkv, slots, d)), w.dtype).astype(np.float64)
-    V = synth.store_round(rng.standard_normal((batch, hkv, slots, d)), w.dtype).astype(np.float64)
-    pos = np.empty((batch, hkv, slots), np.int32)
-    F = np.full((batch, hkv, slots), 0.5)
-    fs = np.empty((batch, hkv), np.int32)
+    d = w.head_dim
+    oc = H.random_cache(w, budget, F_fill=0.5)
     for pr in np.ndindex(batch, hkv):
-        perm = rng.permutation(slots)
-        held = np.sort(rng.choice(w.seq_len, budget, replace=False))
-        fs[pr] = perm[-1]
-        pos[pr][perm[:-1]] = held[rng.permutation(budget)]      # scrambled over the slots
-        pos[pr][perm[-1]] = -1
-        F[pr][perm[-1]] = 0.0
         if pr[1] % 2:   # odd heads: a few equal minima below the rest
-            F[pr][perm[:5]] = 0.25
-    oc = oracle.Cache(K, V, F, pos, fs)
+            occupied = np.flatnonzero(oc.pos[pr] >= 0)
+            oc.F[pr][occupied[:5]] = 0.25
     gc = H.upload_cache(oc, w, p)
     ws = B.alloc_workspace(p)
     out = torch.empty((batch, hq, d), dtype=B.torch_dtype(p.dtype), device="cuda")
@@ -412,3 +401,32 @@ def test_decode_equal_minima_evict_the_highest_position(base, batch, hq, hkv, bu
         assert np.array_equal(gc.free_slot.cpu().numpy(), oc.free_slot), "victims differ at step %d" % t
         assert np.array_equal(gc.pos.cpu().numpy(), oc.pos)
         np.testing.assert_allclose(gc.scores.cpu().numpy()[oc.pos >= 0], oc.F[oc.pos >= 0], rtol=1e-6)
+
+
+def test_decode_split_path_raises_the_split_count_for_large_budgets():
+    """Few heads with a budget whose dots do not fit a split workgroup's LDS at the default
+    split count (64 heads -> 4 splits of 1626 slots x 8 query heads = 68 KB): the plan must
+    use more splits, and the steps must match the oracle."""
+    w = synth.scaled(BF, name="decode_large_budget", batch=8, n_q_heads=64, n_kv_heads=8,
+                     budget=6500, recent=64, seq_len=20000, window=8)
+    oc = H.random_cache(w, 5)
+    ref = H.Result(None, None, oc)
+    flips = H.run_and_check_decode(w, None, ref, steps=3)
+    assert flips == 0
+
+
+@pytest.mark.parametrize("base", [BF, synth.C1], ids=["bf16", "f32"])
+def test_all_zero_value_head_keeps_unrefined_scores(base):
+    """A head whose value rows are all zero has max(gamma) = 0: gamma_bar is 1 there on both
+    sides, and the other heads are refined as usual."""
+    w = synth.scaled(base, name="zero_v", seq_len=700, n_q_heads=4, n_kv_heads=2, budget=90,
+                     recent=16, window=24)
+    Q, K, V = synth.make_prefill(w)
+    V = V.copy()
+    V[0, 1] = 0.0
+    gpu = H.run_prefill_gpu(w, Opts(), (Q, K, V))
+    ref = H.run_prefill_oracle(w, Opts(), (Q, K, V))
+    H.assert_scores_close(gpu.scores, ref.scores, w)
+    H.assert_sets_match(gpu.idx, ref.idx, ref.scores, w)
+    off = H.run_prefill_gpu(w, Opts(value_prior=False), (Q, K, V))
+    assert np.array_equal(gpu.scores[0, 1], off.scores[0, 1])

@@ -270,6 +270,18 @@ def test_value_prior_equal_norm_rows_is_identity():
     np.testing.assert_allclose(on, off, rtol=1e-12)
 
 
+def test_value_prior_of_an_all_zero_head_is_one():
+    """max(gamma) = 0 leaves the quotient undefined; the reading taken is gamma_bar = 1, so the
+    refined scores of that head equal the unrefined ones while other heads are not touched."""
+    Q, K, V = rnd(60, 1, 2, 40, 8), rnd(61, 1, 2, 40, 8), rnd(62, 1, 2, 40, 8)
+    V[0, 1] = 0.0
+    g = oracle.value_prior(V, 5)
+    assert np.all(g[0, 1] == 1.0) and g[0, 0].max() == 1.0 and g[0, 0].min() < 1.0
+    on = oracle.prefill_scores(Q, K, V, Config(6, 10, 2, value_prior=True, pool=5))
+    off = oracle.prefill_scores(Q, K, V, Config(6, 10, 2, value_prior=False))
+    assert np.array_equal(on[0, 1], off[0, 1]) and not np.array_equal(on[0, 0], off[0, 0])
+
+
 def test_value_prior_multiplies_scores():
     b, hq, hk, n, d = 1, 2, 1, 40, 8
     Q, K, V = rnd(27, b, hq, n, d), rnd(28, b, hk, n, d), rnd(29, b, hk, n, d)
