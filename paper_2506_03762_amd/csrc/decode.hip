@@ -519,10 +519,13 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
     const bool one_batch = live <= U * NT;  // then the values stay in registers for pass two
     for (int base = 0; base < live; base += U * NT) {
         if (base) fetch(base);
+        // (entries past the last slot are skipped, not fed as -inf: a scale of exactly 0
+        // would turn them into 0 * inf)
 #pragma unroll
         for (int u = 0; u < U; ++u)
+            if (base + tid + u * NT < live)
 #pragma unroll
-            for (int gi = 0; gi < G; ++gi) zs[gi] += exp2f((wr[u][gi] - mx[gi]) * c_sc);
+                for (int gi = 0; gi < G; ++gi) zs[gi] += exp2f((wr[u][gi] - mx[gi]) * c_sc);
     }
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) {

@@ -215,8 +215,10 @@ def upload_cache(ref: oracle.Cache, w: synth.Workload, p):
 
 def random_cache(w: synth.Workload, seed: int, F_fill=None) -> oracle.Cache:
     """A compact cache that no prefill produced: random K/V rows (rounded to the storage
-    dtype), `budget` distinct positions below seq_len scattered over budget + 1 slots, one
-    free slot; running scores uniform in (0, 1) (float32-representable) or `F_fill`."""
+    dtype), `budget` distinct positions below seq_len - the `recent` last ones, as every
+    state reached from a prefill holds them, and a random choice of the earlier ones -
+    scattered over budget + 1 slots, one free slot; running scores uniform in (0, 1)
+    (float32-representable) or `F_fill`."""
     rng = np.random.default_rng(seed)
     b, hk, d, slots = w.batch, w.n_kv_heads, w.head_dim, w.budget + 1
     K = synth.store_round(rng.standard_normal((b, hk, slots, d), dtype=np.float32), w.dtype).astype(np.float64)
@@ -229,7 +231,9 @@ def random_cache(w: synth.Workload, seed: int, F_fill=None) -> oracle.Cache:
         F = np.full((b, hk, slots), float(F_fill))
     for pr in np.ndindex(b, hk):
         perm = rng.permutation(slots)
-        held = rng.choice(w.seq_len, w.budget, replace=False)
+        held = np.concatenate([np.arange(w.seq_len - w.recent, w.seq_len),
+                               rng.choice(w.seq_len - w.recent, w.budget - w.recent, replace=False)])
+        held = held[rng.permutation(w.budget)]
         fs[pr] = perm[-1]
         pos[pr][perm[:-1]] = held
         pos[pr][perm[-1]] = -1
