@@ -227,6 +227,26 @@ int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_ne
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * aha_decode_step for callers that cannot allocate or carry a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, result and errors as aha_decode_step, without
+ * the workspace: the scratch of the few-heads path lives in a buffer built
+ * into the library (4 MiB per GPU, held until the process ends).  The call
+ * allocates and frees nothing.  A shape whose scratch (aha_workspace_bytes
+ * with seq_len = 0) exceeds 4 MiB returns AHA_ERR_UNSUPPORTED before anything
+ * is launched - e.g. 8 KV heads x 4 query heads x budget 2048 needs 0.8 MiB.
+ * All calls on one GPU share the buffer: two calls that may overlap in time
+ * (different streams, different threads) race and must be ordered by the
+ * caller.  The buffer keeps the previous call's contents; the kernels read
+ * nothing from it that the same call has not written.
+ */
+int32_t aha_decode_step_static(const aha_params *p, const void *q_new, const void *k_new,
+                               const void *v_new, void *k_cache, void *v_cache,
+                               float *scores_c, int32_t *pos_c, int32_t *free_slot,
+                               int32_t cache_slots, int32_t logical_pos, void *out,
+                               void *stream);
+
+/*
  * Optional stage timing for aha_prefill_scores (Sec. 4.1 - 4.3 are computed by
  * three launches: value prior, row statistics, column sums).  `events` is an
  * array of `count` caller-created hipEvent_t handles (HOST array, copied by

@@ -29,7 +29,8 @@ AHA_SCALE_FIXED, AHA_SCALE_ADAPTIVE = 0, 1
 
 # entry points returning an int32 status first, then the two that return strings
 EXPORTS = ("aha_workspace_bytes", "aha_prefill_scores", "aha_prefill_scores_lse", "aha_select_topk",
-           "aha_compact_kv", "aha_decode_step", "aha_profile_events", "aha_last_error",
+           "aha_compact_kv", "aha_decode_step", "aha_decode_step_static", "aha_profile_events",
+           "aha_last_error",
            "aha_version")
 
 
@@ -74,6 +75,7 @@ def load() -> ctypes.CDLL:
     lib.aha_select_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.aha_compact_kv.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     lib.aha_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.aha_decode_step_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp]
     lib.aha_profile_events.argtypes = [ctypes.POINTER(vp), i32]
     for name in EXPORTS[:-2]:
         getattr(lib, name).restype = i32
@@ -197,6 +199,16 @@ def aha_decode_step(p: Params, q_new, k_new, v_new, k_cache, v_cache, scores_c, 
                                   _ptr(free_slot), int(k_cache.shape[2]), int(logical_pos),
                                   _ptr(out), _ptr(workspace),
                                   workspace.numel() if workspace is not None else 0, _stream()))
+
+
+def aha_decode_step_static(p: Params, q_new, k_new, v_new, k_cache, v_cache, scores_c, pos_c,
+                           free_slot, logical_pos: int, out):
+    """aha_decode_step on the library's built-in scratch buffer (allocates nothing)."""
+    cp = p.c()
+    _check(load().aha_decode_step_static(ctypes.byref(cp), _ptr(q_new), _ptr(k_new), _ptr(v_new),
+                                         _ptr(k_cache), _ptr(v_cache), _ptr(scores_c),
+                                         _ptr(pos_c), _ptr(free_slot), int(k_cache.shape[2]),
+                                         int(logical_pos), _ptr(out), _stream()))
 
 
 def profile_events(events=None):

@@ -337,13 +337,14 @@ int32_t aha_compact_kv(const aha_params *p, const void *k, const void *v, const 
                       "compaction kernel");
 }
 
-// Checks and launch shared by aha_decode_step and its variant without a workspace argument
-// (`scratch_limit` > 0: the scratch is the library's own and that many bytes long).
-static int32_t decode_step_impl(const aha_params *p, const void *q_new, const void *k_new,
-                                const void *v_new, void *k_cache, void *v_cache, float *scores_c,
-                                int32_t *pos_c, int32_t *free_slot, int32_t cache_slots,
-                                int32_t logical_pos, void *out, void *workspace,
-                                size_t workspace_bytes, size_t scratch_limit, void *stream) {
+// Host checks shared by aha_decode_step and its variant without a workspace argument
+// (`scratch_limit` > 0: the scratch is the library's own and that many bytes long; the
+// workspace arguments are then not looked at).  Nothing here touches the HIP runtime.
+static int32_t decode_step_check(const aha_params *p, const void *q_new, const void *k_new,
+                                 const void *v_new, void *k_cache, void *v_cache, float *scores_c,
+                                 int32_t *pos_c, int32_t *free_slot, int32_t cache_slots,
+                                 int32_t logical_pos, void *out, const void *workspace,
+                                 size_t workspace_bytes, size_t scratch_limit, DecodePlan *plan) {
     int32_t rc = check_common(p);
     if (rc) return rc;
     if ((rc = check_ptr("q_new", q_new, 16)) || (rc = check_ptr("k_new", k_new, 16)) ||
@@ -361,23 +362,31 @@ static int32_t decode_step_impl(const aha_params *p, const void *q_new, const vo
     const int G = p->n_q_heads / p->n_kv_heads;
     if (G > 8)
         return fail(AHA_ERR_UNSUPPORTED, "decode is built for query groups of up to 8 heads, not %d", G);
-    const DecodePlan dpl = plan_decode(p);
-    if (!dpl.fits)
+    *plan = plan_decode(p);
+    if (!plan->fits)
         return fail(AHA_ERR_UNSUPPORTED,
                     "decode keeps group * (budget + 1) dots in LDS; %d * %d does not fit (%d splits)",
-                    G, p->budget + 1, dpl.nsplit);
+                    G, p->budget + 1, plan->nsplit);
     if (scratch_limit) {
-        if (dpl.bytes > scratch_limit)
+        if (plan->bytes > scratch_limit)
             return fail(AHA_ERR_UNSUPPORTED,
                         "this shape needs %zu bytes of scratch, the built-in buffer holds %zu: use "
-                        "aha_decode_step with a workspace", dpl.bytes, scratch_limit);
-    } else if ((rc = check_ws(workspace, workspace_bytes, dpl.bytes))) {
-        return rc;
+                        "aha_decode_step with a workspace", plan->bytes, scratch_limit);
+        return AHA_OK;
     }
+    return check_ws(workspace, workspace_bytes, plan->bytes);
+}
+
+static int32_t decode_step_launch(const aha_params *p, const DecodePlan &dpl, const void *q_new,
+                                  const void *k_new, const void *v_new, void *k_cache,
+                                  void *v_cache, float *scores_c, int32_t *pos_c,
+                                  int32_t *free_slot, int32_t cache_slots, int32_t logical_pos,
+                                  void *out, void *workspace, void *stream) {
     DecodeGeom g{};
     g.q = q_new; g.k_new = k_new; g.v_new = v_new; g.kc = k_cache; g.vc = v_cache; g.out = out;
     g.fc = scores_c; g.pos = pos_c; g.free_slot = free_slot;
-    g.batch = p->batch; g.Hq = p->n_q_heads; g.Hkv = p->n_kv_heads; g.G = G; g.d = p->head_dim;
+    g.batch = p->batch; g.Hq = p->n_q_heads; g.Hkv = p->n_kv_heads; g.G = g.Hq / g.Hkv;
+    g.d = p->head_dim;
     g.budget = p->budget; g.recent = p->recent; g.slots = cache_slots; g.logical_pos = logical_pos;
     g.scale_mode = p->scale_mode; g.fixed_scale = p->fixed_scale; g.lambda_floor = p->lambda_floor;
     return hip_result(launch_decode(g, dpl, workspace, p->dtype, (hipStream_t)stream),
@@ -389,8 +398,48 @@ int32_t aha_decode_step(const aha_params *p, const void *q_new, const void *k_ne
                         int32_t *pos_c, int32_t *free_slot, int32_t cache_slots,
                         int32_t logical_pos, void *out, void *workspace, size_t workspace_bytes,
                         void *stream) {
-    return decode_step_impl(p, q_new, k_new, v_new, k_cache, v_cache, scores_c, pos_c, free_slot,
-                            cache_slots, logical_pos, out, workspace, workspace_bytes, 0, stream);
+    DecodePlan dpl{};
+    const int32_t rc = decode_step_check(p, q_new, k_new, v_new, k_cache, v_cache, scores_c, pos_c,
+                                         free_slot, cache_slots, logical_pos, out, workspace,
+                                         workspace_bytes, 0, &dpl);
+    if (rc) return rc;
+    return decode_step_launch(p, dpl, q_new, k_new, v_new, k_cache, v_cache, scores_c, pos_c,
+                              free_slot, cache_slots, logical_pos, out, workspace, stream);
+}
+
+// ---- generation step without a workspace argument ----
+// Scratch of the split decode path (raw dots and the splits' partial outputs) for callers
+// that can neither allocate nor carry a workspace.  The array's name is only a host-side
+// stand-in: its device address is asked for once per device (each GPU holds its own copy
+// at its own address) and that pointer is what the kernels get.
+constexpr size_t kScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+static void *g_scratch_ptr[kMaxDevices];
+static DeviceOnce g_scratch_once;
+
+int32_t aha_decode_step_static(const aha_params *p, const void *q_new, const void *k_new,
+                               const void *v_new, void *k_cache, void *v_cache, float *scores_c,
+                               int32_t *pos_c, int32_t *free_slot, int32_t cache_slots,
+                               int32_t logical_pos, void *out, void *stream) {
+    DecodePlan dpl{};
+    const int32_t rc = decode_step_check(p, q_new, k_new, v_new, k_cache, v_cache, scores_c, pos_c,
+                                         free_slot, cache_slots, logical_pos, out, nullptr, 0,
+                                         kScratchBytes, &dpl);
+    if (rc) return rc;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_result(e, "hipGetDevice");
+    e = device_once(g_scratch_once, [dev] {
+        void *ptr = nullptr;
+        const hipError_t es = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        g_scratch_ptr[dev] = es == hipSuccess ? ptr : nullptr;
+        return es;
+    });
+    if (e != hipSuccess) return hip_result(e, "address of the built-in scratch buffer");
+    // every value the kernels read from the scratch is written earlier in the same call:
+    // nothing has to start from zero
+    return decode_step_launch(p, dpl, q_new, k_new, v_new, k_cache, v_cache, scores_c, pos_c,
+                              free_slot, cache_slots, logical_pos, out, g_scratch_ptr[dev], stream);
 }
 
 int32_t aha_profile_events(void *const *events, int32_t count) {
