@@ -1,15 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the AhaKV eviction hot path on one MI355X.
 
-One "step" is one pass of the whole path over one layer of synthetic input
-already resident in HBM: prefill eviction scores -> top-k selection -> KV
-compaction -> one decode step with running eviction on the fresh cache.  The
-workload is the 32K-context GQA layer (batch 1, 32 query / 8 KV heads,
-head_dim 128, bf16, window 64, budget 2048).
+One "step" is the prefill eviction of one layer of synthetic input already
+resident in HBM: eviction scores -> top-k selection -> KV compaction, on the
+32K-context GQA layer (batch 1, 32 query / 8 KV heads, head_dim 128, bf16,
+window 64, budget 2048).  The generation step with running eviction on the fresh
+cache is timed beside it (`decode_step_c3`, and `decode_c4` for the batched
+configuration), as the metric quotes the two separately.
 
-Prints ONE JSON line: the step time and throughput, per-kernel times from HIP events,
-the roofline of the dominant kernel, side measurements of the other configurations and the
-CPU oracle timed on a bounded sample of the same step.
+Prints ONE JSON line: the step time (mean over the timed steps; median and minimum from
+per-step events) and throughput, per-kernel times from HIP events on the launch stream, the
+roofline of the dominant kernel, side measurements of the other configurations and the CPU
+oracle timed on the same step.
 """
 from __future__ import annotations
 
@@ -36,6 +38,16 @@ def avg_ms(pairs):
     return sum(a.elapsed_time(b) for a, b in pairs) / max(len(pairs), 1)
 
 
+def us_stats(pairs):
+    """mean / median / min in microseconds of event pairs (already synchronised)."""
+    t = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)
+    if not t:
+        return {"mean": None, "median": None, "min": None}
+    mid = len(t) // 2
+    med = t[mid] if len(t) % 2 else 0.5 * (t[mid - 1] + t[mid])
+    return {"mean": sum(t) / len(t), "median": med, "min": t[0]}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -56,8 +68,7 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2506_03762_amd import binding as B, synth
-    from tests import harness as H
+    from paper_2506_03762_amd import binding as B, synth, workload as H
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -69,7 +80,7 @@ def main():
     log("generating", w.name)
     Q, K, V = synth.make_prefill(w, threads=16)
     q, k, v = (H.to_device(a, w.dtype) for a in (Q, K, V))
-    p = H.gpu_params(w).with_strides(q, k, v)
+    p = H.params_for(w).with_strides(q, k, v)
     ws = B.alloc_workspace(p)
     b, hq, hk, n, d, G = w.batch, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim, w.group
     scores = torch.empty((b, hk, n), dtype=torch.float32, device="cuda")
@@ -83,8 +94,11 @@ def main():
         B.aha_select_topk(p, scores, idx, ws)
         B.aha_compact_kv(p, k, v, scores, idx, cache.k, cache.v, cache.scores, cache.pos,
                          cache.free_slot)
-        B.aha_decode_step(p, qn, kn, vn, cache.k, cache.v, cache.scores, cache.pos,
-                          cache.free_slot, n + 1, out, ws)
+
+    def ev():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record()
+        return e
 
     if args.copy_probe:
         # an elementwise kernel that reads 256 MiB and writes 256 MiB
@@ -101,13 +115,17 @@ def main():
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / K_STEPS
+    # the same steps once more, each between two events: median and minimum
+    step_evs = []
+    for _ in range(K_STEPS):
+        e0 = ev(); step(); step_evs.append((e0, ev()))
+    torch.cuda.synchronize()
+    step_us = us_stats(step_evs)
 
     # ------------------------------------------- per-kernel times (events) --
-    def ev():
-        e = torch.cuda.Event(enable_timing=True)
-        e.record()
-        return e
-
+    # Events on the launch stream bracket every launch; between two launches that were
+    # enqueued back to back they measure the kernel plus the dispatch gap before it (2-3 us
+    # more than the kernel duration a profiler reports).
     stage_sets, call_sets = [], []
     for _ in range(K_STEPS):
         st = [ev() for _ in range(4)]
@@ -123,14 +141,15 @@ def main():
         stage_sets.append(st)
         call_sets.append((e0, e1, e2, e3))
     torch.cuda.synchronize()
-    kt = {
-        "value_prior": avg_ms([(s[0], s[1]) for s in stage_sets]),
-        "score_pass1": avg_ms([(s[1], s[2]) for s in stage_sets]),
-        "score_pass2": avg_ms([(s[2], s[3]) for s in stage_sets]),
-        "topk": avg_ms([(c[0], c[1]) for c in call_sets]),
-        "compact": avg_ms([(c[1], c[2]) for c in call_sets]),
-        "decode_step": avg_ms([(c[2], c[3]) for c in call_sets]),
+    kstats = {
+        "value_prior": us_stats([(s[0], s[1]) for s in stage_sets]),
+        "score_pass1": us_stats([(s[1], s[2]) for s in stage_sets]),
+        "score_pass2": us_stats([(s[2], s[3]) for s in stage_sets]),
+        "topk": us_stats([(c[0], c[1]) for c in call_sets]),
+        "compact": us_stats([(c[1], c[2]) for c in call_sets]),
+        "decode_step": us_stats([(c[2], c[3]) for c in call_sets]),
     }
+    kt = {name: st["mean"] * 1e-3 for name, st in kstats.items()}   # ms
     e = 2  # bf16 bytes
     kbytes = b * hk * n * d * e
     qbytes = b * hq * w.window * d * e
@@ -143,13 +162,14 @@ def main():
         "decode_step": b * hk * (2 * (w.budget + 1) * d * e + 8 * (w.budget + 1) + 2 * d * e)
                        + 2 * b * hq * d * e,
     }
-    kernels = {name: {"us": kt[name] * 1e3, "alg_bytes": alg[name],
-                      "GBps": alg[name] / (kt[name] * 1e-3) / 1e9 if kt[name] > 0 else None}
+    kernels = {name: {"us": kt[name] * 1e3, "median_us": kstats[name]["median"],
+                      "min_us": kstats[name]["min"], "alg_bytes": alg[name],
+                      "GBps": alg[name] / (kt[name] * 1e-3) / 1e9 if kt[name] > 1e-6 else None}
                for name in kt}
     score_flops_pass = 2.0 * d * b * hq * (w.window * n - w.window * (w.window - 1) / 2)
     for name in ("score_pass1", "score_pass2"):
         kernels[name]["TFLOPs"] = score_flops_pass / (kt[name] * 1e-3) / 1e12
-    dom = max(("value_prior", "score_pass1", "score_pass2", "topk", "compact", "decode_step"),
+    dom = max(("value_prior", "score_pass1", "score_pass2", "topk", "compact"),
               key=lambda nm: kt[nm])
     # HBM bytes per launch from the committed rocprofv3 counter summary of this workload
     traffic = None
@@ -161,17 +181,19 @@ def main():
         traffic = None
     roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["GBps"],
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dom]["GBps"] / HBM_PEAK_GBS,
-                "traffic": traffic}
+                "traffic": traffic,
+                "timing": "mean of HIP events around the launch on its stream (kernel + dispatch gap)",
+                "kernel_us": kt[dom] * 1e3, "alg_bytes": alg[dom]}
     # the whole score stage against the bytes the method needs once (K + V + Q window)
-    stage_ms = kt["value_prior"] + kt["score_pass1"] + kt["score_pass2"]
+    stage_ms = max(kt["value_prior"], 0.0) + kt["score_pass1"] + kt["score_pass2"]
     stage_bytes = 2 * kbytes + qbytes + b * hk * n * 4
-    roofline_stage = {"stage": "prefill_scores (3 launches)", "bound": "hbm",
+    roofline_stage = {"stage": "prefill_scores (all its launches)", "bound": "hbm",
                       "achieved": stage_bytes / (stage_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                       "unit": "GB/s", "frac": stage_bytes / (stage_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "mfma_TFLOPs": 2 * score_flops_pass / (stage_ms * 1e-3) / 1e12}
 
     result = {
-        "metric": "prefill eviction us/layer @32K ctx (scores + top-k + compaction + 1 decode step)",
+        "metric": "prefill eviction us/layer @32K ctx (scores + top-k + compaction)",
         "value": ms_per_step * 1e3, "unit": "us/layer", "n_gpus": 1, "steps": K_STEPS,
         "warmup": W_STEPS, "ms_per_step": ms_per_step, "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
@@ -179,7 +201,17 @@ def main():
                    "head_dim": d, "seq_len": n, "window": w.window, "budget": w.budget,
                    "recent": w.recent, "scale": "adaptive", "value_prior": True},
         "tokens_per_s": b * n / (ms_per_step * 1e-3),
+        "step_us": {"mean_wall_clock": ms_per_step * 1e3, "median_events": step_us["median"],
+                    "min_events": step_us["min"]},
+        "decode_step_c3": {"us": kstats["decode_step"]["mean"],
+                           "median_us": kstats["decode_step"]["median"],
+                           "min_us": kstats["decode_step"]["min"],
+                           "tokens_per_s": b / (kt["decode_step"] * 1e-3),
+                           "note": "one generation step on the fresh 8-head cache (latency-bound)"},
         "roofline": roofline, "roofline_stage": roofline_stage, "kernels": kernels,
+        "note": "the 134 MB of C3 inputs are re-read every step and fit the 256 MB last-level "
+                "cache: GB/s figures of this workload are fabric-side rates; prefill_c5_layer is "
+                "the HBM-bound shape",
     }
 
     if not args.no_extras:
@@ -189,7 +221,7 @@ def main():
         result["scores_from_lse_c3"] = bench_lse_c3(torch, B, H, w, p, q, k, v, scores, ws, K_STEPS)
         result["full_accumulation_c3"] = bench_full_c3(torch, B, w, p, q, k, v, scores)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, (Q, K, V), synth, H)
+        result["cpu_baseline"] = cpu_baseline(w, (Q, K, V))
     print(json.dumps(result))
 
 
@@ -199,7 +231,7 @@ def bench_decode_c4(torch, B, synth, H, steps):
     log("generating", w.name)
     Q, K, V = synth.make_prefill(w, threads=16)
     q, k, v = (H.to_device(a, w.dtype) for a in (Q, K, V))
-    p = H.gpu_params(w).with_strides(q, k, v)
+    p = H.params_for(w).with_strides(q, k, v)
     ws = B.alloc_workspace(p)
     b, hq, hk, n, d = w.batch, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
     scores = torch.empty((b, hk, n), dtype=torch.float32, device="cuda")
@@ -259,9 +291,8 @@ def bench_full_c2(torch, B, synth, H, steps):
     log("generating", w.name)
     Q, K, V = synth.make_prefill(w, threads=16)
     q, k, v = (H.to_device(a, w.dtype) for a in (Q, K, V))
-    opts = H.Opts(window=w.seq_len, scale_mode=0, fixed_scale=1 / math.sqrt(w.head_dim),
-                  value_prior=False)
-    p = H.gpu_params(w, opts).with_strides(q, k, v)
+    p = H.params_for(w, window=w.seq_len, scale_mode=B.AHA_SCALE_FIXED,
+                     fixed_scale=1 / math.sqrt(w.head_dim), value_prior=False).with_strides(q, k, v)
     ws = B.alloc_workspace(p)
     b, hq, hk, n, d = w.batch, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
     scores = torch.empty((b, hk, n), dtype=torch.float32, device="cuda")
@@ -361,7 +392,7 @@ def bench_c5_layer(torch, B, synth, H, steps):
     g = torch.Generator(device="cuda"); g.manual_seed(synth.BASE_SEED + 5000)
     q, k, v = (torch.randn((b, hh, n, d), device="cuda", generator=g).to(torch.bfloat16)
                for hh in (hq, hk, hk))
-    p = H.gpu_params(w).with_strides(q, k, v)
+    p = H.params_for(w).with_strides(q, k, v)
     ws = B.alloc_workspace(p)
     scores = torch.empty((b, hk, n), dtype=torch.float32, device="cuda")
     idx = torch.empty((b, hk, w.budget), dtype=torch.int32, device="cuda")
@@ -402,17 +433,20 @@ def bench_c5_layer(torch, B, synth, H, steps):
     return out
 
 
-def cpu_baseline(w, inputs, synth, H):
-    """The float64 oracle, as it stands, on the host cores: the same step once."""
+def cpu_baseline(w, inputs):
+    """The float64 oracle, as it stands, on the host cores: the same step (scores, selection,
+    compaction of one layer), repeated for about ten seconds."""
     import numpy as np
     import oracle
     Q, K, V = inputs
     log("timing the CPU oracle on", w.name)
-    qn, kn, vn = synth.make_decode_inputs(w, 0)
+    cfg = oracle.Config(window=w.window, budget=w.budget, recent=w.recent)
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
     reps, t0 = 0, time.perf_counter()
     while reps < 3 or time.perf_counter() - t0 < 10.0:
-        ref = H.run_prefill_oracle(w, H.Opts(), (Q, K, V))
-        oracle.decode_step(ref.cache, qn, kn, vn, w.seq_len + 1, H.oracle_cfg(w, H.Opts()))
+        S = oracle.prefill_scores(Q, K, V, cfg)
+        idx = oracle.select_topk(S, w.budget, w.recent)
+        oracle.compact_kv(K64, V64, S, idx, slots=w.budget + 1)
         reps += 1
     dt = (time.perf_counter() - t0) / reps
     cores = min(oracle.num_threads(), w.batch * w.n_kv_heads)

@@ -117,6 +117,14 @@ class Params:
     score_pool: int = 0
 
     def c(self) -> aha_params:
+        """The C struct (built once per distinct set of field values: calls in a loop reuse it)."""
+        key = (self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.seq_len,
+               self.window, self.budget, self.recent, self.dtype, self.scale_mode,
+               self.fixed_scale, self.lambda_floor, self.value_prior, self.pool_kernel,
+               tuple(self.q_stride), tuple(self.k_stride), tuple(self.v_stride), self.score_pool)
+        cached = self.__dict__.get("_c")
+        if cached is not None and cached[0] == key:
+            return aha_params.from_buffer_copy(cached[1])   # a copy: callers may edit theirs
         p = aha_params()
         for f in ("batch", "n_q_heads", "n_kv_heads", "head_dim", "seq_len", "window", "budget",
                   "recent", "dtype", "scale_mode", "value_prior", "pool_kernel", "score_pool"):
@@ -126,6 +134,7 @@ class Params:
         p.q_stride = (ctypes.c_int64 * 3)(*self.q_stride)
         p.k_stride = (ctypes.c_int64 * 3)(*self.k_stride)
         p.v_stride = (ctypes.c_int64 * 3)(*self.v_stride)
+        self.__dict__["_c"] = (key, bytes(p))
         return p
 
     def with_strides(self, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor) -> "Params":

@@ -70,22 +70,16 @@ def run_prefill_oracle(w: synth.Workload, opts: Opts = Opts(), inputs=None, laye
 
 # --------------------------------------------------------------------- GPU --
 def to_device(a: np.ndarray, dtype: str):
-    import torch
-    if dtype == "bf16":
-        bits = synth.bf16_bits(a).view(np.int16)
-        return torch.from_numpy(bits).cuda().view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    from paper_2506_03762_amd import workload
+    return workload.to_device(a, dtype)
 
 
 def gpu_params(w: synth.Workload, opts: Opts = Opts()):
-    from paper_2506_03762_amd import binding as B
-    return B.Params(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
-                    head_dim=w.head_dim, seq_len=w.seq_len, window=opts.window or w.window,
-                    budget=w.budget, recent=w.recent,
-                    dtype=B.AHA_BF16 if w.dtype == "bf16" else B.AHA_F32,
-                    scale_mode=opts.scale_mode, fixed_scale=opts.fixed_scale,
-                    lambda_floor=opts.lambda_floor, value_prior=1 if opts.value_prior else 0,
-                    pool_kernel=opts.pool, score_pool=opts.score_pool)
+    from paper_2506_03762_amd import workload
+    return workload.params_for(w, window=opts.window, scale_mode=opts.scale_mode,
+                               fixed_scale=opts.fixed_scale, lambda_floor=opts.lambda_floor,
+                               value_prior=opts.value_prior, pool=opts.pool,
+                               score_pool=opts.score_pool)
 
 
 def run_prefill_gpu(w: synth.Workload, opts: Opts = Opts(), inputs=None, layer=0,
