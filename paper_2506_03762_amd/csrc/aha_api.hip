@@ -172,10 +172,10 @@ static PrefillPlan plan_prefill(const aha_params *p) {
         off = align_up(off + sizeof(float) * (size_t)pl.Z * rows * pl.nchunks, 256);
     pl.off_gamma = off;
     off = align_up(off + sizeof(float) * (size_t)pl.Z * n, 256);
-    pl.off_gblockmax = off;
-    off = align_up(off + sizeof(float) * (size_t)pl.Z * pl.n_vtiles, 256);
-    pl.off_lam = off;  // log2-domain softmax scale of each window row
-    off = align_up(off + sizeof(float) * (size_t)p->window, 256);
+    pl.off_gblockmax = off;  // per-range maxima of the value prior: per tile, or per key chunk
+    const size_t n_maxima = (size_t)(pl.n_vtiles > pl.nchunks ? pl.n_vtiles : pl.nchunks);
+    off = align_up(off + sizeof(float) * (size_t)pl.Z * n_maxima, 256);
+    pl.can_fold = p->dtype == AHA_BF16 && pl.n_qtiles == 1;
     pl.bytes = off;
     return pl;
 }
@@ -279,12 +279,16 @@ static int32_t prefill_scores_impl(const aha_params *p, const void *q, const voi
     const ScoreGeom g = make_geom(p, q, k, v);
     hipStream_t st = (hipStream_t)stream;
     if ((rc = hip_result(stage(0, st), "stage event"))) return rc;
-    if ((rc = hip_result(launch_value_prior(g, pl, workspace, scores, lse, st), "value-prior kernel")))
+    // the windowed bf16 scores form the value prior inside their row-statistics launch
+    const bool fold_prior = pl.can_fold && p->value_prior && !with_lse;
+    if ((rc = hip_result(launch_value_prior(g, pl, workspace, scores, lse,
+                                            p->value_prior && !fold_prior, st),
+                         "value-prior kernel")))
         return rc;
     if ((rc = hip_result(stage(1, st), "stage event"))) return rc;
     hipEvent_t mid = g_stage_on ? g_stage_ev[2] : nullptr;
     if (p->dtype == AHA_BF16)
-        rc = hip_result(launch_score_bf16(g, pl, workspace, scores, st, mid, with_lse),
+        rc = hip_result(launch_score_bf16(g, pl, workspace, scores, st, mid, with_lse, fold_prior),
                         "bf16 score kernels");
     else
         rc = hip_result(launch_score_f32(g, pl, workspace, scores, st, mid, with_lse),

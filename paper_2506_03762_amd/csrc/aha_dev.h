@@ -141,6 +141,54 @@ __device__ __forceinline__ float prior_factor(float gam, float ginv) {
     return ginv < 0.f ? 1.f : gam * ginv;
 }
 
+// nu = ||V_row||^2 (Sec. 4.3) of the value rows [lo, hi) of one head, into s_nu[row - lo]
+// (LDS); called by all 256 threads of a workgroup, no barrier inside.  16-byte loads, the
+// lanes of a row adjacent.  The rows are read with streaming (non-temporal) loads: they are
+// used once, and kept out of the caches they leave them to the keys, which the two score
+// passes read twice.  U independent loads are in flight per lane: nine for the stand-alone
+// kernel, whose thousands of workgroups keep the memory system full (with 16 lanes per row a
+// 256-row tile and its pooling halo take two batches; many more measured slower there).
+template <int ESIZE, int U = 9>
+__device__ __forceinline__ void value_norms_to_lds(const char *vbase, int64_t row_stride, int d,
+                                                   int lo, int hi, float *s_nu, int tid) {
+    const int lpr = d * ESIZE / 16;  // lanes per row: 8, 16 or 32
+    const int rows_per_pass = 256 / lpr;
+    const int sub = tid % lpr, rloc = tid / lpr;
+    for (int row0 = lo + rloc; row0 < hi; row0 += U * rows_per_pass) {
+        u32x4 w[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int row = min(row0 + u * rows_per_pass, hi - 1);
+            w[u] = __builtin_nontemporal_load(
+                (const u32x4 *)(vbase + (int64_t)ESIZE * row * row_stride + sub * 16));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float s = 0.f;
+            if (ESIZE == 2) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    float a = bf16_lo(w[u][t]), c = bf16_hi(w[u][t]);
+                    s = fmaf(a, a, s);
+                    s = fmaf(c, c, s);
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    float a = __uint_as_float(w[u][t]);
+                    s = fmaf(a, a, s);
+                }
+            }
+            // over the lanes of the row (8, 16 or 32 of them)
+            s = reduce_lanes<1, 8>(s, OpSum{});
+            if (lpr >= 16) s = combine_lane_xor<8>(s, OpSum{});
+            if (lpr >= 32) s = combine_lane_xor<16>(s, OpSum{});
+            const int row = row0 + u * rows_per_pass;
+            if (sub == 0 && row < hi) s_nu[row - lo] = s;
+        }
+    }
+}
+
 // Softmax geometry of the flattened query rows of one KV head: row rho of the
 // group is query head g = rho / r, window row ii = rho % r, token position
 // i = n - r + ii.

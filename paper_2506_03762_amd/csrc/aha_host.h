@@ -52,8 +52,9 @@ struct PrefillPlan {
     int chunk_keys;  // keys per pass-1 workgroup
     int nchunks;     // pass-1 key chunks per (problem, query tile)
     int p2_keys;     // keys per pass-2 workgroup (a multiple of kP2Keys)
-    int n_vtiles;    // value-prior tiles per problem
-    size_t off_rowL, off_partial, off_gamma, off_gblockmax, off_lam;
+    int n_vtiles;    // value-prior tiles per problem (separate launch)
+    bool can_fold;   // windowed bf16 scores: pass 1 can form the value prior per key chunk
+    size_t off_rowL, off_partial, off_gamma, off_gblockmax;
     size_t bytes;
 };
 
@@ -64,16 +65,20 @@ constexpr int kP2Keys = 256;      // keys per pass-2 workgroup (4 waves x 64)
 // `lse`, when not null, holds the caller's natural-log row normalisers
 // [batch, Hq, window]; the launch then also writes them, in the log2 domain, where pass 2
 // expects the row statistics (and the score launchers skip pass 1).
+// `prior_here`: this launch forms the value prior (the windowed bf16 scores form it inside
+// their row-statistics launch instead).  Launches nothing when there is nothing to do.
 hipError_t launch_value_prior(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
-                              float *scores, const float *lse, hipStream_t st);
+                              float *scores, const float *lse, bool prior_here, hipStream_t st);
 // score_f32.hip
 // `mid`, when not null, is recorded between the two passes; `have_lse`: the row statistics
 // are already in the workspace, pass 1 is skipped.
 hipError_t launch_score_f32(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
                             float *scores, hipStream_t st, hipEvent_t mid, bool have_lse);
 // score_bf16.hip
+// `fold_prior`: pass 1 also forms the value prior of its key range (windowed scores only).
 hipError_t launch_score_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
-                             float *scores, hipStream_t st, hipEvent_t mid, bool have_lse);
+                             float *scores, hipStream_t st, hipEvent_t mid, bool have_lse,
+                             bool fold_prior);
 // topk.hip
 // `pool` > 1: the candidates are ranked by the scores pooled over `pool` tokens, which are
 // written to `pooled` ([Z][n] floats) first.

@@ -98,14 +98,15 @@ __device__ __forceinline__ void q_tile_commit(const QTileRegs<D, NB> &t, int tid
 }
 
 // Per-row scale and position of the tile (one row per thread: a tile has at most 256 rows).
-// The scale is requested here and stored by q_tile_meta, so that other loads can be issued
-// in between.
+// The scale of window row ii (token position n - r + ii, c = position + 1 keys) is a
+// logarithm and a square root per row and tile: computed in place, no table.
 template <int D, int NB>
-__device__ __forceinline__ float q_tile_scale_request(const ScoreGeom &g, int rho0, int tid,
-                                                      const float *lam_tab) {
+__device__ __forceinline__ float q_tile_scale(const ScoreGeom &g, int rho0, int tid) {
     static_assert(TileSmem<D, NB>::ROWS <= 256, "one tile row per thread");
     const int rho = rho0 + min(tid, TileSmem<D, NB>::ROWS - 1);
-    return lam_tab[rho < g.R ? rho % g.r : 0];
+    const int ii = rho < g.R ? rho % g.r : 0;
+    return row_scale_log2_f32(g.scale_mode, g.fixed_scale, g.lambda_floor, g.n - g.r + ii + 1,
+                              g.budget, g.d);
 }
 template <int D, int NB>
 __device__ __forceinline__ void q_tile_meta(const ScoreGeom &g, const RowMap &rm, int rho0,
@@ -272,10 +273,56 @@ __device__ __forceinline__ Segment pair_segment(const RowMap &rm, int rows, int 
 }
 
 // ---------------------------------------------------------------- pass 1 --
+// Value prior (Sec. 4.3) of the keys [kbeg, kend) of problem z, formed by the workgroup that
+// computes those keys' row statistics: nu = ||V||^2 of the range and its pooling halo into
+// LDS, gamma = edge-truncated mean over the pool window, written to `gamma`; returns (in
+// every thread) the largest gamma of the range.  Works through the range in pieces of
+// kPriorPiece keys so that the LDS it borrows (the query tile's, free at that time) stays
+// small.  Ends with a barrier: the LDS may be reused at once.
+constexpr int kPriorPiece = 512;
+// value rows a lane requests before it uses the first (9 and 33 measured slower here)
+constexpr int kPriorLoads = 17;
+constexpr size_t kPriorSmem = (kPriorPiece + 256 + 4) * sizeof(float);
+__device__ __forceinline__ float value_prior_of_range(const ScoreGeom &g, int b, int h, int z,
+                                                      int kbeg, int kend, float *s_nu,
+                                                      float *gamma, int tid) {
+    const char *vbase = (const char *)g.v + (int64_t)2 * (b * g.vs[0] + h * g.vs[1]);
+    const int half = (g.pool - 1) / 2;
+    float *s_max = s_nu + kPriorPiece + 256;
+    float gmax = 0.f;
+    for (int t0 = kbeg; t0 < kend; t0 += kPriorPiece) {
+        const int t1 = min(kend, t0 + kPriorPiece);
+        const int lo = max(0, t0 - half), hi = min(g.n, t1 + half);  // hi exclusive
+        value_norms_to_lds<2, kPriorLoads>(vbase, g.vs[2], g.d, lo, hi, s_nu, tid);
+        __syncthreads();
+        for (int j = t0 + tid; j < t1; j += 256) {
+            const int a = max(0, j - half), e = min(g.n - 1, j + half);
+            float s = 0.f;
+            for (int t = a; t <= e; ++t) s += s_nu[t - lo];
+            const float gam = s / (float)(e - a + 1);
+            gamma[(int64_t)z * g.n + j] = gam;
+            gmax = fmaxf(gmax, gam);
+        }
+        __syncthreads();
+    }
+    gmax = wave_max(gmax);
+    if ((tid & 63) == 0) s_max[tid >> 6] = gmax;
+    __syncthreads();
+    gmax = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+    __syncthreads();
+    return gmax;
+}
+
+// `gamma` != null (windowed scores with the value prior): the workgroup also forms the prior
+// of its key range, after its statistics, and leaves the range's maximum in
+// gblockmax[z * nparts + part]: one launch less than a value-prior kernel of its own (a
+// launch costs 4 - 5 us, a third of that kernel's time at 8 heads x 32K).  (Letting half of
+// the workgroups form the prior first, so that value streaming and arithmetic would meet on
+// the chip, measured the same.)
 template <int D, int NB>
 __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles, int nparts,
-                                                            int total_wgs, const float *lam_tab,
-                                                            float *partial) {
+                                                            int total_wgs, float *partial,
+                                                            float *gamma, float *gblockmax) {
     using S = TileSmem<D, NB>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __bf16 *sQ = (__bf16 *)smem;
@@ -329,7 +376,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
             asm volatile("" : "+v"(tid_s));
             QTileRegs<D, NB> qt_regs;
             q_tile_request<D, NB>(g, b, h, rho0, tid_s, qt_regs);
-            const float lam_req = q_tile_scale_request<D, NB>(g, rho0, tid_s, lam_tab);
+            const float lam_req = q_tile_scale<D, NB>(g, rho0, tid_s);
             __builtin_amdgcn_sched_barrier(0);  // the key block is requested last
             load_a<D>(kbase, g.ks[2], kb_of(0), key_end, lane, a0);
             q_tile_meta<D, NB>(g, rm, rho0, tid_s, lam_req, sLam, sPos, sBlk);
@@ -413,6 +460,12 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
                 sum += e.y * fast_exp2(e.x - mref);
             }
             my_partial[tid] = M + log2f(sum);  // -inf for a row that saw no key
+        }
+        if (gamma) {
+            __syncthreads();  // the reduction buffer is done with
+            const float gm = value_prior_of_range(g, b, h, z, key_begin, key_end, (float *)smem,
+                                                  gamma, tid);
+            if (tid == 0) gblockmax[z * nparts + part] = gm;
         }
     }
 }
@@ -508,7 +561,6 @@ __device__ __forceinline__ void chunk_merge(const float (&e)[BATCH], int count, 
 template <int D, int NB, bool SINGLE>
 __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_qtiles,
                                                             int total_wgs, int wg_keys, int nchunks,
-                                                            const float *lam_tab,
                                                             const float *partial,
                                                             const float *gamma,
                                                             const float *gblockmax,
@@ -573,7 +625,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
                                  (tid < S::ROWS ? tid : 0);
             q_tile_request<D, NB>(g, b, h, rho0, tid, qt_regs);
             chunk_request(psrc, S::ROWS, 0, nchunks_t, ch);
-            const float lam_req = q_tile_scale_request<D, NB>(g, rho0, tid, lam_tab);
+            const float lam_req = q_tile_scale<D, NB>(g, rho0, tid);
             __builtin_amdgcn_sched_barrier(0);  // the key block is requested last
             load_a<D>(kbase, g.ks[2], first_kb, key_end, lane, a0);
             q_tile_meta<D, NB>(g, rm, rho0, tid, lam_req, sLam, sPos, sBlk);
@@ -737,13 +789,13 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
 // ---------------------------------------------------------------- launch --
 template <int D, int NB>
 static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
-                           hipStream_t st, hipEvent_t mid, bool have_lse) {
+                           hipStream_t st, hipEvent_t mid, bool have_lse, bool fold_prior) {
     using S = TileSmem<D, NB>;
+    static_assert(S::bytes >= kPriorSmem, "the value-prior phase borrows the query tile's LDS");
     char *w = (char *)ws;
     float *partial = (float *)(w + pl.off_partial);
-    const float *gamma = (const float *)(w + pl.off_gamma);
-    const float *gbm = (const float *)(w + pl.off_gblockmax);
-    const float *lam_tab = (const float *)(w + pl.off_lam);
+    float *gamma = (float *)(w + pl.off_gamma);
+    float *gbm = (float *)(w + pl.off_gblockmax);
     static DeviceOnce once;
     const hipError_t ea = device_once(once, [] {
         const void *kernels[3] = {(const void *)bf16_pass1_kernel<D, NB>,
@@ -764,35 +816,38 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     // with the caller's row normalisers already in place (one "chunk" per row) pass 1 is skipped
     if (!have_lse)
         hipLaunchKernelGGL((bf16_pass1_kernel<D, NB>), xcd_grid(wgs1), dim3(256), S::bytes, st, g,
-                           pl.n_qtiles, pl.nchunks, (int)wgs1, lam_tab, partial);
+                           pl.n_qtiles, pl.nchunks, (int)wgs1, partial,
+                           fold_prior ? gamma : nullptr, gbm);
     const int stat_chunks = have_lse ? 1 : pl.nchunks;
+    // the prior's per-range maxima: one per key chunk when pass 1 formed it, else per tile
+    const int n_maxima = fold_prior ? pl.nchunks : pl.n_vtiles;
     if (mid) (void)hipEventRecord(mid, st);
     if (pl.n_qtiles == 1)
         hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, true>), xcd_grid(wgs2), dim3(256), S::bytes,
-                           st, g, pl.n_qtiles, (int)wgs2, pl.p2_keys, stat_chunks, lam_tab, partial,
-                           gamma, gbm, pl.n_vtiles, scores);
+                           st, g, pl.n_qtiles, (int)wgs2, pl.p2_keys, stat_chunks, partial,
+                           gamma, gbm, n_maxima, scores);
     else
         hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, false>), xcd_grid(wgs1), dim3(256), S::bytes,
-                           st, g, pl.n_qtiles, (int)wgs1, pl.nchunks, stat_chunks, lam_tab, partial,
-                           gamma, gbm, pl.n_vtiles, scores);
+                           st, g, pl.n_qtiles, (int)wgs1, pl.nchunks, stat_chunks, partial,
+                           gamma, gbm, n_maxima, scores);
     return hipGetLastError();
 }
 
 template <int D>
 static hipError_t launch_d(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
-                           hipStream_t st, hipEvent_t mid, bool have_lse) {
+                           hipStream_t st, hipEvent_t mid, bool have_lse, bool fold_prior) {
     switch (pl.NB) {
-        case 1: return launch_t<D, 1>(g, pl, ws, scores, st, mid, have_lse);
-        case 2: return launch_t<D, 2>(g, pl, ws, scores, st, mid, have_lse);
-        case 4: return launch_t<D, 4>(g, pl, ws, scores, st, mid, have_lse);
-        default: return launch_t<D, 8>(g, pl, ws, scores, st, mid, have_lse);
+        case 1: return launch_t<D, 1>(g, pl, ws, scores, st, mid, have_lse, fold_prior);
+        case 2: return launch_t<D, 2>(g, pl, ws, scores, st, mid, have_lse, fold_prior);
+        case 4: return launch_t<D, 4>(g, pl, ws, scores, st, mid, have_lse, fold_prior);
+        default: return launch_t<D, 8>(g, pl, ws, scores, st, mid, have_lse, fold_prior);
     }
 }
 
 hipError_t launch_score_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
-                             hipStream_t st, hipEvent_t mid, bool have_lse) {
-    return g.d == 64 ? launch_d<64>(g, pl, ws, scores, st, mid, have_lse)
-                     : launch_d<128>(g, pl, ws, scores, st, mid, have_lse);
+                             hipStream_t st, hipEvent_t mid, bool have_lse, bool fold_prior) {
+    return g.d == 64 ? launch_d<64>(g, pl, ws, scores, st, mid, have_lse, fold_prior)
+                     : launch_d<128>(g, pl, ws, scores, st, mid, have_lse, fold_prior);
 }
 
 }  // namespace aha

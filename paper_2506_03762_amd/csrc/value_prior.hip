@@ -3,8 +3,10 @@
 // maxima of gamma from which the consumers form gamma / max(gamma).
 //
 // HBM-bound: V is read exactly once (plus (pool-1)/2 halo rows per tile).
-// The same launch tabulates the softmax scale of every window row (evaluated
-// in double), so no separate set-up launch is needed.
+// The windowed bf16 scores form the prior inside their row-statistics launch
+// (score_bf16.hip) and do not use this kernel; it serves the fp32 path, full
+// accumulation (where it also zeroes the scores) and the entry point that is
+// handed the rows' normalisers (which it converts for the column-sum pass).
 #include "aha_dev.h"
 #include "aha_host.h"
 
@@ -14,7 +16,7 @@ namespace aha {
 // 16-byte loads; LPR lanes cover one row.
 template <int ESIZE>
 __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, float *gamma,
-                                                     float *gblockmax, float *lam_tab,
+                                                     float *gblockmax,
                                                      float *zero_scores, const float *lse,
                                                      float *row_stats, int rows_pad) {
     const int z = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
@@ -36,15 +38,6 @@ __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, 
         const int j = tile * kVTileRows + tid;
         if (j < g.n) zero_scores[(int64_t)z * g.n + j] = 0.f;
     }
-    if (z == 0) {
-        // softmax scale of window row ii (token position n - r + ii, c = position + 1 keys)
-        const int ii = tile * 256 + tid;
-        if (ii < g.r)
-            lam_tab[ii] = ESIZE == 2 ? row_scale_log2_f32(g.scale_mode, g.fixed_scale, g.lambda_floor,
-                                                          g.n - g.r + ii + 1, g.budget, g.d)
-                                     : row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor,
-                                                      g.n - g.r + ii + 1, g.budget, g.d);
-    }
     if (!g.value_prior || tile >= n_vtiles) return;
 
     __shared__ float s_nu[kVTileRows + 256];
@@ -56,49 +49,7 @@ __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, 
     const int t0 = tile * kVTileRows;
     const int lo = max(0, t0 - half);
     const int hi = min(g.n, t0 + kVTileRows + half);  // exclusive
-    const int lpr = g.d * ESIZE / 16;                 // lanes per row: 8, 16 or 32
-    const int rows_per_pass = 256 / lpr;
-    const int sub = tid % lpr, rloc = tid / lpr;
-
-    // V is read exactly once, with streaming loads: kept out of the caches it leaves them to
-    // the keys, which the two score passes read twice (pass 1 ran 5 % faster at the
-    // full-depth shape; the same hint on pass 2's key loads made that pass 35 % slower).
-    // nine independent 16-byte loads in flight per lane: with 16 lanes per row a tile and
-    // its pooling halo (256 + 6 rows) then take two batches, not three (many more in flight
-    // measured slower at the large shapes)
-    constexpr int U = 9;
-    for (int row0 = lo + rloc; row0 < hi; row0 += U * rows_per_pass) {
-        u32x4 w[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int row = min(row0 + u * rows_per_pass, hi - 1);
-            w[u] = __builtin_nontemporal_load((const u32x4 *)(vbase + (int64_t)ESIZE * row * g.vs[2] + sub * 16));
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float s = 0.f;
-            if (ESIZE == 2) {
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    float a = bf16_lo(w[u][t]), c = bf16_hi(w[u][t]);
-                    s = fmaf(a, a, s);
-                    s = fmaf(c, c, s);
-                }
-            } else {
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    float a = __uint_as_float(w[u][t]);
-                    s = fmaf(a, a, s);
-                }
-            }
-            // over the lanes of the row (8, 16 or 32 of them)
-            s = reduce_lanes<1, 8>(s, OpSum{});
-            if (lpr >= 16) s = combine_lane_xor<8>(s, OpSum{});
-            if (lpr >= 32) s = combine_lane_xor<16>(s, OpSum{});
-            const int row = row0 + u * rows_per_pass;
-            if (sub == 0 && row < hi) s_nu[row - lo] = s;
-        }
-    }
+    value_norms_to_lds<ESIZE>(vbase, g.vs[2], g.d, lo, hi, s_nu, tid);
     __syncthreads();
 
     const int j = t0 + tid;
@@ -118,26 +69,27 @@ __global__ __launch_bounds__(256) void vprior_kernel(ScoreGeom g, int n_vtiles, 
 }
 
 hipError_t launch_value_prior(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
-                              float *scores, const float *lse, hipStream_t st) {
+                              float *scores, const float *lse, bool prior_here, hipStream_t st) {
     char *w = (char *)ws;
     float *gamma = (float *)(w + pl.off_gamma);
     float *gbm = (float *)(w + pl.off_gblockmax);
-    float *lam_tab = (float *)(w + pl.off_lam);
-    const int lam_blocks = (g.r + 255) / 256;
     // bf16 full accumulation (several query tiles) needs zeroed scores
     float *zero_scores = (g.dtype == AHA_BF16 && pl.n_qtiles > 1) ? scores : nullptr;
-    const int vt = (g.value_prior || zero_scores) ? pl.n_vtiles : 1;
-    dim3 grid(vt > lam_blocks ? vt : lam_blocks, pl.Z);
+    if (!prior_here && !zero_scores && !lse) return hipSuccess;  // nothing for this launch to do
+    ScoreGeom gl = g;
+    gl.value_prior = prior_here ? 1 : 0;
+    const int vt = (prior_here || zero_scores) ? pl.n_vtiles : 1;
+    dim3 grid(vt, pl.Z);
     // where pass 2 reads the row statistics: one chunk per (problem, tile, row) on the bf16
     // path (rows padded to whole tiles), one value per row on the fp32 path
     float *row_stats = (float *)(w + (g.dtype == AHA_BF16 ? pl.off_partial : pl.off_rowL));
     const int rows_pad = g.dtype == AHA_BF16 ? pl.n_qtiles * pl.qtile : g.R;
     if (g.dtype == AHA_BF16)
-        hipLaunchKernelGGL(vprior_kernel<2>, grid, dim3(256), 0, st, g, pl.n_vtiles, gamma, gbm,
-                           lam_tab, zero_scores, lse, row_stats, rows_pad);
+        hipLaunchKernelGGL(vprior_kernel<2>, grid, dim3(256), 0, st, gl, pl.n_vtiles, gamma, gbm,
+                           zero_scores, lse, row_stats, rows_pad);
     else
-        hipLaunchKernelGGL(vprior_kernel<4>, grid, dim3(256), 0, st, g, pl.n_vtiles, gamma, gbm,
-                           lam_tab, zero_scores, lse, row_stats, rows_pad);
+        hipLaunchKernelGGL(vprior_kernel<4>, grid, dim3(256), 0, st, gl, pl.n_vtiles, gamma, gbm,
+                           zero_scores, lse, row_stats, rows_pad);
     return hipGetLastError();
 }
 
