@@ -135,6 +135,20 @@ def row_lse(Q, K, cfg: Config):
     return L
 
 
+def row_entropy(Q, K, cfg: Config):
+    """Entropy (nats) of the observed softmax rows [batch, n_q_heads, window]."""
+    Q, K = _f64(Q), _f64(K)
+    b, hq, n, d = Q.shape
+    hk = K.shape[1]
+    assert hq % hk == 0 and K.shape == (b, hk, n, d) and 1 <= cfg.window <= n
+    H = np.empty((b, hq, cfg.window), dtype=np.float64)
+    _load().aha_oracle_row_entropy(
+        _p(Q), _p(K), _I64(b), _I64(hq), _I64(hk), _I64(n), _I64(d), _I64(cfg.window),
+        _I64(cfg.budget), ctypes.c_int(cfg.scale_mode), ctypes.c_double(cfg.fixed_scale),
+        ctypes.c_double(cfg.lambda_floor), _p(H))
+    return H
+
+
 def prefill_scores_lse(Q, K, V, lse, cfg: Config):
     """Refined eviction scores [batch, n_kv_heads, n] from given row normalisers."""
     Q, K, V, lse = _f64(Q), _f64(K), _f64(V), _f64(lse)

@@ -246,6 +246,44 @@ void aha_oracle_row_lse(const double *Q, const double *K,
 }
 
 /* ------------------------------------------------------------------------
+ * Information entropy of the observed rows (Sec. 4.2, the definition
+ * H_i = - sum_j a_ij log a_ij over the keys j <= i the row attends to,
+ * natural logarithm; a term with a_ij = 0 contributes 0), under the scale the
+ * row uses.  With the standard scale its expectation on Gaussian logits is
+ * log i - d/2 (scaled by 1/sqrt(d): log i - 1/2), with the adaptive scale it
+ * is log k by construction.
+ *
+ * Q: [batch, n_q_heads, n, d], K: [batch, n_kv_heads, n, d]
+ * H: [batch, n_q_heads, window]; entry ii is query position n-window+ii.
+ * ---------------------------------------------------------------------- */
+void aha_oracle_row_entropy(const double *Q, const double *K,
+                            int64_t batch, int64_t n_q_heads, int64_t n_kv_heads,
+                            int64_t n, int64_t d, int64_t window, int64_t budget,
+                            int scale_mode, double fixed_scale, double lambda_floor,
+                            double *H)
+{
+    int64_t G = n_q_heads / n_kv_heads;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int64_t b = 0; b < batch; ++b) {
+        for (int64_t hq = 0; hq < n_q_heads; ++hq) {
+            const double *Kh = K + ((b * n_kv_heads + hq / G) * n) * d;
+            double *p = (double *)malloc(sizeof(double) * (size_t)n);
+            for (int64_t ii = 0; ii < window; ++ii) {
+                int64_t i = n - window + ii, c = i + 1;
+                const double *q = Q + (((b * n_q_heads + hq) * n) + i) * d;
+                double s = row_scale(scale_mode, fixed_scale, lambda_floor, c, budget, d);
+                softmax_row(q, Kh, c, d, s, p);
+                double h = 0.0;
+                for (int64_t j = 0; j < c; ++j)
+                    if (p[j] > 0.0) h -= p[j] * log(p[j]);
+                H[((b * n_q_heads + hq) * window) + ii] = h;
+            }
+            free(p);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------
  * Prefill eviction scores from given row normalisers: the same sum as
  * aha_oracle_prefill_scores, with p_ij = exp(s w_ij - lse_i) taken from the
  * caller's lse instead of normalising the row here.  With the lse of

@@ -219,6 +219,41 @@ def test_entropy_targets_on_gaussian_inputs():
     assert ada < std  # the gain sharpens the rows
 
 
+def test_row_entropy_closed_forms_and_library_route():
+    """Entropy of the observed rows: ln c_i exactly for uniform rows (scale 0), 0 in the
+    one-hot limit, scipy.stats.entropy of a library softmax on the masked logits otherwise,
+    and 0 <= H <= ln c_i throughout; the two expectations of Sec. 4.2 on Gaussian inputs."""
+    from scipy.stats import entropy as sp_entropy
+    b, hq, hk, n, d, r = 2, 4, 2, 90, 16, 11
+    Q, K = rnd(70, b, hq, n, d), rnd(71, b, hk, n, d)
+    c = np.arange(n - r, n) + 1
+    uni = oracle.row_entropy(Q, K, Config(r, 20, 3, scale_mode=SCALE_FIXED, fixed_scale=0.0))
+    np.testing.assert_allclose(uni, np.broadcast_to(np.log(c), uni.shape), rtol=1e-13)
+    hot = oracle.row_entropy(Q, K, Config(r, 20, 3, scale_mode=SCALE_FIXED, fixed_scale=400.0))
+    # (a huge gain leaves one key per row, or two if their logits nearly tie)
+    assert np.all(hot >= 0) and np.median(hot) < 1e-9 and hot.max() < math.log(2) + 1e-9
+    for cfg in (Config(r, 20, 3, scale_mode=SCALE_FIXED, fixed_scale=0.25),
+                Config(r, 20, 3), Config(r, 20, 3, lambda_floor=0.0)):
+        got = oracle.row_entropy(Q, K, cfg)
+        for bb in range(b):
+            for h in range(hq):
+                for ii in range(r):
+                    i = n - r + ii
+                    s = cfg.fixed_scale if cfg.scale_mode == SCALE_FIXED else \
+                        oracle.lam(i + 1, cfg.budget, d, cfg.lambda_floor)
+                    logits = s * (K[bb, h // (hq // hk), :i + 1] @ Q[bb, h, i])
+                    want = sp_entropy(sp_softmax(logits))
+                    assert got[bb, h, ii] == pytest.approx(want, rel=1e-10, abs=1e-12)
+                    assert 0.0 <= got[bb, h, ii] <= math.log(i + 1) + 1e-12
+    # expectations on Gaussian inputs (loose band, as in the test above, by the new function)
+    b, h, n, d, r, k = 1, 24, 4096, 64, 8, 512
+    Q, K = rnd(18, b, h, n, d), rnd(19, b, h, n, d)
+    std = oracle.row_entropy(Q, K, Config(r, k, 4, scale_mode=SCALE_FIXED,
+                                          fixed_scale=1 / math.sqrt(d))).mean()
+    ada = oracle.row_entropy(Q, K, Config(r, k, 4, lambda_floor=0.0)).mean()
+    assert abs(std - (math.log(n) - 0.5)) < 0.2 and abs(ada - math.log(k)) < 0.25
+
+
 def test_accumulated_score_bias_in_expectation():
     """iid Gaussian, full accumulation: E[S_j] = H_n - H_j (each row's entries
     are exchangeable), so the score decays with position."""
