@@ -157,6 +157,24 @@ int32_t aha_prefill_scores_lse(const aha_params *p, const void *q, const void *k
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Statistics of the observed rows (Sec. 4.2: the information entropy of an
+ * attention row, H_i = - sum_{j <= i} a_ij ln a_ij, whose expectation the
+ * adaptive scale is derived from), by the row-statistics pass alone:
+ *
+ *  lse      out, fp32 dense [batch, n_q_heads, window] or NULL: natural
+ *           logarithm of sum_{j <= i} exp(s_i * Q_i . K_j) of window row ii
+ *           (query position seq_len - window + ii), s_i the scale that
+ *           p->scale_mode gives the row: what aha_prefill_scores_lse takes.
+ *  entropy  out, fp32 dense [batch, n_q_heads, window] or NULL: H_i in nats of
+ *           the row softmax_{j <= i}(s_i * Q_i . K_j).
+ * At least one of the two must be given.  window == seq_len gives the curve
+ * over all positions.  v, value_prior and pool_kernel are not used.
+ */
+int32_t aha_prefill_row_stats(const aha_params *p, const void *q, const void *k,
+                              float *lse, float *entropy, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/*
  * Selection (Alg. 1: recent set, TopK, union).
  *
  *  scores  fp32 [batch, n_kv_heads, seq_len], non-negative and finite.

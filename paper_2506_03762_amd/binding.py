@@ -28,7 +28,8 @@ AHA_F32, AHA_BF16 = 0, 1
 AHA_SCALE_FIXED, AHA_SCALE_ADAPTIVE = 0, 1
 
 # entry points returning an int32 status first, then the two that return strings
-EXPORTS = ("aha_workspace_bytes", "aha_prefill_scores", "aha_prefill_scores_lse", "aha_select_topk",
+EXPORTS = ("aha_workspace_bytes", "aha_prefill_scores", "aha_prefill_scores_lse",
+           "aha_prefill_row_stats", "aha_select_topk",
            "aha_compact_kv", "aha_decode_step", "aha_decode_step_static", "aha_profile_events",
            "aha_last_error",
            "aha_version")
@@ -72,6 +73,7 @@ def load() -> ctypes.CDLL:
     lib.aha_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
     lib.aha_prefill_scores.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
     lib.aha_prefill_scores_lse.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.aha_prefill_row_stats.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
     lib.aha_select_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.aha_compact_kv.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     lib.aha_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
@@ -184,6 +186,16 @@ def aha_prefill_scores_lse(p: Params, q, k, v, lse, scores, workspace):
                                          _ptr(scores), _ptr(workspace),
                                          workspace.numel() if workspace is not None else 0,
                                          _stream()))
+
+
+def aha_prefill_row_stats(p: Params, q, k, lse, entropy, workspace):
+    """lse / entropy [b, Hq, window] (fp32, either may be None) <- natural-log normaliser and
+    entropy (nats) of the observed softmax rows."""
+    cp = p.c()
+    _check(load().aha_prefill_row_stats(ctypes.byref(cp), _ptr(q), _ptr(k), _ptr(lse),
+                                        _ptr(entropy), _ptr(workspace),
+                                        workspace.numel() if workspace is not None else 0,
+                                        _stream()))
 
 
 def aha_select_topk(p: Params, scores, idx, workspace=None):

@@ -170,6 +170,9 @@ static PrefillPlan plan_prefill(const aha_params *p) {
     pl.off_partial = off;
     if (p->dtype == AHA_BF16)
         off = align_up(off + sizeof(float) * (size_t)pl.Z * rows * pl.nchunks, 256);
+    pl.off_partial_mean = off;  // aha_prefill_row_stats: per-chunk mean scaled logit
+    if (p->dtype == AHA_BF16)
+        off = align_up(off + sizeof(float) * (size_t)pl.Z * rows * pl.nchunks, 256);
     pl.off_gamma = off;
     off = align_up(off + sizeof(float) * (size_t)pl.Z * n, 256);
     pl.off_gblockmax = off;  // per-range maxima of the value prior: per tile, or per key chunk
@@ -307,6 +310,31 @@ int32_t aha_prefill_scores_lse(const aha_params *p, const void *q, const void *k
                                const float *lse, float *scores, void *workspace,
                                size_t workspace_bytes, void *stream) {
     return prefill_scores_impl(p, q, k, v, lse, true, scores, workspace, workspace_bytes, stream);
+}
+
+int32_t aha_prefill_row_stats(const aha_params *p, const void *q, const void *k, float *lse,
+                              float *entropy, void *workspace, size_t workspace_bytes,
+                              void *stream) {
+    int32_t rc = check_prefill(p, false);
+    if (rc) return rc;
+    if ((rc = check_stride("q", p->q_stride, p->dtype, p->head_dim)) ||
+        (rc = check_stride("k", p->k_stride, p->dtype, p->head_dim)))
+        return rc;
+    if ((rc = check_ptr("q", q, 16)) || (rc = check_ptr("k", k, 16))) return rc;
+    if (!lse && !entropy) return fail(AHA_ERR_INVALID_ARG, "lse and entropy are both null");
+    if ((lse && (rc = check_ptr("lse", lse, 4))) || (entropy && (rc = check_ptr("entropy", entropy, 4))))
+        return rc;
+    const PrefillPlan pl = plan_prefill(p);
+    if ((rc = check_ws(workspace, workspace_bytes, pl.bytes))) return rc;
+    const int64_t score_wgs = (int64_t)pl.Z * ((pl.n_qtiles + 1) / 2) * pl.nchunks;
+    if (score_wgs > (int64_t)1 << 30)
+        return fail(AHA_ERR_UNSUPPORTED, "problem exceeds the launch grid limits");
+    const ScoreGeom g = make_geom(p, q, k, nullptr);
+    if (p->dtype == AHA_BF16)
+        return hip_result(launch_row_stats_bf16(g, pl, workspace, lse, entropy, (hipStream_t)stream),
+                          "bf16 row-statistics kernels");
+    return hip_result(launch_row_stats_f32(g, pl, workspace, lse, entropy, (hipStream_t)stream),
+                      "fp32 row-statistics kernel");
 }
 
 int32_t aha_select_topk(const aha_params *p, const float *scores, int32_t *idx, void *workspace,

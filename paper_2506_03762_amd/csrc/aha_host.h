@@ -54,7 +54,7 @@ struct PrefillPlan {
     int p2_keys;     // keys per pass-2 workgroup (a multiple of kP2Keys)
     int n_vtiles;    // value-prior tiles per problem (separate launch)
     bool can_fold;   // windowed bf16 scores: pass 1 can form the value prior per key chunk
-    size_t off_rowL, off_partial, off_gamma, off_gblockmax;
+    size_t off_rowL, off_partial, off_partial_mean, off_gamma, off_gblockmax;
     size_t bytes;
 };
 
@@ -79,6 +79,12 @@ hipError_t launch_score_f32(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
 hipError_t launch_score_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
                              float *scores, hipStream_t st, hipEvent_t mid, bool have_lse,
                              bool fold_prior);
+// Row statistics of the observed rows out (pass 1 only): natural-log normaliser and entropy,
+// dense [batch, Hq, window]; either pointer may be null.
+hipError_t launch_row_stats_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *lse,
+                                 float *entropy, hipStream_t st);
+hipError_t launch_row_stats_f32(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *lse,
+                                float *entropy, hipStream_t st);
 // topk.hip
 // `pool` > 1: the candidates are ranked by the scores pooled over `pool` tokens, which are
 // written to `pooled` ([Z][n] floats) first.

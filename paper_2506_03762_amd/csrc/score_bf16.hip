@@ -168,9 +168,11 @@ __device__ __forceinline__ int acc_key(int kb, int mb, int v, int lane) {
 // Online max / sum-of-exp2 of one 64 x 32 block for this lane's query column.
 // The scale is non-negative, so the maximum of the scaled logits is the scale
 // times the maximum raw dot.
-template <bool MASK>
+// With ENT the first moment u = sum of exp2(t - m) * (t - m) is kept beside the sum: the
+// row's entropy is ln 2 * (log2 s - u / s) (Sec. 4.2, entropy of a softmax row).
+template <bool MASK, bool ENT>
 __device__ __forceinline__ void stats_update(const f32x16 (&acc)[kMB], float lam, int pos, int kb,
-                                             int lane, float &m, float &s) {
+                                             int lane, float &m, float &s, float &u) {
     if (MASK) asm volatile("" ::: "memory");
     float amax = -INFINITY;
 #pragma unroll
@@ -186,16 +188,24 @@ __device__ __forceinline__ void stats_update(const f32x16 (&acc)[kMB], float lam
     const float mref = mn == -INFINITY ? 0.f : mn;
     // four partial sums: independent chains, so that the exponentials' result latency is
     // covered by other work instead of wait states
-    float sum[4] = {0.f, 0.f, 0.f, 0.f};
+    float sum[4] = {0.f, 0.f, 0.f, 0.f}, mom[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int mb = 0; mb < kMB; ++mb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            float e = fast_exp2(fmaf(acc[mb][v], lam, -mref));
+            const float x = fmaf(acc[mb][v], lam, -mref);
+            float e = fast_exp2(x);
             if (MASK && acc_key(kb, mb, v, lane) > pos) e = 0.f;
             sum[v & 3] += e;
+            // (e = 0 for masked or far-away keys: 0 * x, x finite, adds nothing)
+            if (ENT) mom[v & 3] = fmaf(e, x, mom[v & 3]);
         }
-    s = s * fast_exp2(m - mref) + ((sum[0] + sum[1]) + (sum[2] + sum[3]));
+    const float f = fast_exp2(m - mref);  // 0 while the row has seen no key
+    if (ENT) {
+        const float dm = m == -INFINITY ? 0.f : m - mref;
+        u = (u + dm * s) * f + ((mom[0] + mom[1]) + (mom[2] + mom[3]));
+    }
+    s = s * f + ((sum[0] + sum[1]) + (sum[2] + sum[3]));
     m = mn;
 }
 
@@ -319,17 +329,21 @@ __device__ __forceinline__ float value_prior_of_range(const ScoreGeom &g, int b,
 // launch costs 4 - 5 us, a third of that kernel's time at 8 heads x 32K).  (Letting half of
 // the workgroups form the prior first, so that value streaming and arithmetic would meet on
 // the chip, measured the same.)
-template <int D, int NB>
+// ENT: the chunk's mean scaled logit under its own probabilities, E_c[t] = m + u / s, is
+// written to `partial_mean` beside the chunk's log2-sum-exp2; entropy_merge_kernel turns the
+// chunks of a row into its entropy.
+template <int D, int NB, bool ENT>
 __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles, int nparts,
                                                             int total_wgs, float *partial,
-                                                            float *gamma, float *gblockmax) {
+                                                            float *partial_mean, float *gamma,
+                                                            float *gblockmax) {
     using S = TileSmem<D, NB>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __bf16 *sQ = (__bf16 *)smem;
     float *sLam = (float *)(smem + S::q_bytes);
     int *sPos = (int *)(sLam + S::ROWS);
     int *sBlk = sPos + 2 * S::ROWS;
-    float2 *sRed = (float2 *)smem;  // reuses the query tile after the main loop
+    float4 *sRed = (float4 *)smem;  // reuses the query tile after the main loop
 
     // logical workgroup index -> (part, tile pair, problem)
     const int wg = logical_wg_index(total_wgs, n_qtiles > 1);
@@ -345,11 +359,15 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
         const Segment sg = pair_segment(rm, S::ROWS, n_qtiles, pair, part, nparts, seg);
         if (sg.qt < 0) break;
         const int qt = sg.qt, rho0 = qt * S::ROWS;
-        float *my_partial = partial + ((int64_t)(z * n_qtiles + qt) * nparts + part) * S::ROWS;
+        const int64_t my_off = ((int64_t)(z * n_qtiles + qt) * nparts + part) * S::ROWS;
+        float *my_partial = partial + my_off;
         const int key_begin = sg.kbeg, key_end = sg.kend;
         if (key_begin >= key_end) {
             // none of this part's steps fall on this tile: leave neutral statistics
-            if (tid < S::ROWS) my_partial[tid] = -INFINITY;
+            if (tid < S::ROWS) {
+                my_partial[tid] = -INFINITY;
+                if (ENT) partial_mean[my_off + tid] = 0.f;
+            }
             continue;
         }
         if (seg) __syncthreads();  // the previous tile (and its reduction buffer) is done with
@@ -384,7 +402,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
         }
         __syncthreads();
 
-        float lam[NB], m[NB], s[NB];
+        float lam[NB], m[NB], s[NB], u[ENT ? NB : 1];
         int pos[NB], bmax[NB], bmin[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
@@ -394,6 +412,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
             bmin[nb] = uniform(sBlk[NB + nb]);
             m[nb] = -INFINITY;
             s[nb] = 0.f;
+            u[ENT ? nb : 0] = 0.f;
         }
 
         const int tile_min = rm.min_pos(rho0, rho0 + S::ROWS);
@@ -405,7 +424,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
                 for (int nb = 0; nb < NB; ++nb) {
                     f32x16 acc[kMB];
                     mma_block<D, NB>(a, sQ, nb, lane, acc);
-                    stats_update<false>(acc, lam[nb], 0, kb, lane, m[nb], s[nb]);
+                    stats_update<false, ENT>(acc, lam[nb], 0, kb, lane, m[nb], s[nb], u[ENT ? nb : 0]);
                 }
                 return;
             }
@@ -415,9 +434,9 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
                 f32x16 acc[kMB];
                 mma_block<D, NB>(a, sQ, nb, lane, acc);
                 if (kb + kWaveKeys - 1 > bmin[nb])
-                    stats_update<true>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb]);
+                    stats_update<true, ENT>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb], u[ENT ? nb : 0]);
                 else
-                    stats_update<false>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb]);
+                    stats_update<false, ENT>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb], u[ENT ? nb : 0]);
             }
         };
         // The prefetch is issued unconditionally (past the range it re-reads clamped rows
@@ -432,20 +451,31 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
             step(a1, kb_of(i + 1));
         }
 
-        // fold the two half-waves (same query column, different key rows)
+        // fold the two half-waves (same query column, different key rows); a statistic
+        // (m, s, u) re-referenced to a maximum M >= m is (M, s f, (u + (m - M) s) f), f = 2^(m - M)
+        auto reref = [](float m_, float mref, float &s_, float &u_) {
+            const float f = fast_exp2(m_ - mref);
+            if (ENT) u_ = (u_ + (m_ == -INFINITY ? 0.f : m_ - mref) * s_) * f;
+            s_ *= f;
+        };
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            const float m2 = __shfl_xor(m[nb], 32), s2 = __shfl_xor(s[nb], 32);
+            float m2 = __shfl_xor(m[nb], 32), s2 = __shfl_xor(s[nb], 32);
+            float u1 = u[ENT ? nb : 0], u2 = ENT ? __shfl_xor(u1, 32) : 0.f;
             const float mn = fmaxf(m[nb], m2);
             const float mref = mn == -INFINITY ? 0.f : mn;
-            s[nb] = s[nb] * fast_exp2(m[nb] - mref) + s2 * fast_exp2(m2 - mref);
+            reref(m[nb], mref, s[nb], u1);
+            reref(m2, mref, s2, u2);
+            s[nb] += s2;
+            u[ENT ? nb : 0] = u1 + u2;
             m[nb] = mn;
         }
         __syncthreads();  // everyone is done reading the query tile
         if (lane < 32) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
-                sRed[wave * S::ROWS + nb * 32 + lane] = make_float2(m[nb], s[nb]);
+                sRed[wave * S::ROWS + nb * 32 + lane] =
+                    make_float4(m[nb], s[nb], u[ENT ? nb : 0], 0.f);
         }
         __syncthreads();
         if (tid < S::ROWS) {
@@ -453,13 +483,17 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
 #pragma unroll
             for (int w = 0; w < 4; ++w) M = fmaxf(M, sRed[w * S::ROWS + tid].x);
             const float mref = M == -INFINITY ? 0.f : M;
-            float sum = 0.f;
+            float sum = 0.f, mom = 0.f;
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                const float2 e = sRed[w * S::ROWS + tid];
-                sum += e.y * fast_exp2(e.x - mref);
+                const float4 e = sRed[w * S::ROWS + tid];
+                float sw = e.y, uw = e.z;
+                reref(e.x, mref, sw, uw);
+                sum += sw;
+                mom += uw;
             }
             my_partial[tid] = M + log2f(sum);  // -inf for a row that saw no key
+            if (ENT) partial_mean[my_off + tid] = sum > 0.f ? mref + mom / sum : 0.f;
         }
         if (gamma) {
             __syncthreads();  // the reduction buffer is done with
@@ -786,6 +820,36 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     }
 }
 
+// Row statistics out (Sec. 4.2): from pass 1's per-chunk log2-sum-exp2 L_c and mean scaled
+// logit E_c, the row's natural-log normaliser lse = ln 2 * L, L = log2 sum_c 2^L_c, and its
+// entropy H = ln 2 * (L - sum_c 2^(L_c - L) E_c).  One thread per observed row.
+__global__ __launch_bounds__(256) void row_stats_merge_kernel(ScoreGeom g, int rows_tile,
+                                                              int n_qtiles, int nparts,
+                                                              const float *partial,
+                                                              const float *partial_mean,
+                                                              float *lse, float *entropy) {
+    const int z = blockIdx.y, rho = blockIdx.x * 256 + threadIdx.x;
+    if (rho >= g.R) return;
+    const int b = z / g.Hkv, h = z % g.Hkv;
+    const int qt = rho / rows_tile, row = rho % rows_tile;
+    const float *pl = partial + ((int64_t)(z * n_qtiles + qt) * nparts) * rows_tile + row;
+    const float *pm = partial_mean + ((int64_t)(z * n_qtiles + qt) * nparts) * rows_tile + row;
+    float M = -INFINITY;
+    for (int c = 0; c < nparts; ++c) M = fmaxf(M, pl[(int64_t)c * rows_tile]);
+    float sum = 0.f, mean = 0.f;
+    for (int c = 0; c < nparts; ++c) {
+        const float wgt = exp2f(pl[(int64_t)c * rows_tile] - M);  // 0 for a chunk without keys
+        sum += wgt;
+        mean = fmaf(wgt, pm[(int64_t)c * rows_tile], mean);
+    }
+    const float L = M + log2f(sum);
+    const int gi = rho / g.r, ii = rho - gi * g.r;
+    const int64_t o = ((int64_t)b * g.Hq + h * g.G + gi) * g.r + ii;
+    const float kLn2 = 0.69314718055994531f;
+    if (lse) lse[o] = L * kLn2;
+    if (entropy) entropy[o] = fmaxf(0.f, (L - mean / sum) * kLn2);
+}
+
 // ---------------------------------------------------------------- launch --
 template <int D, int NB>
 static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
@@ -798,7 +862,8 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     float *gbm = (float *)(w + pl.off_gblockmax);
     static DeviceOnce once;
     const hipError_t ea = device_once(once, [] {
-        const void *kernels[3] = {(const void *)bf16_pass1_kernel<D, NB>,
+        const void *kernels[4] = {(const void *)bf16_pass1_kernel<D, NB, false>,
+                                  (const void *)bf16_pass1_kernel<D, NB, true>,
                                   (const void *)bf16_pass2_kernel<D, NB, true>,
                                   (const void *)bf16_pass2_kernel<D, NB, false>};
         for (const void *kf : kernels) {
@@ -815,8 +880,8 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     const int64_t wgs2 = (int64_t)((g.n + pl.p2_keys - 1) / pl.p2_keys) * pl.Z;
     // with the caller's row normalisers already in place (one "chunk" per row) pass 1 is skipped
     if (!have_lse)
-        hipLaunchKernelGGL((bf16_pass1_kernel<D, NB>), xcd_grid(wgs1), dim3(256), S::bytes, st, g,
-                           pl.n_qtiles, pl.nchunks, (int)wgs1, partial,
+        hipLaunchKernelGGL((bf16_pass1_kernel<D, NB, false>), xcd_grid(wgs1), dim3(256), S::bytes,
+                           st, g, pl.n_qtiles, pl.nchunks, (int)wgs1, partial, (float *)nullptr,
                            fold_prior ? gamma : nullptr, gbm);
     const int stat_chunks = have_lse ? 1 : pl.nchunks;
     // the prior's per-range maxima: one per key chunk when pass 1 formed it, else per tile
@@ -842,6 +907,44 @@ static hipError_t launch_d(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
         case 4: return launch_t<D, 4>(g, pl, ws, scores, st, mid, have_lse, fold_prior);
         default: return launch_t<D, 8>(g, pl, ws, scores, st, mid, have_lse, fold_prior);
     }
+}
+
+template <int D, int NB>
+static hipError_t launch_stats_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *lse,
+                                 float *entropy, hipStream_t st) {
+    using S = TileSmem<D, NB>;
+    char *w = (char *)ws;
+    float *partial = (float *)(w + pl.off_partial);
+    float *partial_mean = (float *)(w + pl.off_partial_mean);
+    static DeviceOnce once;
+    const hipError_t ea = device_once(once, [] {
+        return hipFuncSetAttribute((const void *)bf16_pass1_kernel<D, NB, true>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::bytes);
+    });
+    if (ea != hipSuccess) return ea;
+    const int64_t wgs1 = (int64_t)pl.nchunks * ((pl.n_qtiles + 1) / 2) * pl.Z;
+    hipLaunchKernelGGL((bf16_pass1_kernel<D, NB, true>), xcd_grid(wgs1), dim3(256), S::bytes, st,
+                       g, pl.n_qtiles, pl.nchunks, (int)wgs1, partial, partial_mean,
+                       (float *)nullptr, (float *)nullptr);
+    const hipError_t e1 = hipGetLastError();
+    if (e1 != hipSuccess) return e1;
+    hipLaunchKernelGGL(row_stats_merge_kernel, dim3((g.R + 255) / 256, pl.Z), dim3(256), 0, st, g,
+                       pl.qtile, pl.n_qtiles, pl.nchunks, partial, partial_mean, lse, entropy);
+    return hipGetLastError();
+}
+
+hipError_t launch_row_stats_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *lse,
+                                 float *entropy, hipStream_t st) {
+#define AHA_STATS(DD)                                                         \
+    switch (pl.NB) {                                                          \
+        case 1: return launch_stats_t<DD, 1>(g, pl, ws, lse, entropy, st);    \
+        case 2: return launch_stats_t<DD, 2>(g, pl, ws, lse, entropy, st);    \
+        case 4: return launch_stats_t<DD, 4>(g, pl, ws, lse, entropy, st);    \
+        default: return launch_stats_t<DD, 8>(g, pl, ws, lse, entropy, st);   \
+    }
+    if (g.d == 64) { AHA_STATS(64) }
+    AHA_STATS(128)
+#undef AHA_STATS
 }
 
 hipError_t launch_score_bf16(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,

@@ -11,8 +11,21 @@
 
 namespace aha {
 
+// A running statistic (m, s, u) of scaled logits t: m = max t, s = sum exp2(t - m),
+// u = sum exp2(t - m) (t - m).  The row's entropy is ln 2 * (log2 s - u / s) (Sec. 4.2).
+// Re-referenced to a maximum M >= m it is (M, s f, (u + (m - M) s) f) with f = 2^(m - M).
+__device__ __forceinline__ void reref_stat(float m, float M, float &s, float &u) {
+    if (m == -INFINITY) { s = 0.f; u = 0.f; return; }
+    const float f = exp2f(m - M);
+    u = (u + (m - M) * s) * f;
+    s *= f;
+}
+
+// `lse_out` / `ent_out` (either may be null): natural-log normaliser and entropy of every
+// observed row, dense [batch, Hq, window].
 template <int D>
-__global__ __launch_bounds__(256) void f32_pass1_kernel(ScoreGeom g, float *rowL) {
+__global__ __launch_bounds__(256) void f32_pass1_kernel(ScoreGeom g, float *rowL, float *lse_out,
+                                                        float *ent_out) {
     const int z = blockIdx.y, rho = blockIdx.x, tid = threadIdx.x;
     const int b = z / g.Hkv, h = z % g.Hkv;
     const RowMap rm{g.n, g.r, g.R};
@@ -22,13 +35,13 @@ __global__ __launch_bounds__(256) void f32_pass1_kernel(ScoreGeom g, float *rowL
     const float *kbase = (const float *)g.k + b * g.ks[0] + h * g.ks[1];
 
     __shared__ float s_q[D];
-    __shared__ float s_m[4], s_s[4];
+    __shared__ float s_m[4], s_s[4], s_u[4];
     if (tid < D) s_q[tid] = qrow[tid];
     __syncthreads();
     const float lam = row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor, i + 1,
                                      g.budget, g.d);
 
-    float m = -INFINITY, s = 0.f;
+    float m = -INFINITY, s = 0.f, u = 0.f;
     for (int j = tid; j <= i; j += 256) {
         const float4 *kr = (const float4 *)(kbase + (int64_t)j * g.ks[2]);
         float w = 0.f;
@@ -42,20 +55,33 @@ __global__ __launch_bounds__(256) void f32_pass1_kernel(ScoreGeom g, float *rowL
         }
         const float t = w * lam;
         const float mn = fmaxf(m, t);
-        s = s * exp2f(m - mn) + exp2f(t - mn);
+        reref_stat(m, mn, s, u);
+        const float e = exp2f(t - mn);
+        s += e;
+        u = fmaf(e, t - mn, u);
         m = mn;
     }
-    // combine the per-thread (m, s) pairs
-    float wm = wave_max(m);
-    float ws = wave_sum(m == -INFINITY ? 0.f : s * exp2f(m - wm));
-    if ((tid & 63) == 0) { s_m[tid >> 6] = wm; s_s[tid >> 6] = ws; }
+    // combine the per-thread statistics
+    const float wm = wave_max(m);
+    reref_stat(m, wm, s, u);
+    const float ws = wave_sum(s), wu = wave_sum(u);
+    if ((tid & 63) == 0) { s_m[tid >> 6] = wm; s_s[tid >> 6] = ws; s_u[tid >> 6] = wu; }
     __syncthreads();
     if (tid == 0) {
-        float M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
-        float S = 0.f;
-        for (int t = 0; t < 4; ++t)
-            if (s_m[t] != -INFINITY) S += s_s[t] * exp2f(s_m[t] - M);
-        rowL[(int64_t)z * g.R + rho] = M + log2f(S);
+        const float M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+        float S = 0.f, U = 0.f;
+        for (int t = 0; t < 4; ++t) {
+            float st = s_s[t], ut = s_u[t];
+            reref_stat(s_m[t], M, st, ut);
+            S += st;
+            U += ut;
+        }
+        const float L = M + log2f(S);
+        rowL[(int64_t)z * g.R + rho] = L;
+        const int64_t o = ((int64_t)b * g.Hq + hq) * g.r + (rho % g.r);
+        const float kLn2 = 0.69314718055994531f;
+        if (lse_out) lse_out[o] = L * kLn2;
+        if (ent_out) ent_out[o] = fmaxf(0.f, (log2f(S) - U / S) * kLn2);
     }
 }
 
@@ -139,16 +165,31 @@ hipError_t launch_score_f32(const ScoreGeom &g, const PrefillPlan &pl, void *ws,
     const float *gbm = (const float *)(w + pl.off_gblockmax);
     dim3 g1(g.R, pl.Z), g2((g.n + 255) / 256, pl.Z);
     if (g.d == 64) {
-        if (!have_lse) hipLaunchKernelGGL(f32_pass1_kernel<64>, g1, dim3(256), 0, st, g, rowL);
+        if (!have_lse)
+            hipLaunchKernelGGL(f32_pass1_kernel<64>, g1, dim3(256), 0, st, g, rowL, (float *)nullptr,
+                               (float *)nullptr);
         if (mid) (void)hipEventRecord(mid, st);
         hipLaunchKernelGGL(f32_pass2_kernel<64>, g2, dim3(256), 0, st, g, rowL, gamma, gbm,
                            pl.n_vtiles, scores);
     } else {
-        if (!have_lse) hipLaunchKernelGGL(f32_pass1_kernel<128>, g1, dim3(256), 0, st, g, rowL);
+        if (!have_lse)
+            hipLaunchKernelGGL(f32_pass1_kernel<128>, g1, dim3(256), 0, st, g, rowL, (float *)nullptr,
+                               (float *)nullptr);
         if (mid) (void)hipEventRecord(mid, st);
         hipLaunchKernelGGL(f32_pass2_kernel<128>, g2, dim3(256), 0, st, g, rowL, gamma, gbm,
                            pl.n_vtiles, scores);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_row_stats_f32(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *lse,
+                                float *entropy, hipStream_t st) {
+    float *rowL = (float *)((char *)ws + pl.off_rowL);
+    dim3 g1(g.R, pl.Z);
+    if (g.d == 64)
+        hipLaunchKernelGGL(f32_pass1_kernel<64>, g1, dim3(256), 0, st, g, rowL, lse, entropy);
+    else
+        hipLaunchKernelGGL(f32_pass1_kernel<128>, g1, dim3(256), 0, st, g, rowL, lse, entropy);
     return hipGetLastError();
 }
 

@@ -124,6 +124,23 @@ def test_prefill_with_given_normalisers_validates(lib):
                                       big, None) == B.AHA_ERR_INVALID_ARG
 
 
+def test_row_stats_validate(lib):
+    """aha_prefill_row_stats: needs q, k and at least one output; the value strides are not looked at."""
+    p = good(v_stride=(0, 0, 0))
+    cp = p.c()
+    big = 1 << 40
+    call = lambda q=DUMMY, lse=DUMMY, ent=DUMMY, ws=DUMMY, nbytes=big: lib.aha_prefill_row_stats(
+        ctypes.byref(cp), q, DUMMY, lse, ent, ws, nbytes, None)
+    assert call(lse=None, ent=None) == B.AHA_ERR_INVALID_ARG
+    assert call(q=None) == B.AHA_ERR_INVALID_ARG
+    assert call(ent=ctypes.c_void_p(0x1002)) == B.AHA_ERR_INVALID_ARG
+    assert call(ws=None) == B.AHA_ERR_WORKSPACE
+    assert call(nbytes=B.workspace_bytes(good()) - 1) == B.AHA_ERR_WORKSPACE
+    bad = good(q_stride=(0, 0, 64)).c()
+    assert lib.aha_prefill_row_stats(ctypes.byref(bad), DUMMY, DUMMY, DUMMY, DUMMY, DUMMY, big,
+                                     None) == B.AHA_ERR_INVALID_ARG
+
+
 def test_other_entry_points_validate(lib):
     p = good()
     cp = p.c()
