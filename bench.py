@@ -57,6 +57,8 @@ def main():
                     help="skip the oracle timing (used under rocprofv3)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the C4 decode and C2 full-accumulation side measurements")
+    ap.add_argument("--only", choices=["decode_c4", "full_c2", "c5_layer"], default=None,
+                    help="run one side measurement alone and print it (for profiling that kernel)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB elementwise kernel (calibrates the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters against a known size)")
@@ -74,6 +76,20 @@ def main():
     torch.cuda.set_device(0)
     B.load()
     K_STEPS, W_STEPS = args.steps, args.warmup
+
+    if args.copy_probe:
+        # an elementwise kernel that reads 256 MiB and writes 256 MiB
+        src = torch.ones(64 << 20, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+    if args.only:
+        fn = {"decode_c4": lambda: bench_decode_c4(torch, B, synth, H, K_STEPS),
+              "full_c2": lambda: bench_full_c2(torch, B, synth, H, max(5, K_STEPS // 5)),
+              "c5_layer": lambda: bench_c5_layer(torch, B, synth, H, max(5, K_STEPS // 5))}[args.only]
+        print(json.dumps({"only": args.only, args.only: fn()}))
+        return
 
     # ------------------------------------------------------------ workload --
     w = synth.C3
@@ -100,13 +116,6 @@ def main():
         e.record()
         return e
 
-    if args.copy_probe:
-        # an elementwise kernel that reads 256 MiB and writes 256 MiB
-        src = torch.ones(64 << 20, dtype=torch.int32, device="cuda")
-        dst = torch.empty_like(src)
-        torch.add(src, 1, out=dst)
-        torch.cuda.synchronize()
-        del src, dst
     for _ in range(W_STEPS):
         step()
     torch.cuda.synchronize()
@@ -252,17 +261,19 @@ def bench_decode_c4(torch, B, synth, H, steps):
     alg = b * hk * (2 * (w.budget + 1) * d * 2 + 8 * (w.budget + 1) + 2 * d * 2) + 2 * b * hq * d * 2
 
     def run(rotate):
-        # the paper-shaped run: 256 consecutive steps; mean over steps 32..255
-        evs = []
+        # the paper-shaped run: 256 consecutive steps, enqueued back to back as a generation
+        # loop does; two events bracket steps 32..255 and the step time is their mean (an
+        # event pair around every single step adds 2-3 us of dispatch gap to each)
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
         for t in range(nsteps):
             c = caches[t % ncopies] if rotate else caches[0]
-            e0 = torch.cuda.Event(enable_timing=True); e0.record()
+            if t == 32:
+                e0.record()
             B.aha_decode_step(p, qs[t], ks[t], vs[t], c.k, c.v, c.scores, c.pos, c.free_slot,
                               n + 1 + (t // ncopies if rotate else t), out, ws)
-            e1 = torch.cuda.Event(enable_timing=True); e1.record()
-            evs.append((e0, e1))
+        e1.record()
         torch.cuda.synchronize()
-        return avg_ms(evs[32:]) * 1e3
+        return e0.elapsed_time(e1) * 1e3 / (nsteps - 32)
 
     def reset():
         for c in caches:

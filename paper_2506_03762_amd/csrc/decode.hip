@@ -28,6 +28,33 @@ __device__ __forceinline__ void unpack(const u32x4 &w, float (&f)[16 / ESIZE]) {
     }
 }
 
+// Dot product of one 16-byte chunk of a key row with the same chunk of a query.  bf16: the
+// packed pairs go through v_dot2c_f32_bf16 (exact products, fp32 accumulation) without
+// being unpacked; fp32: four fused multiply-adds.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+template <int ESIZE>
+__device__ __forceinline__ float chunk_dot(const u32x4 &kw, const u32x4 &qw) {
+    if constexpr (ESIZE == 2) {
+        float a = 0.f, b = 0.f;  // two chains
+        auto pair = [](uint32_t w) {
+            bf16x2 v;
+            __builtin_memcpy(&v, &w, 4);
+            return v;
+        };
+#pragma unroll
+        for (int t = 0; t < 4; t += 2) {
+            a = __builtin_amdgcn_fdot2_f32_bf16(pair(kw[t]), pair(qw[t]), a, false);
+            b = __builtin_amdgcn_fdot2_f32_bf16(pair(kw[t + 1]), pair(qw[t + 1]), b, false);
+        }
+        return a + b;
+    } else {
+        float w = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) w = fmaf(__uint_as_float(kw[t]), __uint_as_float(qw[t]), w);
+        return w;
+    }
+}
+
 // Smallest (score bits << 32 | ~position) key of the wave, in two 32-bit reductions: the
 // smallest score, then the smallest ~position among the lanes that hold it.
 __device__ __forceinline__ unsigned long long wave_min_key(unsigned long long key) {
@@ -71,6 +98,11 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     for (int gi = 0; gi < G; ++gi)
         qw[gi] = *(const u32x4 *)((const char *)g.q + ((int64_t)(b * g.Hq + h * G + gi)) * ROWB + sub * 16);
 
+    // the running score and position of this thread's first slot (the later phase that updates
+    // them would otherwise wait a full round trip to memory in the middle of the kernel)
+    const float f_first = fcz[min(tid, live - 1)];
+    const int p_first = posz[min(tid, live - 1)];
+
     // ---- raw dots over the live slots (the new key stands in for slot fs) ----
     // cache rows per thread requested before the first is used (fewer for wide groups,
     // whose queries and outputs fill the 128 registers a thread of this workgroup has)
@@ -79,9 +111,6 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
 #pragma unroll
     for (int u = 0; u < PF; ++u)
         kpf[u] = *(const u32x4 *)(kcz + (int64_t)min(rg + u * RP, live - 1) * ROWB + sub * 16);
-    float qr[G][CH];
-#pragma unroll
-    for (int gi = 0; gi < G; ++gi) unpack<ESIZE>(qw[gi], qr[gi]);
     float mloc[G];
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) mloc[gi] = -INFINITY;
@@ -90,13 +119,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
             kw = knw;
             *(u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16) = kw;
         }
-        float kf[CH];
-        unpack<ESIZE>(kw, kf);
 #pragma unroll
         for (int gi = 0; gi < G; ++gi) {
-            float w = 0.f;
-#pragma unroll
-            for (int c = 0; c < CH; ++c) w = fmaf(qr[gi][c], kf[c], w);
+            float w = chunk_dot<ESIZE>(kw, qw[gi]);
             w = reduce_lanes<1, LPR>(w, OpSum{});  // over the lanes of the row
             if (sub == 0) s_w[gi * live + s] = w;
             mloc[gi] = fmaxf(mloc[gi], w);
@@ -106,7 +131,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     for (int u = 0; u < PF; ++u)
         if (rg + u * RP < live) dots(rg + u * RP, kpf[u]);
     // the rest in batches of PF rows per thread, requested together (written out by hand:
-    // a loop with lane exchanges in its body is not unrolled by the compiler)
+    // a loop with lane exchanges in its body is not unrolled by the compiler).  (A rolling
+    // window - every used row's registers given at once to the row PF sweeps further on -
+    // measured 10 % slower than whole batches.)
     for (int sb = rg + PF * RP; sb < live; sb += PF * RP) {
 #pragma unroll
         for (int u = 0; u < PF; ++u)
@@ -115,10 +142,13 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
         for (int u = 0; u < PF; ++u)
             if (sb + u * RP < live) dots(sb + u * RP, kpf[u]);
     }
-    // the first value rows travel while the softmax statistics are formed
-    u32x4 vpf[PF];
+    // the first value rows travel while the softmax statistics are formed (requesting more
+    // of them here, or already behind the last batch of key rows, measured 6 % slower: the
+    // key and value streams of the 256 workgroups then mix in memory)
+    constexpr int VPF = PF;
+    u32x4 vpf[VPF];
 #pragma unroll
-    for (int u = 0; u < PF; ++u)
+    for (int u = 0; u < VPF; ++u)
         vpf[u] = *(const u32x4 *)(vcz + (int64_t)min(rg + u * RP, live - 1) * ROWB + sub * 16);
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) {
@@ -179,10 +209,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
             s_p[gi * live + s] = exp2f(d * c_out) / zo[gi];
             add += exp2f(d * c_sc) / zs[gi];
         }
-        const float f = (s == fs ? 0.f : fcz[s]) + add;
+        const float f = (s == fs ? 0.f : (s == tid ? f_first : fcz[s])) + add;
         fcz[s] = f;
         int ps;
-        if (s == fs) { ps = g.logical_pos - 1; posz[s] = ps; } else { ps = posz[s]; }
+        if (s == fs) { ps = g.logical_pos - 1; posz[s] = ps; } else { ps = s == tid ? p_first : posz[s]; }
         if (ps < g.logical_pos - g.recent) {
             const unsigned long long key =
                 ((unsigned long long)__float_as_uint(f) << 32) | (uint32_t)(~ps);
@@ -218,10 +248,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
         }
     };
 #pragma unroll
-    for (int u = 0; u < PF; ++u)
+    for (int u = 0; u < VPF; ++u)
         if (rg + u * RP < live) weigh(rg + u * RP, vpf[u]);
 #pragma unroll 8
-    for (int s = rg + PF * RP; s < live; s += RP)
+    for (int s = rg + VPF * RP; s < live; s += RP)
         weigh(s, *(const u32x4 *)(vcz + (int64_t)s * ROWB + sub * 16));
     float *s_o = s_w;  // [waves][G][D]
 #pragma unroll
@@ -292,10 +322,6 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
         kpf[u] = *(const u32x4 *)(kcz + (int64_t)sc * ROWB + sub * 16);
         vpf[u] = *(const u32x4 *)(vcz + (int64_t)sc * ROWB + sub * 16);
     }
-    float qr[G][CH];
-#pragma unroll
-    for (int gi = 0; gi < G; ++gi) unpack<ESIZE>(qw[gi], qr[gi]);
-
     float mloc[G];
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) mloc[gi] = -INFINITY;
@@ -304,13 +330,9 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
             kw = knw;
             *(u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16) = kw;
         }
-        float kf[CH];
-        unpack<ESIZE>(kw, kf);
 #pragma unroll
         for (int gi = 0; gi < G; ++gi) {
-            float w = 0.f;
-#pragma unroll
-            for (int c = 0; c < CH; ++c) w = fmaf(qr[gi][c], kf[c], w);
+            float w = chunk_dot<ESIZE>(kw, qw[gi]);
             w = reduce_lanes<1, LPR>(w, OpSum{});  // over the lanes of the row
             if (sub == 0) {
                 s_p[gi * sps + s - s0] = w;
