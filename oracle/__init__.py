@@ -75,6 +75,8 @@ class Config:
     lambda_floor: float = -1.0  # <0: 1/sqrt(d); 0: literal closed form
     value_prior: bool = True
     pool: int = 7               # odd average-pool width over tokens
+    sink: int = 0               # first tokens that are always retained (selection and decode)
+    decode_value_prior: bool = False   # generation: refine the added probabilities by the value prior
 
 
 def lam(c: int, k: int, d: int, floor: float = -1.0) -> float:
@@ -178,6 +180,20 @@ def select_topk(scores, budget: int, recent: int):
     return idx.reshape(lead + (budget,))
 
 
+def select_topk_sink(scores, budget: int, recent: int, sink: int):
+    """Ascending retained indices [..., budget]: the first `sink` tokens, the `recent` last ones
+    and the budget - sink - recent highest scores in between."""
+    scores = _f64(scores)
+    n = scores.shape[-1]
+    assert sink >= 0 and recent >= 0 and sink + recent <= budget <= n
+    lead = scores.shape[:-1]
+    problems = int(np.prod(lead)) if lead else 1
+    idx = np.empty((problems, budget), dtype=np.int32)
+    _load().aha_oracle_select_topk_sink(_p(scores), _I64(problems), _I64(n), _I64(budget),
+                                        _I64(recent), _I64(sink), _p(idx, ctypes.c_int32))
+    return idx.reshape(lead + (budget,))
+
+
 def pool_scores(scores, pool: int):
     """Average-pooled scores [..., n] (edge-truncated mean over `pool` tokens)."""
     scores = _f64(scores)
@@ -190,11 +206,13 @@ def pool_scores(scores, pool: int):
     return out.reshape(scores.shape)
 
 
-def select_topk_pooled(scores, budget: int, recent: int, score_pool: int):
-    """Selection that ranks the candidates by their pooled scores (score_pool = 1: select_topk)."""
-    if score_pool <= 1:
-        return select_topk(scores, budget, recent)
-    return select_topk(pool_scores(scores, score_pool), budget, recent)
+def select_topk_pooled(scores, budget: int, recent: int, score_pool: int, sink: int = 0):
+    """Selection that ranks the candidates by their pooled scores (score_pool <= 1: the scores
+    themselves), with `sink` first tokens always retained."""
+    ranked = pool_scores(scores, score_pool) if score_pool > 1 else scores
+    if sink:
+        return select_topk_sink(ranked, budget, recent, sink)
+    return select_topk(ranked, budget, recent)
 
 
 @dataclass
@@ -237,11 +255,12 @@ def decode_step(cache: Cache, q, k_new, v_new, logical_pos: int, cfg: Config):
     for a in (cache.K, cache.V, cache.F):
         assert a.dtype == np.float64 and a.flags.c_contiguous
     out = np.empty((b, hq, d), dtype=np.float64)
-    _load().aha_oracle_decode_step(
+    _load().aha_oracle_decode_step_ext(
         _p(q), _p(k_new), _p(v_new), _I64(b * hk), _I64(G), _I64(d),
         _I64(cfg.budget), _I64(cfg.recent), _I64(slots), _I64(logical_pos),
         ctypes.c_int(cfg.scale_mode), ctypes.c_double(cfg.fixed_scale),
-        ctypes.c_double(cfg.lambda_floor), _p(cache.K), _p(cache.V), _p(cache.F),
+        ctypes.c_double(cfg.lambda_floor), _I64(cfg.sink),
+        ctypes.c_int(1 if cfg.decode_value_prior else 0), _p(cache.K), _p(cache.V), _p(cache.F),
         _p(cache.pos, ctypes.c_int32), _p(cache.free_slot, ctypes.c_int32), _p(out))
     return out
 

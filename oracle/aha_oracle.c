@@ -378,6 +378,43 @@ void aha_oracle_select_topk(const double *scores, int64_t problems, int64_t n,
 }
 
 /* ------------------------------------------------------------------------
+ * Selection with attention-sink tokens (related work: the static policy that
+ * keeps the first few tokens and the most recent ones, because the beginning
+ * of the sequence matters for the whole generation).
+ * READING: as a mode of the method's selection, the first `sink` tokens are
+ * always retained like the `recent` last ones, and the remaining
+ * budget - sink - recent places go to the highest scores among the tokens in
+ * between (ties to the lower index).  sink = 0 is aha_oracle_select_topk;
+ * budget = sink + recent is the static policy, which looks at no score.
+ * Requires sink + recent <= budget <= n.
+ *
+ * scores: [problems, n];  idx: [problems, budget] (int32), ascending
+ * ---------------------------------------------------------------------- */
+void aha_oracle_select_topk_sink(const double *scores, int64_t problems, int64_t n,
+                                 int64_t budget, int64_t recent, int64_t sink, int32_t *idx)
+{
+    int64_t first_recent = n - recent;
+    int64_t n_mid = first_recent - sink;          /* candidates sink .. n-recent-1 */
+    int64_t n_sel = budget - recent - sink;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t pr = 0; pr < problems; ++pr) {
+        const double *s = scores + pr * n;
+        int32_t *out = idx + pr * budget;
+        scored_t *c = (scored_t *)malloc(sizeof(scored_t) * (size_t)(n_mid > 0 ? n_mid : 1));
+        int64_t *keep = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_sel > 0 ? n_sel : 1));
+        for (int64_t j = 0; j < n_mid; ++j) { c[j].s = s[sink + j]; c[j].j = sink + j; }
+        qsort(c, (size_t)(n_mid > 0 ? n_mid : 0), sizeof(scored_t), cmp_scored);
+        for (int64_t t = 0; t < n_sel; ++t) keep[t] = c[t].j;
+        qsort(keep, (size_t)n_sel, sizeof(int64_t), cmp_i64);
+        for (int64_t t = 0; t < sink; ++t) out[t] = (int32_t)t;
+        for (int64_t t = 0; t < n_sel; ++t) out[sink + t] = (int32_t)keep[t];
+        for (int64_t t = 0; t < recent; ++t) out[sink + n_sel + t] = (int32_t)(first_recent + t);
+        free(c);
+        free(keep);
+    }
+}
+
+/* ------------------------------------------------------------------------
  * Smoothing of the eviction scores before the selection (caption of the
  * method's overview figure: pooling is applied to the refined scores so that
  * the retained text is not sparsified excessively).
@@ -468,6 +505,15 @@ void aha_oracle_compact_kv(const double *K, const double *V, const double *score
  * Kc, Vc: [problems, slots, d]; Fc, pos: [problems, slots]; free_slot: [problems]
  * out: [problems, G, d]
  * ---------------------------------------------------------------------- */
+void aha_oracle_decode_step_ext(const double *q, const double *k_new, const double *v_new,
+                                int64_t problems, int64_t G, int64_t d,
+                                int64_t budget, int64_t recent, int64_t slots,
+                                int64_t logical_pos,
+                                int scale_mode, double fixed_scale, double lambda_floor,
+                                int64_t sink, int value_prior,
+                                double *Kc, double *Vc, double *Fc, int32_t *pos,
+                                int32_t *free_slot, double *out);
+
 void aha_oracle_decode_step(const double *q, const double *k_new, const double *v_new,
                             int64_t problems, int64_t G, int64_t d,
                             int64_t budget, int64_t recent, int64_t slots,
@@ -475,6 +521,34 @@ void aha_oracle_decode_step(const double *q, const double *k_new, const double *
                             int scale_mode, double fixed_scale, double lambda_floor,
                             double *Kc, double *Vc, double *Fc, int32_t *pos,
                             int32_t *free_slot, double *out)
+{
+    aha_oracle_decode_step_ext(q, k_new, v_new, problems, G, d, budget, recent, slots,
+                               logical_pos, scale_mode, fixed_scale, lambda_floor, 0, 0,
+                               Kc, Vc, Fc, pos, free_slot, out);
+}
+
+/* ------------------------------------------------------------------------
+ * The generation step with two options that the paper names without fixing
+ * them for generation:
+ *   sink          tokens at positions < sink are never evicted (the static
+ *                 policy of the related work: the beginning tokens are kept);
+ *   value_prior   the probabilities added to the running scores are refined
+ *                 by the value prior (Sec. 4.3) inside the generation loop too.
+ * READING for value_prior: nu_s = ||Vc[s]||^2 over the budget + 1 live slots
+ * (the new token included), gamma_bar_s = nu_s / max over the live slots, no
+ * average pool (neighbouring slots of the compact cache are not neighbouring
+ * tokens); F[s] += gamma_bar_s * sum over the group's heads of the score
+ * probabilities.  If every live value row is zero, gamma_bar = 1.
+ * With sink = 0 and value_prior = 0 this is the step as the algorithm prints it.
+ * ---------------------------------------------------------------------- */
+void aha_oracle_decode_step_ext(const double *q, const double *k_new, const double *v_new,
+                                int64_t problems, int64_t G, int64_t d,
+                                int64_t budget, int64_t recent, int64_t slots,
+                                int64_t logical_pos,
+                                int scale_mode, double fixed_scale, double lambda_floor,
+                                int64_t sink, int value_prior,
+                                double *Kc, double *Vc, double *Fc, int32_t *pos,
+                                int32_t *free_slot, double *out)
 {
     int64_t live = budget + 1;
     double s_out = 1.0 / sqrt((double)d);
@@ -493,6 +567,18 @@ void aha_oracle_decode_step(const double *q, const double *k_new, const double *
 
         double *po = (double *)malloc(sizeof(double) * (size_t)live);
         double *pscore = (double *)malloc(sizeof(double) * (size_t)live);
+        double *gbar = (double *)malloc(sizeof(double) * (size_t)live);
+        for (int64_t s = 0; s < live; ++s) gbar[s] = 1.0;
+        if (value_prior) {
+            double numax = 0.0;
+            for (int64_t s = 0; s < live; ++s) {
+                double nu = 0.0;
+                for (int64_t t = 0; t < d; ++t) nu += vc[s * d + t] * vc[s * d + t];
+                gbar[s] = nu;
+                if (nu > numax) numax = nu;
+            }
+            for (int64_t s = 0; s < live; ++s) gbar[s] = numax > 0.0 ? gbar[s] / numax : 1.0;
+        }
         for (int64_t g = 0; g < G; ++g) {
             const double *qg = q + (pr * G + g) * d;
             softmax_row(qg, kc, live, d, s_out, po);
@@ -501,10 +587,11 @@ void aha_oracle_decode_step(const double *q, const double *k_new, const double *
             for (int64_t t = 0; t < d; ++t) o[t] = 0.0;
             for (int64_t s = 0; s < live; ++s)
                 for (int64_t t = 0; t < d; ++t) o[t] += po[s] * vc[s * d + t];
-            for (int64_t s = 0; s < live; ++s) F[s] += pscore[s];
+            for (int64_t s = 0; s < live; ++s) F[s] += gbar[s] * pscore[s];
         }
         free(po);
         free(pscore);
+        free(gbar);
 
         /* protected = the `recent` largest positions: positions are distinct,
          * so count how many live slots have a larger position */
@@ -512,7 +599,8 @@ void aha_oracle_decode_step(const double *q, const double *k_new, const double *
         for (int64_t s = 0; s < live; ++s) {
             int64_t newer = 0;
             for (int64_t u = 0; u < live; ++u) if (ps[u] > ps[s]) ++newer;
-            if (newer < recent) continue; /* protected */
+            if (newer < recent) continue; /* protected: recent */
+            if (ps[s] < sink) continue;   /* protected: sink token */
             if (victim < 0 || F[s] < F[victim] ||
                 (F[s] == F[victim] && ps[s] > ps[victim]))
                 victim = s;

@@ -428,20 +428,23 @@ def test_compaction_is_a_gather():
 
 
 # ------------------------------------------------------------ decode ----
-def _python_decode_sim(entries, q, k, v, c_t, B, Br, d, scale):
+def _python_decode_sim(entries, q, k, v, c_t, B, Br, d, scale, sink=0, value_prior=False):
     """Independent re-simulation on a dict keyed by token position."""
     entries = dict(entries)
     entries[c_t - 1] = [k.copy(), v.copy(), 0.0]
     keys = sorted(entries)
     outs = []
+    nu = np.array([float(entries[p][1] @ entries[p][1]) for p in keys])
+    gbar = nu / nu.max() if value_prior else np.ones(len(keys))
     for g in range(q.shape[0]):
         w = np.array([float(q[g] @ entries[p][0]) for p in keys])
         po = sp_softmax(w / math.sqrt(d))
         outs.append(sum(po[t] * entries[p][1] for t, p in enumerate(keys)))
         ps = sp_softmax(scale * w)
         for t, p in enumerate(keys):
-            entries[p][2] += ps[t]
+            entries[p][2] += gbar[t] * ps[t]
     protected = set(keys[len(keys) - Br:]) if Br else set()
+    protected |= {p for p in keys if p < sink}
     cands = [p for p in keys if p not in protected]
     victim = min(cands, key=lambda p: (entries[p][2], -p))
     del entries[victim]
@@ -554,3 +557,88 @@ def test_decode_equal_minima_evict_the_highest_position():
     c = _tied_cache(positions, [0.5] * 9, d, 48)
     oracle.decode_step(c, q, k, v, 21, cfg0)
     assert c.free_slot[0, 0] == 4
+
+
+# ------------------------------------------- sink tokens, value prior in decode ----
+def test_sink_selection_by_definition():
+    """First `sink` tokens + `recent` last ones + the best of the rest; sink = 0 is the plain
+    selection; budget = sink + recent looks at no score; brute force on random scores."""
+    rng = np.random.default_rng(80)
+    s = rng.random((4, 60))
+    assert np.array_equal(oracle.select_topk_sink(s, 17, 5, 0), oracle.select_topk(s, 17, 5))
+    assert oracle.select_topk_sink(s, 9, 5, 4)[2].tolist() == [0, 1, 2, 3, 55, 56, 57, 58, 59]
+    for budget, recent, sink in ((17, 5, 4), (20, 0, 3), (12, 3, 9), (60, 10, 4)):
+        idx = oracle.select_topk_sink(s, budget, recent, sink)
+        for pr in range(s.shape[0]):
+            mid = np.arange(sink, 60 - recent)
+            order = sorted(mid, key=lambda j: (-s[pr, j], j))[:budget - recent - sink]
+            want = sorted(list(range(sink)) + order + list(range(60 - recent, 60)))
+            assert idx[pr].tolist() == want
+    # a sink token with the lowest score of all is kept, a high score elsewhere is not displaced
+    z = np.linspace(1.0, 2.0, 30)[None].copy(); z[0, 0] = 0.0; z[0, 1] = 0.0
+    assert oracle.select_topk_sink(z, 6, 2, 2)[0].tolist() == [0, 1, 26, 27, 28, 29]
+
+
+@pytest.mark.parametrize("sink,vp", [(3, False), (0, True), (2, True)])
+def test_decode_with_sink_and_value_prior_against_python_resimulation(sink, vp):
+    b, hq, hk, d, n, B, Br = 1, 4, 2, 8, 40, 11, 3
+    G = hq // hk
+    Q, K, V = rnd(90, b, hq, n, d), rnd(91, b, hk, n, d), rnd(92, b, hk, n, d)
+    V *= np.linspace(0.3, 2.0, n)[None, None, :, None]          # value norms that differ a lot
+    cfg = Config(window=6, budget=B, recent=Br, value_prior=True, pool=3, sink=sink,
+                 decode_value_prior=vp)
+    S = oracle.prefill_scores(Q, K, V, cfg)
+    idx = oracle.select_topk_sink(S, B, Br, sink)
+    cache = oracle.compact_kv(K, V, S, idx, slots=B + 1)
+    sims = {p: {int(j): [K[p][j].copy(), V[p][j].copy(), float(S[p][j])] for j in idx[p]}
+            for p in np.ndindex(b, hk)}
+    rng = np.random.default_rng(93)
+    for step in range(10):
+        c_t = n + step + 1
+        q, k, v = rng.standard_normal((b, hq, d)), rng.standard_normal((b, hk, d)), \
+            rng.standard_normal((b, hk, d))
+        out = oracle.decode_step(cache, q, k, v, c_t, cfg)
+        scale = oracle.lam(c_t, B, d, cfg.lambda_floor)
+        for p in np.ndindex(b, hk):
+            sims[p], o, victim = _python_decode_sim(
+                sims[p], q[p[0], p[1] * G:(p[1] + 1) * G], k[p], v[p], c_t, B, Br, d, scale,
+                sink=sink, value_prior=vp)
+            np.testing.assert_allclose(out[p[0], p[1] * G:(p[1] + 1) * G], o, rtol=1e-11)
+            live = cache.pos[p] >= 0
+            got = {int(pp): float(f) for pp, f in zip(cache.pos[p][live], cache.F[p][live])}
+            want = {pp: e[2] for pp, e in sims[p].items()}
+            assert got.keys() == want.keys()
+            for pp in got:
+                assert got[pp] == pytest.approx(want[pp], rel=1e-11)
+            assert set(range(sink)) <= set(got)                  # sink tokens survive
+
+
+def test_decode_value_prior_special_cases():
+    """Equal value norms leave the step as printed; scaling all values changes nothing; a
+    slot with a tiny value row gains next to nothing; the total added is sum gamma_bar p."""
+    d, G, B = 8, 2, 8
+    rng = np.random.default_rng(94)
+    q, k, v = rng.standard_normal((1, G, d)), rng.standard_normal((1, 1, d)), rng.standard_normal((1, 1, d))
+    positions = [4, 9, 17, 15, -1, 0, 11, 2, 7]
+    def fresh(vscale=1.0, unit=False):
+        c = _tied_cache(positions, [0.5] * 9, d, 95)
+        if unit:
+            c.V /= np.linalg.norm(c.V, axis=-1, keepdims=True)
+        c.V *= vscale
+        return c
+    off = Config(4, B, 2)
+    on = Config(4, B, 2, decode_value_prior=True)
+    vu = v / np.linalg.norm(v)
+    a, bb = fresh(unit=True), fresh(unit=True)
+    oracle.decode_step(a, q, k, vu, 21, off); oracle.decode_step(bb, q, k, vu, 21, on)
+    np.testing.assert_allclose(a.F, bb.F, rtol=1e-13)            # equal norms: identity
+    a, bb = fresh(), fresh(3.0)
+    oracle.decode_step(a, q, k, v, 21, on); oracle.decode_step(bb, q, k, 3.0 * v, 21, on)
+    np.testing.assert_allclose(a.F, bb.F, rtol=1e-12)            # V -> cV: invariant
+    c = fresh(); c.V[0, 0, 2] *= 1e-6
+    before = c.F.copy()
+    oracle.decode_step(c, q, k, v, 21, on)
+    assert c.F[0, 0, 2] - before[0, 0, 2] < 1e-10                # tiny value row: no gain
+    ref = fresh(); oracle.decode_step(ref, q, k, v, 21, off)
+    gain_on = (c.F - before)[0, 0]; gain_on[4] = c.F[0, 0, 4]
+    assert 0 < gain_on.sum() < G                                 # less than the G units of the plain step
