@@ -84,6 +84,19 @@ enum { AHA_SCALE_FIXED = 0, AHA_SCALE_ADAPTIVE = 1 };
  *               seq_len tokens, formed in fp32 left to right).  0 or 1: off.
  *               The scores themselves, and with them the running scores that
  *               aha_compact_kv seeds, are not changed.
+ *  sink         the first `sink` tokens are always retained, like the `recent`
+ *               last ones (the static policy of the related work, which keeps
+ *               the beginning tokens and the most recent ones, as a mode of
+ *               this selection): aha_select_topk fills the remaining
+ *               budget - sink - recent places by score, aha_decode_step never
+ *               evicts a position < sink.  budget = sink + recent is the
+ *               static policy itself.  0: off.
+ *  decode_value_prior  the value prior of Sec. 4.3 inside the generation loop:
+ *               aha_decode_step multiplies what it adds to the running score
+ *               of slot s by ||v_cache[s]||^2 / max over the live slots (no
+ *               average pool: neighbouring slots are not neighbouring tokens;
+ *               all-zero values: factor 1).  0: the loop as the algorithm
+ *               prints it.
  */
 typedef struct aha_params {
     int32_t batch;        /* batch * n_kv_heads <= 65535 */
@@ -104,6 +117,8 @@ typedef struct aha_params {
     int64_t k_stride[3];  /* elements: batch, head, token (prefill K) */
     int64_t v_stride[3];  /* elements: batch, head, token (prefill V) */
     int32_t score_pool;   /* 0 | odd, 1..255; used by aha_select_topk (and the workspace size) */
+    int32_t sink;         /* >= 0, sink + recent <= budget: first tokens always retained */
+    int32_t decode_value_prior; /* 0 | 1: aha_decode_step refines what it adds to the scores */
     int32_t reserved;     /* must be 0 */
 } aha_params;
 
@@ -179,9 +194,9 @@ int32_t aha_prefill_row_stats(const aha_params *p, const void *q, const void *k,
  *
  *  scores  fp32 [batch, n_kv_heads, seq_len], non-negative and finite.
  *  idx     out, int32 dense [batch, n_kv_heads, budget], ascending token
- *          positions: the budget - recent highest-scoring tokens among
- *          positions < seq_len - recent (ties: lower position wins) followed
- *          by the `recent` last positions.
+ *          positions: the first `sink` positions, the budget - sink - recent
+ *          highest-scoring tokens among sink <= position < seq_len - recent
+ *          (ties: lower position wins), and the `recent` last positions.
  * With p->score_pool > 1 the candidates are ranked by their pooled scores,
  * which are written to the workspace first (batch * n_kv_heads * seq_len
  * floats; aha_workspace_bytes accounts for them); otherwise the workspace is
@@ -221,9 +236,10 @@ int32_t aha_compact_kv(const aha_params *p, const void *k, const void *v,
  *   3. out = sum_s softmax_s(w_s / sqrt(d)) v_cache[s]   (the attention output);
  *   4. scores_c[s] += sum_{g in group} softmax_s(scale * w_s), with the scale
  *      of p->scale_mode evaluated at c = logical_pos;
- *   5. slots whose position >= logical_pos - recent are protected; of the
- *      others the one with the smallest score is evicted (ties: the highest
- *      position): pos_c = -1 there and free_slot points to it.
+ *      (with p->decode_value_prior, times the value prior of the slot);
+ *   5. slots whose position >= logical_pos - recent or < p->sink are
+ *      protected; of the others the one with the smallest score is evicted
+ *      (ties: the highest position): pos_c = -1 there and free_slot points to it.
  *
  *  q_new        [batch, n_q_heads, head_dim] dense, p->dtype.
  *  k_new, v_new [batch, n_kv_heads, head_dim] dense, p->dtype.

@@ -51,7 +51,8 @@ class aha_params(ctypes.Structure):
         ("pool_kernel", ctypes.c_int32),
         ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
         ("v_stride", ctypes.c_int64 * 3),
-        ("score_pool", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("score_pool", ctypes.c_int32), ("sink", ctypes.c_int32),
+        ("decode_value_prior", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -117,19 +118,23 @@ class Params:
     k_stride: tuple = (0, 0, 0)
     v_stride: tuple = (0, 0, 0)
     score_pool: int = 0
+    sink: int = 0
+    decode_value_prior: int = 0
 
     def c(self) -> aha_params:
         """The C struct (built once per distinct set of field values: calls in a loop reuse it)."""
         key = (self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.seq_len,
                self.window, self.budget, self.recent, self.dtype, self.scale_mode,
                self.fixed_scale, self.lambda_floor, self.value_prior, self.pool_kernel,
-               tuple(self.q_stride), tuple(self.k_stride), tuple(self.v_stride), self.score_pool)
+               tuple(self.q_stride), tuple(self.k_stride), tuple(self.v_stride), self.score_pool,
+               self.sink, self.decode_value_prior)
         cached = self.__dict__.get("_c")
         if cached is not None and cached[0] == key:
             return aha_params.from_buffer_copy(cached[1])   # a copy: callers may edit theirs
         p = aha_params()
         for f in ("batch", "n_q_heads", "n_kv_heads", "head_dim", "seq_len", "window", "budget",
-                  "recent", "dtype", "scale_mode", "value_prior", "pool_kernel", "score_pool"):
+                  "recent", "dtype", "scale_mode", "value_prior", "pool_kernel", "score_pool",
+                  "sink", "decode_value_prior"):
             setattr(p, f, int(getattr(self, f)))
         p.fixed_scale = float(self.fixed_scale)
         p.lambda_floor = float(self.lambda_floor)

@@ -51,6 +51,12 @@ static int32_t check_common(const aha_params *p) {
         return fail(AHA_ERR_INVALID_ARG, "scale_mode %d is unknown", p->scale_mode);
     if (p->scale_mode == AHA_SCALE_FIXED && !(p->fixed_scale >= 0.f))
         return fail(AHA_ERR_INVALID_ARG, "fixed_scale must be >= 0");
+    if (p->sink < 0 || (int64_t)p->sink + p->recent > p->budget)
+        return fail(AHA_ERR_INVALID_ARG, "sink (%d) must be >= 0 and sink + recent (%d) <= budget (%d)",
+                    p->sink, p->recent, p->budget);
+    if (p->decode_value_prior != 0 && p->decode_value_prior != 1)
+        return fail(AHA_ERR_INVALID_ARG, "decode_value_prior must be 0 or 1");
+    if (p->reserved != 0) return fail(AHA_ERR_INVALID_ARG, "reserved must be 0");
     return AHA_OK;
 }
 
@@ -86,7 +92,6 @@ static int32_t check_prefill(const aha_params *p, bool need_strides) {
     if (p->score_pool < 0 || p->score_pool > 255 || (p->score_pool > 1 && p->score_pool % 2 == 0))
         return fail(AHA_ERR_INVALID_ARG, "score_pool (%d) must be 0 or odd and in [1, 255]",
                     p->score_pool);
-    if (p->reserved != 0) return fail(AHA_ERR_INVALID_ARG, "reserved must be 0");
     if (need_strides) {
         if ((rc = check_stride("q", p->q_stride, p->dtype, p->head_dim))) return rc;
         if ((rc = check_stride("k", p->k_stride, p->dtype, p->head_dim))) return rc;
@@ -212,12 +217,16 @@ static DecodePlan plan_decode(const aha_params *p) {
     pl.nsplit = (live + pl.sps - 1) / pl.sps;
     if (pl.nsplit > 1) {
         pl.off_part = align_up(sizeof(float) * (size_t)Z * G * live, 256);
-        pl.bytes = align_up(pl.off_part + sizeof(float) * (size_t)Z * pl.nsplit * G * (p->head_dim + 2), 256);
+        pl.off_nu = align_up(pl.off_part + sizeof(float) * (size_t)Z * pl.nsplit * G * (p->head_dim + 2), 256);
+        pl.bytes = pl.off_nu;
     } else {
         // one workgroup per head: dots and output probabilities of all live slots in LDS
         const size_t w_floats = (size_t)(G * live > 16 * G * p->head_dim ? G * live : 16 * G * p->head_dim);
         if ((w_floats + (size_t)G * live) * 4 > kDecodeSingleLds) pl.fits = false;
     }
+    // value prior inside the loop: the live slots' value norms and their maximum per head
+    if (p->decode_value_prior)
+        pl.bytes = align_up(pl.off_nu + sizeof(float) * ((size_t)Z * live + Z), 256);
     return pl;
 }
 
@@ -345,7 +354,8 @@ int32_t aha_select_topk(const aha_params *p, const float *scores, int32_t *idx, 
     const int pool = p->score_pool > 1 ? p->score_pool : 1;
     if (pool > 1 && (rc = check_ws(workspace, workspace_bytes, topk_ws_bytes(p)))) return rc;
     return hip_result(launch_topk(scores, p->batch * p->n_kv_heads, p->seq_len, p->budget,
-                                  p->recent, pool, (float *)workspace, idx, (hipStream_t)stream),
+                                  p->recent, p->sink, pool, (float *)workspace, idx,
+                                  (hipStream_t)stream),
                       "top-k kernels");
 }
 
@@ -421,6 +431,7 @@ static int32_t decode_step_launch(const aha_params *p, const DecodePlan &dpl, co
     g.d = p->head_dim;
     g.budget = p->budget; g.recent = p->recent; g.slots = cache_slots; g.logical_pos = logical_pos;
     g.scale_mode = p->scale_mode; g.fixed_scale = p->fixed_scale; g.lambda_floor = p->lambda_floor;
+    g.sink = p->sink; g.value_prior = p->decode_value_prior;
     return hip_result(launch_decode(g, dpl, workspace, p->dtype, (hipStream_t)stream),
                       "decode kernel");
 }

@@ -88,8 +88,9 @@ hipError_t launch_row_stats_f32(const ScoreGeom &g, const PrefillPlan &pl, void 
 // topk.hip
 // `pool` > 1: the candidates are ranked by the scores pooled over `pool` tokens, which are
 // written to `pooled` ([Z][n] floats) first.
-hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent, int pool,
-                       float *pooled, int32_t *idx, hipStream_t st);
+// `sink`: the first positions, always retained and not ranked.
+hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent, int sink,
+                       int pool, float *pooled, int32_t *idx, hipStream_t st);
 // compact.hip
 hipError_t launch_compact(const ScoreGeom &g, const float *scores, const int32_t *idx,
                           int budget, int slots, int dtype, void *kc, void *vc, float *fc,
@@ -103,6 +104,8 @@ struct DecodeGeom {
     int batch, Hq, Hkv, G, d, budget, recent, slots, logical_pos;
     int scale_mode;
     float fixed_scale, lambda_floor;
+    int sink;          // positions < sink are never evicted
+    int value_prior;   // the added probabilities are refined by ||v||^2 / max over the live slots
 };
 // With few (batch, KV head) problems the slots of a head are split over nsplit workgroups
 // (two launches, partials in the workspace); otherwise one workgroup handles a head.
@@ -114,6 +117,7 @@ struct DecodePlan {
     int nsplit;      // 1: single-launch path
     int sps;         // slots per split
     size_t off_part; // partial outputs behind the raw dots
+    size_t off_nu;   // ||v||^2 of every live slot behind those (value prior in the loop)
     size_t bytes;    // workspace bytes (0 when nsplit == 1)
     bool fits;       // the LDS the chosen path needs is within its limit
 };

@@ -65,7 +65,9 @@ __device__ __forceinline__ unsigned long long wave_min_key(unsigned long long ke
 }
 
 template <int ESIZE, int D, int G>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w_floats) {
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w_floats,
+                                                             const float *ws_nu,
+                                                             const float *ws_numax) {
     constexpr int CH = 16 / ESIZE;       // channels per 16-byte chunk
     constexpr int LPR = D / CH;          // lanes per row
     constexpr int RP = kDecThreads / LPR;  // rows per sweep
@@ -98,6 +100,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     for (int gi = 0; gi < G; ++gi)
         qw[gi] = *(const u32x4 *)((const char *)g.q + ((int64_t)(b * g.Hq + h * G + gi)) * ROWB + sub * 16);
 
+    // value prior inside the loop (an option): the slots' norms and their maximum come from
+    // a launch of their own (decode_value_norms_kernel)
+    const float ginv = g.value_prior ? prior_inverse(ws_numax[z]) : 1.f;
     // the running score and position of this thread's first slot (the later phase that updates
     // them would otherwise wait a full round trip to memory in the middle of the kernel)
     const float f_first = fcz[min(tid, live - 1)];
@@ -209,11 +214,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
             s_p[gi * live + s] = exp2f(d * c_out) / zo[gi];
             add += exp2f(d * c_sc) / zs[gi];
         }
+        if (g.value_prior) add *= prior_factor(ws_nu[(int64_t)z * live + s], ginv);
         const float f = (s == fs ? 0.f : (s == tid ? f_first : fcz[s])) + add;
         fcz[s] = f;
         int ps;
         if (s == fs) { ps = g.logical_pos - 1; posz[s] = ps; } else { ps = s == tid ? p_first : posz[s]; }
-        if (ps < g.logical_pos - g.recent) {
+        if (ps < g.logical_pos - g.recent && ps >= g.sink) {
             const unsigned long long key =
                 ((unsigned long long)__float_as_uint(f) << 32) | (uint32_t)(~ps);
             if (key < best) { best = key; best_slot = s; }
@@ -279,6 +285,38 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
         posz[victim] = -1;
         g.free_slot[z] = victim;
     }
+}
+
+// Value prior inside the generation loop (an option; Sec. 4.3 applied to the compact cache):
+// nu_s = ||v_cache[s]||^2 of every live slot - the new token's row standing in for the free
+// slot - and the largest of them, one workgroup per (batch, KV head).  A launch of its own, so
+// that the decode kernels proper carry nothing of it.
+template <int ESIZE, int D>
+__global__ __launch_bounds__(256) void decode_value_norms_kernel(DecodeGeom g, float *ws_nu,
+                                                                 float *ws_numax) {
+    constexpr int CH = 16 / ESIZE, LPR = D / CH, RP = 256 / LPR, ROWB = D * ESIZE;
+    __shared__ float s_max[4];
+    const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int live = g.budget + 1, fs = g.free_slot[z];
+    const int rg = tid / LPR, sub = tid % LPR;
+    const char *vcz = (const char *)g.vc + (int64_t)z * g.slots * ROWB;
+    const u32x4 vnw = *(const u32x4 *)((const char *)g.v_new + (int64_t)z * ROWB + sub * 16);
+    float numax = 0.f;
+    for (int s = rg; s < live; s += RP) {
+        const u32x4 vw = s == fs ? vnw : *(const u32x4 *)(vcz + (int64_t)s * ROWB + sub * 16);
+        float vf[CH];
+        unpack<ESIZE>(vw, vf);
+        float nu = 0.f;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) nu = fmaf(vf[c], vf[c], nu);
+        nu = reduce_lanes<1, LPR>(nu, OpSum{});  // over the lanes of the row
+        if (sub == 0) ws_nu[(int64_t)z * live + s] = nu;
+        numax = fmaxf(numax, nu);
+    }
+    numax = wave_max(numax);
+    if (lane == 0) s_max[wave] = numax;
+    __syncthreads();
+    if (tid == 0) ws_numax[z] = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
 }
 
 // ---- few problems: split the slots of a head over several workgroups ----
@@ -441,7 +479,9 @@ constexpr int kMergeThreads = 1024;
 template <int ESIZE, int D, int G>
 __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom g, int nsplit,
                                                            const float *ws_w,
-                                                           const float *ws_part) {
+                                                           const float *ws_part,
+                                                           const float *ws_nu,
+                                                           const float *ws_numax) {
     static_assert(G * D <= kMergeThreads, "one output element per thread");
     static_assert(kMaxDecodeSplit * G <= kMergeThreads, "one (split, head) statistic per thread");
     __shared__ float s_pm[kMaxDecodeSplit][G], s_pz[kMaxDecodeSplit][G];
@@ -470,7 +510,7 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
         my_pm = part[tid * (D + 2) + D];  // tid = split * G + head
         my_pz = part[tid * (D + 2) + D + 1];
     }
-    float wr[U][G], fr[U];
+    float wr[U][G], fr[U], nur[U];
     int pr[U];
     auto fetch = [&](int base) {
 #pragma unroll
@@ -482,6 +522,7 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
                 wr[u][gi] = ok ? ws_w[((int64_t)z * G + gi) * live + s] : -INFINITY;
             fr[u] = ok ? fcz[s] : 0.f;
             pr[u] = ok ? posz[s] : 0x7fffffff;
+            nur[u] = (ok && g.value_prior) ? ws_nu[(int64_t)z * live + s] : 0.f;
         }
     };
     auto patch_free_slot = [&](int base) {  // the new token: score 0, position logical_pos - 1
@@ -541,6 +582,7 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
     const bool one_batch = live <= U * NT;  // then the values stay in registers for pass two
     for (int base = 0; base < live; base += U * NT) {
         if (base) fetch(base);
+
         // (entries past the last slot are skipped, not fed as -inf: a scale of exactly 0
         // would turn them into 0 * inf)
 #pragma unroll
@@ -562,6 +604,7 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
         for (int w = 0; w < NT / 64; ++w) a += s_red[w][gi];
         zs[gi] = 1.f / a;
     }
+    const float ginv = g.value_prior ? prior_inverse(ws_numax[z]) : 1.f;
     unsigned long long best = ~0ull;
     int best_slot = -1;
     for (int base = 0; base < live; base += U * NT) {
@@ -574,11 +617,12 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
             float add = 0.f;
 #pragma unroll
             for (int gi = 0; gi < G; ++gi) add += exp2f((wr[u][gi] - mx[gi]) * c_sc) * zs[gi];
+            if (g.value_prior) add *= prior_factor(nur[u], ginv);
             const float f = fr[u] + add;
             fcz[s] = f;
             const int ps = pr[u];
             if (s == fs) posz[s] = ps;
-            if (ps < g.logical_pos - g.recent) {
+            if (ps < g.logical_pos - g.recent && ps >= g.sink) {
                 const unsigned long long key =
                     ((unsigned long long)__float_as_uint(f) << 32) | (uint32_t)(~ps);
                 if (key < best) { best = key; best_slot = s; }
@@ -601,6 +645,14 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
 template <int ESIZE, int D>
 static hipError_t launch_g(const DecodeGeom &g, const DecodePlan &pl, void *ws, hipStream_t st) {
     const int live = g.budget + 1;
+    float *ws_nu = (float *)((char *)ws + pl.off_nu);
+    float *ws_numax = ws_nu + (size_t)g.batch * g.Hkv * live;
+    if (g.value_prior) {
+        hipLaunchKernelGGL((decode_value_norms_kernel<ESIZE, D>), dim3(g.batch * g.Hkv), dim3(256),
+                           0, st, g, ws_nu, ws_numax);
+        const hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+    }
     if (pl.nsplit > 1) {
         float *ws_w = (float *)ws;
         float *ws_part = (float *)((char *)ws + pl.off_part);
@@ -614,7 +666,7 @@ static hipError_t launch_g(const DecodeGeom &g, const DecodePlan &pl, void *ws, 
         const hipError_t e1 = hipGetLastError();                                                 \
         if (e1 != hipSuccess) return e1;                                                         \
         hipLaunchKernelGGL((decode_merge_kernel<ESIZE, D, GG>), g2, dim3(kMergeThreads), 0, st, g,         \
-                           pl.nsplit, ws_w, ws_part);                                            \
+                           pl.nsplit, ws_w, ws_part, ws_nu, ws_numax);                           \
     }
         switch (g.G) {
             case 1: AHA_DECS(1) break;
@@ -643,7 +695,7 @@ static hipError_t launch_g(const DecodeGeom &g, const DecodePlan &pl, void *ws, 
         });                                                                                      \
         if (ea != hipSuccess) return ea;                                                         \
         hipLaunchKernelGGL((decode_kernel<ESIZE, D, GG>), grid, dim3(kDecThreads), smem, st, g,  \
-                           w_floats);                                                            \
+                           w_floats, ws_nu, ws_numax);                                           \
     }
     switch (g.G) {
         case 1: AHA_DEC(1) break;

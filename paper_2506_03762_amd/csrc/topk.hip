@@ -65,19 +65,22 @@ __device__ __forceinline__ int suffix_above(int loc, int lane, int wave, int *ws
 
 // ITEMS > 0: keys of positions [tid*ITEMS, tid*ITEMS+ITEMS) live in registers.
 // ITEMS == 0: keys are re-read (thread tid owns [tid*ipt, tid*ipt+ipt)).
+// `sink`: positions below it are retained without being ranked (their keys are the padding
+// key 0, which is never counted), like the `recent` last positions.
 template <int ITEMS>
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restrict__ scores,
                                                             int n, int budget, int recent,
-                                                            int32_t *__restrict__ idx) {
+                                                            int sink, int32_t *__restrict__ idx) {
     extern __shared__ __attribute__((aligned(16))) char topk_smem[];
     TopkSmem &sm = *(TopkSmem *)topk_smem;
 
     const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *sc = scores + (int64_t)z * n;
-    int32_t *out = idx + (int64_t)z * budget;
+    int32_t *out = idx + (int64_t)z * budget + sink;  // the ranked part starts behind the sinks
     const int n_cand = n - recent;
-    const int k = budget - recent;
+    const int k = budget - recent - sink;
 
+    for (int t = tid; t < sink; t += kTopkThreads) out[t - sink] = t;
     for (int t = tid; t < recent; t += kTopkThreads) out[k + t] = n_cand + t;
     if (k == 0) return;
 
@@ -102,15 +105,19 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
 #pragma unroll
             for (int t = 0; t < R; ++t) key[t] = j0 + t < j1 ? order_key(sc[j0 + t]) : 0u;
         }
+        if (j0 < sink) {
+#pragma unroll
+            for (int t = 0; t < R; ++t) key[t] = j0 + t < sink ? 0u : key[t];
+        }
     }
     // visit every owned key: f(key, position)
     auto for_keys = [&](auto f) {
         if (ITEMS > 0) {
 #pragma unroll
             for (int t = 0; t < R; ++t)
-                if (j0 + t < j1) f(key[t], j0 + t);
+                if (j0 + t < j1 && j0 + t >= sink) f(key[t], j0 + t);
         } else {
-            for (int j = j0; j < j1; ++j) f(order_key(sc[j]), j);
+            for (int j = max(j0, sink); j < j1; ++j) f(order_key(sc[j]), j);
         }
     };
 
@@ -314,10 +321,10 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
 }
 
 template <int ITEMS>
-static void launch_items(const float *scores, int Z, int n, int budget, int recent, int32_t *idx,
-                         hipStream_t st) {
+static void launch_items(const float *scores, int Z, int n, int budget, int recent, int sink,
+                         int32_t *idx, hipStream_t st) {
     hipLaunchKernelGGL(topk_kernel<ITEMS>, dim3(Z), dim3(kTopkThreads), sizeof(TopkSmem), st, scores,
-                       n, budget, recent, idx);
+                       n, budget, recent, sink, idx);
 }
 
 // Scores smoothed over tokens before the selection (caption of the method's overview
@@ -335,8 +342,8 @@ __global__ __launch_bounds__(256) void pool_scores_kernel(const float *__restric
     pooled[(int64_t)z * n + j] = __fdiv_rn(acc, (float)(hi - lo + 1));
 }
 
-hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent, int pool,
-                       float *pooled, int32_t *idx, hipStream_t st) {
+hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent, int sink,
+                       int pool, float *pooled, int32_t *idx, hipStream_t st) {
     static_assert(sizeof(TopkSmem) < 64 * 1024, "top-k LDS must fit the default dynamic limit");
     if (pool > 1) {
         hipLaunchKernelGGL(pool_scores_kernel, dim3((n + 255) / 256, Z), dim3(256), 0, st, scores, n,
@@ -345,12 +352,12 @@ hipError_t launch_topk(const float *scores, int Z, int n, int budget, int recent
     }
     const int n_cand = n - recent;
     const int ipt = (n_cand + kTopkThreads - 1) / kTopkThreads;
-    if (ipt <= 4) launch_items<4>(scores, Z, n, budget, recent, idx, st);
-    else if (ipt <= 8) launch_items<8>(scores, Z, n, budget, recent, idx, st);
-    else if (ipt <= 16) launch_items<16>(scores, Z, n, budget, recent, idx, st);
-    else if (ipt <= 32) launch_items<32>(scores, Z, n, budget, recent, idx, st);
-    else if (ipt <= 64) launch_items<64>(scores, Z, n, budget, recent, idx, st);
-    else launch_items<0>(scores, Z, n, budget, recent, idx, st);
+    if (ipt <= 4) launch_items<4>(scores, Z, n, budget, recent, sink, idx, st);
+    else if (ipt <= 8) launch_items<8>(scores, Z, n, budget, recent, sink, idx, st);
+    else if (ipt <= 16) launch_items<16>(scores, Z, n, budget, recent, sink, idx, st);
+    else if (ipt <= 32) launch_items<32>(scores, Z, n, budget, recent, sink, idx, st);
+    else if (ipt <= 64) launch_items<64>(scores, Z, n, budget, recent, sink, idx, st);
+    else launch_items<0>(scores, Z, n, budget, recent, sink, idx, st);
     return hipGetLastError();
 }
 

@@ -29,6 +29,8 @@ class Opts:
     value_prior: bool = True
     pool: int = 7
     score_pool: int = 0                # > 1: the selection ranks pooled scores
+    sink: int = 0                      # first tokens always retained (selection and decode)
+    decode_value_prior: bool = False   # generation: value prior inside the loop
 
 
 def rtol_of(w: synth.Workload) -> float:
@@ -44,7 +46,8 @@ def oracle_cfg(w: synth.Workload, opts: Opts) -> oracle.Config:
     return oracle.Config(window=opts.window or w.window, budget=w.budget, recent=w.recent,
                          scale_mode=opts.scale_mode, fixed_scale=opts.fixed_scale,
                          lambda_floor=opts.lambda_floor, value_prior=opts.value_prior,
-                         pool=opts.pool)
+                         pool=opts.pool, sink=opts.sink,
+                         decode_value_prior=opts.decode_value_prior)
 
 
 @dataclass
@@ -60,7 +63,7 @@ def run_prefill_oracle(w: synth.Workload, opts: Opts = Opts(), inputs=None, laye
     Q, K, V = inputs if inputs is not None else synth.make_prefill(w, layer)
     cfg = oracle_cfg(w, opts)
     S = oracle.prefill_scores(Q, K, V, cfg)
-    idx = oracle.select_topk_pooled(S, w.budget, w.recent, opts.score_pool)
+    idx = oracle.select_topk_pooled(S, w.budget, w.recent, opts.score_pool, opts.sink)
     cache = oracle.compact_kv(K.astype(np.float64), V.astype(np.float64), S, idx,
                               slots=w.budget + 1)
     # the scores that ranked the candidates (near-ties are judged on these)
@@ -79,7 +82,8 @@ def gpu_params(w: synth.Workload, opts: Opts = Opts()):
     return workload.params_for(w, window=opts.window, scale_mode=opts.scale_mode,
                                fixed_scale=opts.fixed_scale, lambda_floor=opts.lambda_floor,
                                value_prior=opts.value_prior, pool=opts.pool,
-                               score_pool=opts.score_pool)
+                               score_pool=opts.score_pool, sink=opts.sink,
+                               decode_value_prior=1 if opts.decode_value_prior else 0)
 
 
 def run_prefill_gpu(w: synth.Workload, opts: Opts = Opts(), inputs=None, layer=0,
@@ -145,16 +149,16 @@ def assert_scores_close(got, want, w, opts: Opts = Opts()):
                              % (bad.sum(), bad.size, t, got[t], want[t]))
 
 
-def assert_sets_match(idx_gpu, idx_ref, scores_ref, w, max_excused_frac=0.01):
+def assert_sets_match(idx_gpu, idx_ref, scores_ref, w, max_excused_frac=0.01, sink=0):
     """Retained sets equal, except indices whose oracle score is within rtol of
     the oracle's threshold (the B_s-th largest candidate score).  `scores_ref` are the
     oracle's float64 scores that ranked the candidates (the pooled ones when the selection
     ranks pooled scores).  Returns the number of excused indices."""
     return sets_match(idx_gpu, idx_ref, scores_ref, w.seq_len, w.budget, w.recent, rtol_of(w),
-                      max_excused_frac)
+                      max_excused_frac, sink)
 
 
-def sets_match(idx_gpu, idx_ref, scores_ref, n, B, Br, rtol, max_excused_frac=0.01):
+def sets_match(idx_gpu, idx_ref, scores_ref, n, B, Br, rtol, max_excused_frac=0.01, sink=0):
     assert idx_gpu.shape == idx_ref.shape
     excused = 0
     for p in np.ndindex(idx_ref.shape[:-1]):
@@ -162,9 +166,10 @@ def sets_match(idx_gpu, idx_ref, scores_ref, n, B, Br, rtol, max_excused_frac=0.
         assert np.all(np.diff(g) > 0), "GPU indices not strictly ascending at %s" % (p,)
         assert g.min() >= 0 and g.max() < n
         assert np.array_equal(g[B - Br:], np.arange(n - Br, n)), "recent tokens not kept"
+        assert np.array_equal(g[:sink], np.arange(sink)), "sink tokens not kept"
         if np.array_equal(g, r):
             continue
-        sel = r[r < n - Br]
+        sel = r[(r < n - Br) & (r >= sink)]
         thr = scores_ref[p][sel].min() if sel.size else 0.0
         diff = np.setxor1d(g, r)
         for j in diff:

@@ -38,10 +38,12 @@ def test_header_symbols_are_exported(lib):
 
 
 def test_struct_layout_matches_header():
-    # 14 four-byte fields, nine int64 strides, two four-byte fields
-    assert ctypes.sizeof(B.aha_params) == 14 * 4 + 9 * 8 + 2 * 4
+    # 14 four-byte fields, nine int64 strides, four four-byte fields
+    assert ctypes.sizeof(B.aha_params) == 14 * 4 + 9 * 8 + 4 * 4
     assert B.aha_params.q_stride.offset == 56
     assert B.aha_params.score_pool.offset == 56 + 72
+    assert B.aha_params.sink.offset == 56 + 72 + 4
+    assert B.aha_params.decode_value_prior.offset == 56 + 72 + 8
 
 
 def test_workspace_bytes(lib):
@@ -84,6 +86,9 @@ def call_prefill(lib, p, q=DUMMY, k=DUMMY, v=DUMMY, s=DUMMY, ws=DUMMY, nbytes=1 
     (dict(score_pool=4), B.AHA_ERR_INVALID_ARG),
     (dict(score_pool=-1), B.AHA_ERR_INVALID_ARG),
     (dict(score_pool=257), B.AHA_ERR_INVALID_ARG),
+    (dict(sink=-1), B.AHA_ERR_INVALID_ARG),
+    (dict(sink=449), B.AHA_ERR_INVALID_ARG),               # sink + recent beyond the budget
+    (dict(decode_value_prior=2), B.AHA_ERR_INVALID_ARG),
 ])
 def test_bad_params_are_rejected(lib, kw, code):
     assert call_prefill(lib, good(**kw)) == code

@@ -22,7 +22,7 @@ def check_prefill(w, opts=Opts(), decode_steps=0, layer=0):
     gpu = H.run_prefill_gpu(w, opts, inputs)
     ref = H.run_prefill_oracle(w, opts, inputs)
     H.assert_scores_close(gpu.scores, ref.scores, w, opts)
-    excused = H.assert_sets_match(gpu.idx, ref.idx, ref.extra["rank_scores"], w)
+    excused = H.assert_sets_match(gpu.idx, ref.idx, ref.extra["rank_scores"], w, sink=opts.sink)
     H.assert_compact_matches(gpu, w, inputs[1], inputs[2])
     if decode_steps:
         flips = H.run_and_check_decode(w, gpu, ref, decode_steps, opts)
@@ -250,18 +250,18 @@ def test_repeat_calls_are_bit_identical():
 
 
 # ------------------------------------------------------------------ top-k --
-def topk_both(scores32, budget, recent, score_pool=0):
+def topk_both(scores32, budget, recent, score_pool=0, sink=0):
     import torch
     from paper_2506_03762_amd import binding as B
     b, h, n = scores32.shape
     p = B.Params(batch=b, n_q_heads=h, n_kv_heads=h, head_dim=128, seq_len=n, window=1,
-                 budget=budget, recent=recent, score_pool=score_pool)
+                 budget=budget, recent=recent, score_pool=score_pool, sink=sink)
     idx = torch.full((b, h, budget), -5, dtype=torch.int32, device="cuda")
     ws = B.alloc_workspace(p)
     ws.fill_(0xA5)
     B.aha_select_topk(p, torch.from_numpy(scores32).cuda(), idx, ws)
     return idx.cpu().numpy(), oracle.select_topk_pooled(scores32.astype(np.float64), budget, recent,
-                                                        score_pool)
+                                                        score_pool, sink)
 
 
 @pytest.mark.parametrize("n,budget,recent", [
@@ -430,3 +430,69 @@ def test_all_zero_value_head_keeps_unrefined_scores(base):
     H.assert_sets_match(gpu.idx, ref.idx, ref.scores, w)
     off = H.run_prefill_gpu(w, Opts(value_prior=False), (Q, K, V))
     assert np.array_equal(gpu.scores[0, 1], off.scores[0, 1])
+
+
+# ------------------------------------------ sink tokens, value prior in the loop --
+@pytest.mark.parametrize("n,budget,recent,sink", [
+    (32768, 2048, 64, 4), (4096, 512, 64, 4), (1000, 300, 10, 290), (777, 9, 5, 4),   # last: static policy
+    (100000, 9000, 100, 7), (131072, 8192, 128, 4), (37, 9, 3, 1), (5, 5, 1, 4),
+])
+def test_topk_with_sink_tokens_bit_exact(n, budget, recent, sink):
+    rng = np.random.default_rng(n + sink)
+    heavy = np.exp(rng.standard_normal((2, 3, n)) * 3).astype(np.float32)
+    heavy[..., :sink] = 0.0                                          # sinks kept whatever they score
+    tied = (rng.integers(0, 7, (2, 3, n)) / 8.0).astype(np.float32)
+    const = np.full((1, 2, n), 0.25, np.float32)
+    for s in (heavy, tied, const):
+        got, want = topk_both(s, budget, recent, sink=sink)
+        assert np.array_equal(got, want)
+        assert np.array_equal(got[..., :sink], np.broadcast_to(np.arange(sink), got[..., :sink].shape))
+
+
+def test_sink_policy_end_to_end_with_decode():
+    """Scores -> selection with 4 sink tokens -> compaction -> generation steps in which the
+    sinks are never evicted, on both decode paths and both dtypes."""
+    check_prefill(BF, Opts(sink=4), decode_steps=12)
+    check_prefill(synth.C1, Opts(sink=4), decode_steps=12)
+    wide = synth.scaled(BF, name="bf16_sink_wide", seq_len=300, n_q_heads=16, n_kv_heads=8,
+                        budget=70, recent=8, window=16, batch=16)
+    check_prefill(wide, Opts(sink=3), decode_steps=8)
+    # sinks with scores far below everything else must still survive generation
+    w = synth.scaled(BF, name="sink_low", batch=1, n_q_heads=8, n_kv_heads=2, budget=64,
+                     recent=4, seq_len=400, window=8)
+    oc = H.random_cache(w, 21)
+    for pr in np.ndindex(1, 2):
+        pos = oc.pos[pr]
+        for sp in range(3):                                         # make sure 0, 1, 2 are cached
+            hit = np.flatnonzero(pos == sp)
+            slot = hit[0] if hit.size else np.flatnonzero((pos >= 3) & (pos < w.seq_len - w.recent))[0]
+            pos[slot] = sp
+            oc.F[pr][slot] = 0.0                                    # ... with the lowest scores
+    flips = H.run_and_check_decode(w, None, H.Result(None, None, oc), steps=6, opts=Opts(sink=3))
+    assert flips == 0
+
+
+@pytest.mark.parametrize("base,batch,hq,hkv,budget", [
+    (BF, 1, 8, 2, 300),            # few heads: split + merge launches
+    (BF, 16, 8, 8, 70),            # one workgroup per head
+    (synth.C1, 2, 4, 2, 129),      # fp32
+])
+def test_decode_with_value_prior_in_the_loop(base, batch, hq, hkv, budget):
+    """Generation with the value prior applied to what is added to the running scores
+    (gamma_bar = ||v||^2 / max over the live slots): lock-step with the oracle; value rows of
+    very different norms, so that the option changes the victims."""
+    w = synth.scaled(base, name="decode_vp", batch=batch, n_q_heads=hq, n_kv_heads=hkv,
+                     budget=budget, recent=8, seq_len=4 * budget, window=8)
+    oc = H.random_cache(w, 31 + budget)
+    scale = np.random.default_rng(5).uniform(0.1, 3.0, oc.V.shape[:3])[..., None]
+    oc.V = synth.store_round((oc.V * scale).astype(np.float32), w.dtype).astype(np.float64)
+    ref = H.Result(None, None, oc)
+    plain = oracle.Cache(oc.K.copy(), oc.V.copy(), oc.F.copy(), oc.pos.copy(), oc.free_slot.copy())
+    flips = H.run_and_check_decode(w, None, ref, steps=10, opts=Opts(decode_value_prior=True))
+    assert flips <= 1
+    # the option is not a no-op on this state: the plain loop ends elsewhere
+    cfg = H.oracle_cfg(w, Opts())
+    for t in range(10):
+        q, k, v = synth.make_decode_inputs(w, t)
+        oracle.decode_step(plain, q, k, v, w.seq_len + t + 1, cfg)
+    assert not np.allclose(np.sort(plain.F, axis=-1), np.sort(oc.F, axis=-1))
