@@ -137,6 +137,18 @@ def row_lse(Q, K, cfg: Config):
     return L
 
 
+def window_attention(Q, K, V, window: int):
+    """Causal attention output (standard scale) of the last `window` rows [b, n_q_heads, window, d]."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    b, hq, n, d = Q.shape
+    hk = K.shape[1]
+    assert hq % hk == 0 and K.shape == V.shape == (b, hk, n, d) and 1 <= window <= n
+    O = np.empty((b, hq, window, d), dtype=np.float64)
+    _load().aha_oracle_window_attention(_p(Q), _p(K), _p(V), _I64(b), _I64(hq), _I64(hk), _I64(n),
+                                        _I64(d), _I64(window), _p(O))
+    return O
+
+
 def row_entropy(Q, K, cfg: Config):
     """Entropy (nats) of the observed softmax rows [batch, n_q_heads, window]."""
     Q, K = _f64(Q), _f64(K)

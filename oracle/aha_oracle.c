@@ -246,6 +246,42 @@ void aha_oracle_row_lse(const double *Q, const double *K,
 }
 
 /* ------------------------------------------------------------------------
+ * Attention output of the observed rows (the self-attention that the score is
+ * computed beside, App. on compatibility with FlashAttention; Alg. 1 Prefill
+ * builds both from the same logits A = Q K^T / sqrt(d)):
+ *     O_i = sum_{j <= i} softmax_j(Q_i . K_j / sqrt(d)) V_j
+ * for the last `window` query positions, always with the standard scale.
+ *
+ * Q: [batch, n_q_heads, n, d]; K, V: [batch, n_kv_heads, n, d]
+ * O: [batch, n_q_heads, window, d]; row ii is query position n-window+ii.
+ * ---------------------------------------------------------------------- */
+void aha_oracle_window_attention(const double *Q, const double *K, const double *V,
+                                 int64_t batch, int64_t n_q_heads, int64_t n_kv_heads,
+                                 int64_t n, int64_t d, int64_t window, double *O)
+{
+    int64_t G = n_q_heads / n_kv_heads;
+    double s = 1.0 / sqrt((double)d);
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int64_t b = 0; b < batch; ++b) {
+        for (int64_t hq = 0; hq < n_q_heads; ++hq) {
+            const double *Kh = K + ((b * n_kv_heads + hq / G) * n) * d;
+            const double *Vh = V + ((b * n_kv_heads + hq / G) * n) * d;
+            double *p = (double *)malloc(sizeof(double) * (size_t)n);
+            for (int64_t ii = 0; ii < window; ++ii) {
+                int64_t i = n - window + ii, c = i + 1;
+                const double *q = Q + (((b * n_q_heads + hq) * n) + i) * d;
+                double *o = O + (((b * n_q_heads + hq) * window) + ii) * d;
+                softmax_row(q, Kh, c, d, s, p);
+                for (int64_t t = 0; t < d; ++t) o[t] = 0.0;
+                for (int64_t j = 0; j < c; ++j)
+                    for (int64_t t = 0; t < d; ++t) o[t] += p[j] * Vh[j * d + t];
+            }
+            free(p);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------
  * Information entropy of the observed rows (Sec. 4.2, the definition
  * H_i = - sum_j a_ij log a_ij over the keys j <= i the row attends to,
  * natural logarithm; a term with a_ij = 0 contributes 0), under the scale the

@@ -642,3 +642,29 @@ def test_decode_value_prior_special_cases():
     ref = fresh(); oracle.decode_step(ref, q, k, v, 21, off)
     gain_on = (c.F - before)[0, 0]; gain_on[4] = c.F[0, 0, 4]
     assert 0 < gain_on.sum() < G                                 # less than the G units of the plain step
+
+
+# ------------------------------------------------ attention output of the window ----
+def test_window_attention_is_textbook_attention():
+    """softmax(Q K^T / sqrt(d)) V over the causal prefix, against scipy's softmax and a
+    matrix product; the first row of a full window is V_0; constant values come back
+    unchanged; every output is a convex combination of the value rows it may see."""
+    b, hq, hk, n, d, r = 2, 4, 2, 50, 8, 9
+    Q, K, V = rnd(100, b, hq, n, d), rnd(101, b, hk, n, d), rnd(102, b, hk, n, d)
+    O = oracle.window_attention(Q, K, V, r)
+    for bb in range(b):
+        for h in range(hq):
+            for ii in range(r):
+                i = n - r + ii
+                p = sp_softmax((K[bb, h // 2, :i + 1] @ Q[bb, h, i]) / math.sqrt(d))
+                np.testing.assert_allclose(O[bb, h, ii], p @ V[bb, h // 2, :i + 1], rtol=1e-12, atol=1e-14)
+                assert np.all(O[bb, h, ii] <= V[bb, h // 2, :i + 1].max(0) + 1e-12)
+                assert np.all(O[bb, h, ii] >= V[bb, h // 2, :i + 1].min(0) - 1e-12)
+    full = oracle.window_attention(Q, K, V, n)
+    np.testing.assert_allclose(full[:, :, 0], np.repeat(V[:, :, 0], 2, axis=1), rtol=1e-13)
+    np.testing.assert_allclose(full[:, :, n - r:], O, rtol=1e-13)
+    const = np.broadcast_to(rnd(103, 1, 1, 1, d), V.shape).copy()
+    np.testing.assert_allclose(oracle.window_attention(Q, K, const, r),
+                               np.broadcast_to(const[:, :1, :1], (b, hq, r, d)), rtol=1e-12)
+    # swapping K and V, or Q and K, is noticed
+    assert np.abs(oracle.window_attention(Q, V, K, r) - O).max() > 1e-2
