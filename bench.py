@@ -228,6 +228,7 @@ def main():
         result["full_accumulation_c2"] = bench_full_c2(torch, B, synth, H, max(5, K_STEPS // 5))
         result["prefill_c5_layer"] = bench_c5_layer(torch, B, synth, H, max(5, K_STEPS // 5))
         result["scores_from_lse_c3"] = bench_lse_c3(torch, B, H, w, p, q, k, v, scores, ws, K_STEPS)
+        result["window_attention_c3"] = bench_window_attn_c3(torch, B, w, p, q, k, v, scores, ws, K_STEPS)
         result["full_accumulation_c3"] = bench_full_c3(torch, B, w, p, q, k, v, scores)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, (Q, K, V))
@@ -392,6 +393,41 @@ def bench_lse_c3(torch, B, H, w, p, q, k, v, scores, ws, steps):
     err = float(((scores - ref).abs() / (ref.abs() + 1e-6)).max())
     return {"workload": w.name + " fixed scale 1/sqrt(d)", "two_pass_us": two, "from_lse_us": one,
             "max_rel_diff": err}
+
+
+def bench_window_attn_c3(torch, B, w, p, q, k, v, scores, ws, steps):
+    """Attention output of the 64 observed rows of all heads on the C3 layer (one flash-style
+    pass on the matrix cores, two contractions), and output + scores through its log-sum-exp
+    (that launch, then the column-sum pass alone) against the two-pass scores alone."""
+    import dataclasses
+    n, d, r = w.seq_len, w.head_dim, w.window
+    pf = dataclasses.replace(p, scale_mode=B.AHA_SCALE_FIXED, fixed_scale=1.0 / math.sqrt(d))
+    wsa = torch.empty(max(B.window_attention_workspace_bytes(pf), 256), dtype=torch.uint8, device="cuda")
+    out = torch.empty((w.batch, w.n_q_heads, r, d), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((w.batch, w.n_q_heads, r), dtype=torch.float32, device="cuda")
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / steps
+
+    def both():
+        B.aha_prefill_window_attention(pf, q, k, v, out, lse, wsa)
+        B.aha_prefill_scores_lse(pf, q, k, v, lse, scores, ws)
+
+    attn = timed(lambda: B.aha_prefill_window_attention(pf, q, k, v, out, lse, wsa))
+    flops = 2 * 2.0 * d * w.batch * w.n_q_heads * (r * n - r * (r - 1) / 2)
+    return {"workload": w.name + " window rows, standard scale", "attention_us": attn,
+            "flops": flops, "TFLOPs": flops / (attn * 1e-6) / 1e12,
+            "mfma_frac": flops / (attn * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "attention_plus_scores_us": timed(both),
+            "two_pass_scores_alone_us": timed(lambda: B.aha_prefill_scores(pf, q, k, v, scores, ws))}
 
 
 def bench_c5_layer(torch, B, synth, H, steps):

@@ -172,6 +172,34 @@ int32_t aha_prefill_scores_lse(const aha_params *p, const void *q, const void *k
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Attention output of the observed rows, beside which the score is computed
+ * (appendix on compatibility with FlashAttention; Alg. 1 Prefill forms both
+ * from the logits A = Q K^T / sqrt(d)):
+ *
+ *   out[b, h, ii, :] = sum_{j <= i} softmax_j(Q_i . K_j / sqrt(d)) V_j,
+ *                      i = seq_len - window + ii,
+ *
+ * always with the standard scale, whatever p->scale_mode says.
+ *
+ *  q, k, v  as in aha_prefill_scores.
+ *  out      element type p->dtype, dense [batch, n_q_heads, window, head_dim].
+ *  lse      out, fp32 dense [batch, n_q_heads, window] or NULL: natural log of
+ *           sum_{j <= i} exp(Q_i . K_j / sqrt(d)): with scale_mode FIXED and
+ *           fixed_scale = 1/sqrt(d), what aha_prefill_scores_lse takes - the two
+ *           calls then give output and scores with one pass over the keys each.
+ *  workspace  at least aha_window_attention_workspace_bytes() bytes (its own
+ *           size query: the partial outputs of the key ranges, which
+ *           aha_workspace_bytes does not count; 0 for fp32).
+ * bf16 runs on the matrix cores (one flash-style pass); fp32 is a plain kernel
+ * for small problems.
+ */
+int32_t aha_window_attention_workspace_bytes(const aha_params *p, size_t *out_bytes);
+int32_t aha_prefill_window_attention(const aha_params *p, const void *q, const void *k,
+                                     const void *v, void *out, float *lse,
+                                     void *workspace, size_t workspace_bytes,
+                                     void *stream);
+
+/*
  * Statistics of the observed rows (Sec. 4.2: the information entropy of an
  * attention row, H_i = - sum_{j <= i} a_ij ln a_ij, whose expectation the
  * adaptive scale is derived from), by the row-statistics pass alone:

@@ -29,7 +29,8 @@ AHA_SCALE_FIXED, AHA_SCALE_ADAPTIVE = 0, 1
 
 # entry points returning an int32 status first, then the two that return strings
 EXPORTS = ("aha_workspace_bytes", "aha_prefill_scores", "aha_prefill_scores_lse",
-           "aha_prefill_row_stats", "aha_select_topk",
+           "aha_prefill_row_stats", "aha_window_attention_workspace_bytes",
+           "aha_prefill_window_attention", "aha_select_topk",
            "aha_compact_kv", "aha_decode_step", "aha_decode_step_static", "aha_profile_events",
            "aha_last_error",
            "aha_version")
@@ -75,6 +76,8 @@ def load() -> ctypes.CDLL:
     lib.aha_prefill_scores.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
     lib.aha_prefill_scores_lse.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.aha_prefill_row_stats.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
+    lib.aha_window_attention_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
+    lib.aha_prefill_window_attention.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.aha_select_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.aha_compact_kv.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     lib.aha_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp]
@@ -191,6 +194,22 @@ def aha_prefill_scores_lse(p: Params, q, k, v, lse, scores, workspace):
                                          _ptr(scores), _ptr(workspace),
                                          workspace.numel() if workspace is not None else 0,
                                          _stream()))
+
+
+def window_attention_workspace_bytes(p: Params) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().aha_window_attention_workspace_bytes(ctypes.byref(p.c()), ctypes.byref(out)))
+    return out.value
+
+
+def aha_prefill_window_attention(p: Params, q, k, v, out, lse, workspace):
+    """out [b, Hq, window, d] <- causal attention output (standard scale) of the observed rows;
+    lse [b, Hq, window] fp32 (or None) <- their natural-log softmax denominators."""
+    cp = p.c()
+    _check(load().aha_prefill_window_attention(ctypes.byref(cp), _ptr(q), _ptr(k), _ptr(v),
+                                               _ptr(out), _ptr(lse), _ptr(workspace),
+                                               workspace.numel() if workspace is not None else 0,
+                                               _stream()))
 
 
 def aha_prefill_row_stats(p: Params, q, k, lse, entropy, workspace):

@@ -11,8 +11,8 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaha.so")
 OBJDIR = os.path.join(HERE, "_build")
 
-SOURCES = ["aha_api.hip", "value_prior.hip", "score_f32.hip", "score_bf16.hip", "topk.hip",
-           "compact.hip", "decode.hip"]
+SOURCES = ["aha_api.hip", "value_prior.hip", "score_f32.hip", "score_bf16.hip", "attn_window.hip",
+           "topk.hip", "compact.hip", "decode.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -188,6 +188,26 @@ static PrefillPlan plan_prefill(const aha_params *p) {
     return pl;
 }
 
+// Attention output of the observed rows: about 512 workgroups over (block of 32 rows, key
+// range, problem); the key ranges' partials go through the workspace.
+static WindowAttnPlan plan_window_attn(const aha_params *p) {
+    WindowAttnPlan pl{};
+    const int64_t R = (int64_t)(p->n_q_heads / p->n_kv_heads) * p->window;
+    const int64_t Z = (int64_t)p->batch * p->n_kv_heads;
+    pl.n_blocks = (int)((R + 31) / 32);
+    pl.nparts = 1;
+    if (p->dtype != AHA_BF16) return pl;  // fp32: one workgroup per row, no partials
+    const int64_t steps = (p->seq_len + kP2Keys - 1) / kP2Keys;
+    int64_t want = (512 + Z * pl.n_blocks - 1) / (Z * pl.n_blocks);
+    if (want > steps) want = steps;
+    if (want > 64) want = 64;
+    pl.nparts = (int)(want < 1 ? 1 : want);
+    const size_t rows = (size_t)Z * pl.nparts * pl.n_blocks * 32;
+    pl.off_ms = align_up(sizeof(float) * rows * p->head_dim, 256);
+    pl.bytes = align_up(pl.off_ms + 2 * sizeof(float) * rows, 256);
+    return pl;
+}
+
 // Decode: split a head's slots over workgroups when there are too few heads to fill the GPU.
 // A split workgroup keeps group * (slots of its range) dots and 4 * group * head_dim partial
 // outputs in LDS; the number of splits is raised until that fits kDecodeSplitLds (the limit
@@ -319,6 +339,35 @@ int32_t aha_prefill_scores_lse(const aha_params *p, const void *q, const void *k
                                const float *lse, float *scores, void *workspace,
                                size_t workspace_bytes, void *stream) {
     return prefill_scores_impl(p, q, k, v, lse, true, scores, workspace, workspace_bytes, stream);
+}
+
+int32_t aha_window_attention_workspace_bytes(const aha_params *p, size_t *out_bytes) {
+    if (!out_bytes) return fail(AHA_ERR_INVALID_ARG, "out_bytes is null");
+    const int32_t rc = check_prefill(p, false);
+    if (rc) return rc;
+    *out_bytes = plan_window_attn(p).bytes;
+    return AHA_OK;
+}
+
+int32_t aha_prefill_window_attention(const aha_params *p, const void *q, const void *k,
+                                     const void *v, void *out, float *lse, void *workspace,
+                                     size_t workspace_bytes, void *stream) {
+    int32_t rc = check_prefill(p, true);
+    if (rc) return rc;
+    if ((rc = check_ptr("q", q, 16)) || (rc = check_ptr("k", k, 16)) || (rc = check_ptr("v", v, 16)) ||
+        (rc = check_ptr("out", out, 16)))
+        return rc;
+    if (lse && (rc = check_ptr("lse", lse, 4))) return rc;
+    const WindowAttnPlan pl = plan_window_attn(p);
+    if ((rc = check_ws(workspace, workspace_bytes, pl.bytes))) return rc;
+    const int64_t Z = (int64_t)p->batch * p->n_kv_heads;
+    const int64_t wgs = p->dtype == AHA_BF16 ? (Z * pl.nparts + 7) / 8 * 8 * pl.n_blocks
+                                             : (int64_t)pl.n_blocks * 32;
+    if (wgs > (int64_t)1 << 30 || (int64_t)pl.n_blocks * 32 > (int64_t)1 << 30)
+        return fail(AHA_ERR_UNSUPPORTED, "problem exceeds the launch grid limits");
+    const ScoreGeom g = make_geom(p, q, k, v);
+    return hip_result(launch_window_attention(g, pl, workspace, out, lse, (hipStream_t)stream),
+                      "window attention kernels");
 }
 
 int32_t aha_prefill_row_stats(const aha_params *p, const void *q, const void *k, float *lse,

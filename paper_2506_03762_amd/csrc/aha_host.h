@@ -85,6 +85,18 @@ hipError_t launch_row_stats_bf16(const ScoreGeom &g, const PrefillPlan &pl, void
                                  float *entropy, hipStream_t st);
 hipError_t launch_row_stats_f32(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *lse,
                                 float *entropy, hipStream_t st);
+// attn_window.hip
+// Attention output of the observed rows: blocks of 32 flattened query rows per problem, each
+// split over `nparts` key ranges whose partials (output rows + (max, sum) per row) sit in the
+// workspace.
+struct WindowAttnPlan {
+    int n_blocks;   // blocks of 32 flattened query rows per (batch, KV head)
+    int nparts;     // key ranges per block (bf16 path; 1 on the fp32 path, which needs no workspace)
+    size_t off_ms;  // (max, sum) pairs behind the partial outputs
+    size_t bytes;
+};
+hipError_t launch_window_attention(const ScoreGeom &g, const WindowAttnPlan &pl, void *ws,
+                                   void *out, float *lse, hipStream_t st);
 // topk.hip
 // `pool` > 1: the candidates are ranked by the scores pooled over `pool` tokens, which are
 // written to `pooled` ([Z][n] floats) first.

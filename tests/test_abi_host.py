@@ -129,6 +129,24 @@ def test_prefill_with_given_normalisers_validates(lib):
                                       big, None) == B.AHA_ERR_INVALID_ARG
 
 
+def test_window_attention_validates(lib):
+    p = good()
+    cp = p.c()
+    need = ctypes.c_size_t(0)
+    assert lib.aha_window_attention_workspace_bytes(ctypes.byref(cp), ctypes.byref(need)) == B.AHA_OK
+    assert need.value > 0 and need.value % 256 == 0
+    f32 = good(dtype=B.AHA_F32, q_stride=(0, 0, 128)).c()
+    assert lib.aha_window_attention_workspace_bytes(ctypes.byref(f32), ctypes.byref(need)) == B.AHA_OK
+    assert need.value == 0
+    call = lambda q=DUMMY, out=DUMMY, lse=DUMMY, ws=DUMMY, nbytes=1 << 40: \
+        lib.aha_prefill_window_attention(ctypes.byref(cp), q, DUMMY, DUMMY, out, lse, ws, nbytes, None)
+    assert call(q=None) == B.AHA_ERR_INVALID_ARG
+    assert call(out=None) == B.AHA_ERR_INVALID_ARG
+    assert call(lse=ctypes.c_void_p(0x1002)) == B.AHA_ERR_INVALID_ARG
+    assert call(ws=None) == B.AHA_ERR_WORKSPACE
+    assert call(nbytes=B.window_attention_workspace_bytes(p) - 1) == B.AHA_ERR_WORKSPACE
+
+
 def test_row_stats_validate(lib):
     """aha_prefill_row_stats: needs q, k and at least one output; the value strides are not looked at."""
     p = good(v_stride=(0, 0, 0))
