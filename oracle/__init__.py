@@ -123,6 +123,24 @@ def prefill_scores(Q, K, V, cfg: Config):
     return S
 
 
+def prefill_scores_rows(Q, K, V, rows, cfg: Config):
+    """Refined eviction scores [batch, n_kv_heads, n] accumulated over the query rows at the
+    positions rows[batch, n_q_heads, window] instead of the most recent ones."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    b, hq, n, d = Q.shape
+    hk = K.shape[1]
+    assert hq % hk == 0 and K.shape == V.shape == (b, hk, n, d)
+    assert rows.shape == (b, hq, cfg.window) and rows.min() >= 0 and rows.max() < n
+    S = np.empty((b, hk, n), dtype=np.float64)
+    _load().aha_oracle_prefill_scores_rows(
+        _p(Q), _p(K), _p(V), _p(rows, ctypes.c_int32), _I64(b), _I64(hq), _I64(hk), _I64(n),
+        _I64(d), _I64(cfg.window), _I64(cfg.budget), ctypes.c_int(cfg.scale_mode),
+        ctypes.c_double(cfg.fixed_scale), ctypes.c_double(cfg.lambda_floor),
+        ctypes.c_int(1 if cfg.value_prior else 0), _I64(cfg.pool), _p(S))
+    return S
+
+
 def row_lse(Q, K, cfg: Config):
     """Natural-log softmax denominators of the observed rows [batch, n_q_heads, window]."""
     Q, K = _f64(Q), _f64(K)

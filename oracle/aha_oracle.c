@@ -203,6 +203,58 @@ void aha_oracle_prefill_scores(const double *Q, const double *K, const double *V
 }
 
 /* ------------------------------------------------------------------------
+ * Prefill eviction scores accumulated over GIVEN query rows (Limitations: the
+ * choice of the constant number of accumulators is not unique - instead of
+ * the most recent rows one may select the same number of rows by a Top-k
+ * strategy).
+ * READING: the paper names no criterion for that Top-k; the rows are the
+ * caller's choice, `window` positions per (batch, query head), and everything
+ * else is the method unchanged: row at position i attends keys j <= i with the
+ * scale of a row over c = i + 1 keys, the rows' probabilities are summed per
+ * key (over the group's heads too), the value prior refines the sum.  With
+ * rows = n-window .. n-1 for every head this is aha_oracle_prefill_scores.
+ *
+ * rows: [batch, n_q_heads, window] int32 positions in [0, n); other layouts
+ * as aha_oracle_prefill_scores.
+ * ---------------------------------------------------------------------- */
+void aha_oracle_prefill_scores_rows(const double *Q, const double *K, const double *V,
+                                    const int32_t *rows,
+                                    int64_t batch, int64_t n_q_heads, int64_t n_kv_heads,
+                                    int64_t n, int64_t d, int64_t window, int64_t budget,
+                                    int scale_mode, double fixed_scale, double lambda_floor,
+                                    int value_prior, int64_t pool, double *S)
+{
+    int64_t G = n_q_heads / n_kv_heads;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int64_t b = 0; b < batch; ++b) {
+        for (int64_t hk = 0; hk < n_kv_heads; ++hk) {
+            const double *Kh = K + ((b * n_kv_heads + hk) * n) * d;
+            double *Sh = S + (b * n_kv_heads + hk) * n;
+            double *p = (double *)malloc(sizeof(double) * (size_t)n);
+            for (int64_t j = 0; j < n; ++j) Sh[j] = 0.0;
+            for (int64_t g = 0; g < G; ++g) {
+                int64_t hq = hk * G + g;
+                for (int64_t ii = 0; ii < window; ++ii) {
+                    int64_t i = rows[(b * n_q_heads + hq) * window + ii];
+                    int64_t c = i + 1;
+                    const double *q = Q + (((b * n_q_heads + hq) * n) + i) * d;
+                    double s = row_scale(scale_mode, fixed_scale, lambda_floor, c, budget, d);
+                    softmax_row(q, Kh, c, d, s, p);
+                    for (int64_t j = 0; j < c; ++j) Sh[j] += p[j];
+                }
+            }
+            free(p);
+        }
+    }
+    if (value_prior) {
+        double *gb = (double *)malloc(sizeof(double) * (size_t)(batch * n_kv_heads * n));
+        aha_oracle_value_prior(V, batch, n_kv_heads, n, d, pool, gb);
+        for (int64_t t = 0; t < batch * n_kv_heads * n; ++t) S[t] *= gb[t];
+        free(gb);
+    }
+}
+
+/* ------------------------------------------------------------------------
  * Row normalisers of the observed rows, as an attention forward pass emits
  * them (App. on compatibility with FlashAttention: the score is computed
  * beside a forward pass that keeps, per query row, the logarithm of the

@@ -668,3 +668,40 @@ def test_window_attention_is_textbook_attention():
                                np.broadcast_to(const[:, :1, :1], (b, hq, r, d)), rtol=1e-12)
     # swapping K and V, or Q and K, is noticed
     assert np.abs(oracle.window_attention(Q, V, K, r) - O).max() > 1e-2
+
+
+# ------------------------------------------------ accumulation over chosen rows ----
+def test_scores_over_given_rows():
+    """Accumulators chosen by the caller: the most recent rows give the method's scores; at
+    scale 0 the closed form S_j = sum over the chosen rows i >= j of 1 / (i + 1); a library
+    route (scipy softmax per row) for random rows; the order of the rows does not matter."""
+    b, hq, hk, n, d, r = 2, 4, 2, 70, 8, 6
+    Q, K, V = rnd(110, b, hq, n, d), rnd(111, b, hk, n, d), rnd(112, b, hk, n, d)
+    last = np.broadcast_to(np.arange(n - r, n, dtype=np.int32), (b, hq, r))
+    for cfg in (Config(r, 12, 3), Config(r, 12, 3, value_prior=False, lambda_floor=0.0)):
+        np.testing.assert_allclose(oracle.prefill_scores_rows(Q, K, V, last, cfg),
+                                   oracle.prefill_scores(Q, K, V, cfg), rtol=1e-13)
+    rng = np.random.default_rng(113)
+    rows = np.stack([[np.sort(rng.choice(n, r, replace=False)) for _ in range(hq)]
+                     for _ in range(b)]).astype(np.int32)
+    uni = oracle.prefill_scores_rows(Q, K, V, rows, Config(r, 12, 3, scale_mode=SCALE_FIXED,
+                                                           fixed_scale=0.0, value_prior=False))
+    for bb in range(b):
+        for h in range(hk):
+            want = np.zeros(n)
+            for g in range(hq // hk):
+                for i in rows[bb, h * 2 + g]:
+                    want[:i + 1] += 1.0 / (i + 1)
+            np.testing.assert_allclose(uni[bb, h], want, rtol=1e-13)
+    cfg = Config(r, 12, 3, value_prior=False)
+    got = oracle.prefill_scores_rows(Q, K, V, rows, cfg)
+    for bb in range(b):
+        for h in range(hk):
+            want = np.zeros(n)
+            for g in range(hq // hk):
+                for i in rows[bb, h * 2 + g]:
+                    lam = oracle.lam(i + 1, cfg.budget, d, cfg.lambda_floor)
+                    want[:i + 1] += sp_softmax(lam * (K[bb, h, :i + 1] @ Q[bb, h * 2 + g, i]))
+            np.testing.assert_allclose(got[bb, h], want, rtol=1e-11)
+    np.testing.assert_allclose(oracle.prefill_scores_rows(Q, K, V, rows[:, :, ::-1], cfg), got, rtol=1e-12)
+    assert np.isclose(got.sum(), b * hq * r)          # every chosen row adds one unit
