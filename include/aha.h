@@ -172,6 +172,27 @@ int32_t aha_prefill_scores_lse(const aha_params *p, const void *q, const void *k
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Prefill eviction scores accumulated over query rows that the caller chose
+ * (Limitations: the recent rows are not the only possible choice of the
+ * constant number of accumulators; the same number of rows may be selected by
+ * a Top-k strategy - the criterion is the caller's, e.g. the rows of lowest
+ * entropy from aha_prefill_row_stats).  Same result and arguments as
+ * aha_prefill_scores, except that the `window` accumulated rows of query head
+ * (b, hq) are the positions
+ *
+ *  rows    int32 dense [batch, n_q_heads, window], each in [0, seq_len)
+ *          (positions outside are clamped to the sequence; a position listed
+ *          twice is accumulated twice).
+ *
+ * The row at position i attends keys j <= i with the scale of a row over
+ * i + 1 keys.  bf16: n_q_heads / n_kv_heads * window must not exceed 256
+ * (AHA_ERR_UNSUPPORTED otherwise).
+ */
+int32_t aha_prefill_scores_rows(const aha_params *p, const void *q, const void *k,
+                                const void *v, const int32_t *rows, float *scores,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Attention output of the observed rows, beside which the score is computed
  * (appendix on compatibility with FlashAttention; Alg. 1 Prefill forms both
  * from the logits A = Q K^T / sqrt(d)):

@@ -29,6 +29,7 @@ AHA_SCALE_FIXED, AHA_SCALE_ADAPTIVE = 0, 1
 
 # entry points returning an int32 status first, then the two that return strings
 EXPORTS = ("aha_workspace_bytes", "aha_prefill_scores", "aha_prefill_scores_lse",
+           "aha_prefill_scores_rows",
            "aha_prefill_row_stats", "aha_window_attention_workspace_bytes",
            "aha_prefill_window_attention", "aha_select_topk",
            "aha_compact_kv", "aha_decode_step", "aha_decode_step_static", "aha_profile_events",
@@ -75,6 +76,7 @@ def load() -> ctypes.CDLL:
     lib.aha_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
     lib.aha_prefill_scores.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
     lib.aha_prefill_scores_lse.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.aha_prefill_scores_rows.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.aha_prefill_row_stats.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
     lib.aha_window_attention_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
     lib.aha_prefill_window_attention.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -194,6 +196,16 @@ def aha_prefill_scores_lse(p: Params, q, k, v, lse, scores, workspace):
                                          _ptr(scores), _ptr(workspace),
                                          workspace.numel() if workspace is not None else 0,
                                          _stream()))
+
+
+def aha_prefill_scores_rows(p: Params, q, k, v, rows, scores, workspace):
+    """As aha_prefill_scores, accumulated over the query rows at positions rows[b, Hq, window]
+    (int32) instead of the most recent ones."""
+    cp = p.c()
+    _check(load().aha_prefill_scores_rows(ctypes.byref(cp), _ptr(q), _ptr(k), _ptr(v), _ptr(rows),
+                                          _ptr(scores), _ptr(workspace),
+                                          workspace.numel() if workspace is not None else 0,
+                                          _stream()))
 
 
 def window_attention_workspace_bytes(p: Params) -> int:

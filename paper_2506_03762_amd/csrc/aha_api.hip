@@ -121,7 +121,7 @@ static int32_t check_ptr(const char *name, const void *ptr, size_t align) {
 
 static ScoreGeom make_geom(const aha_params *p, const void *q, const void *k, const void *v) {
     ScoreGeom g{};
-    g.q = q; g.k = k; g.v = v;
+    g.q = q; g.k = k; g.v = v; g.rows = nullptr;
     for (int t = 0; t < 3; ++t) { g.qs[t] = p->q_stride[t]; g.ks[t] = p->k_stride[t]; g.vs[t] = p->v_stride[t]; }
     g.batch = p->batch; g.Hq = p->n_q_heads; g.Hkv = p->n_kv_heads; g.G = g.Hq / g.Hkv;
     g.d = p->head_dim; g.n = p->seq_len; g.r = p->window; g.R = g.G * g.r;
@@ -291,10 +291,12 @@ int32_t aha_workspace_bytes(const aha_params *p, size_t *out_bytes) {
     return AHA_OK;
 }
 
-// Shared by aha_prefill_scores (lse == nullptr) and aha_prefill_scores_lse.
+// Shared by aha_prefill_scores (lse == nullptr), aha_prefill_scores_lse and
+// aha_prefill_scores_rows (rows != nullptr).
 static int32_t prefill_scores_impl(const aha_params *p, const void *q, const void *k,
-                                   const void *v, const float *lse, bool with_lse, float *scores,
-                                   void *workspace, size_t workspace_bytes, void *stream) {
+                                   const void *v, const float *lse, bool with_lse,
+                                   const int32_t *rows, float *scores, void *workspace,
+                                   size_t workspace_bytes, void *stream) {
     int32_t rc = check_prefill(p, true);
     if (rc) return rc;
     if ((rc = check_ptr("q", q, 16)) || (rc = check_ptr("k", k, 16)) ||
@@ -308,7 +310,13 @@ static int32_t prefill_scores_impl(const aha_params *p, const void *q, const voi
     const int64_t score_wgs = (int64_t)pl.Z * ((pl.n_qtiles + 1) / 2) * pl.nchunks;
     if (score_wgs > (int64_t)1 << 30)
         return fail(AHA_ERR_UNSUPPORTED, "problem exceeds the launch grid limits");
-    const ScoreGeom g = make_geom(p, q, k, v);
+    // chosen accumulator rows: the bf16 kernels keep them in one query tile
+    if (rows && p->dtype == AHA_BF16 && pl.n_qtiles != 1)
+        return fail(AHA_ERR_UNSUPPORTED,
+                    "chosen accumulator rows: group * window (%d) must not exceed 256 for bf16",
+                    (p->n_q_heads / p->n_kv_heads) * p->window);
+    ScoreGeom g = make_geom(p, q, k, v);
+    g.rows = rows;
     hipStream_t st = (hipStream_t)stream;
     if ((rc = hip_result(stage(0, st), "stage event"))) return rc;
     // the windowed bf16 scores form the value prior inside their row-statistics launch
@@ -331,14 +339,24 @@ static int32_t prefill_scores_impl(const aha_params *p, const void *q, const voi
 
 int32_t aha_prefill_scores(const aha_params *p, const void *q, const void *k, const void *v,
                            float *scores, void *workspace, size_t workspace_bytes, void *stream) {
-    return prefill_scores_impl(p, q, k, v, nullptr, false, scores, workspace, workspace_bytes,
-                               stream);
+    return prefill_scores_impl(p, q, k, v, nullptr, false, nullptr, scores, workspace,
+                               workspace_bytes, stream);
+}
+
+int32_t aha_prefill_scores_rows(const aha_params *p, const void *q, const void *k, const void *v,
+                                const int32_t *rows, float *scores, void *workspace,
+                                size_t workspace_bytes, void *stream) {
+    const int32_t rc = check_ptr("rows", rows, 4);
+    if (rc) return rc;
+    return prefill_scores_impl(p, q, k, v, nullptr, false, rows, scores, workspace,
+                               workspace_bytes, stream);
 }
 
 int32_t aha_prefill_scores_lse(const aha_params *p, const void *q, const void *k, const void *v,
                                const float *lse, float *scores, void *workspace,
                                size_t workspace_bytes, void *stream) {
-    return prefill_scores_impl(p, q, k, v, lse, true, scores, workspace, workspace_bytes, stream);
+    return prefill_scores_impl(p, q, k, v, lse, true, nullptr, scores, workspace, workspace_bytes,
+                               stream);
 }
 
 int32_t aha_window_attention_workspace_bytes(const aha_params *p, size_t *out_bytes) {

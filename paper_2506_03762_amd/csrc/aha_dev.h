@@ -191,22 +191,44 @@ __device__ __forceinline__ void value_norms_to_lds(const char *vbase, int64_t ro
 
 // Softmax geometry of the flattened query rows of one KV head: row rho of the
 // group is query head g = rho / r, window row ii = rho % r, token position
-// i = n - r + ii.
+// i = n - r + ii - or, when the caller chose the accumulator rows, rows[rho]
+// (`rows` points at the positions of this KV head's first query head; the G heads'
+// lists follow each other, which is the flattened order; positions are clamped to
+// the sequence, so that a bad list cannot address memory outside the tensors).
 struct RowMap {
     int n, r, R;  // sequence length, window, G * r
-    __device__ __forceinline__ int pos(int rho) const { return rho < R ? n - r + rho % r : -1; }
+    const int32_t *rows;  // null: the r most recent rows
+    __device__ __forceinline__ int pos(int rho) const {
+        if (rho >= R) return -1;
+        if (rows) return min(max(rows[rho], 0), n - 1);
+        return n - r + rho % r;
+    }
     __device__ __forceinline__ int head(int rho) const { return rho / r; }
-    // largest / smallest position among rows [lo, hi) (hi > lo, clipped to R)
+    // largest / smallest position among rows [lo, hi) (hi > lo, clipped to R); closed forms
+    // for the most recent rows, a scan for chosen rows (used on the small fp32 path only)
     __device__ __forceinline__ int max_pos(int lo, int hi) const {
         if (hi > R) hi = R;
         if (lo >= hi) return -1;
+        if (rows) {
+            int m = -1;
+            for (int t = lo; t < hi; ++t) m = max(m, pos(t));
+            return m;
+        }
         return (lo / r != (hi - 1) / r) ? n - 1 : n - r + (hi - 1) % r;
     }
     __device__ __forceinline__ int min_pos(int lo, int hi) const {
         if (hi > R) hi = R;
         if (lo >= hi) return n;
+        if (rows) {
+            int m = n;
+            for (int t = lo; t < hi; ++t) m = min(m, pos(t));
+            return m;
+        }
         return (lo / r != (hi - 1) / r) ? n - r : n - r + lo % r;
     }
 };
+
+struct OpMinI { __device__ __forceinline__ int operator()(int a, int b) const { return a < b ? a : b; } };
+struct OpMaxI { __device__ __forceinline__ int operator()(int a, int b) const { return a > b ? a : b; } };
 
 }  // namespace aha

@@ -32,6 +32,7 @@ inline hipError_t device_once(DeviceOnce &o, F fn) {
 // Geometry of one prefill call, passed by value to the kernels.
 struct ScoreGeom {
     const void *q, *k, *v;
+    const int32_t *rows;  // accumulator rows chosen by the caller [batch, Hq, r], or null
     int64_t qs[3], ks[3], vs[3];  // element strides: batch, head, token
     int batch, Hq, Hkv, G, d, n;
     int r;       // window

@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256, 2) void window_attn_kernel(ScoreGeom g, int n_
     const int part = u % nparts, z = u / nparts;
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const RowMap rm{g.n, g.r, g.R};
+    const RowMap rm{g.n, g.r, g.R, nullptr};
     const int rho0 = nbk * 32;
     const int end = rm.max_pos(rho0, rho0 + 32) + 1;  // the keys this block of rows may see
     const int steps = (end + kWgKeys - 1) / kWgKeys;
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256) void f32_window_attn_kernel(ScoreGeom g, float
     constexpr int SL = 256 / D;  // key slices of a block
     const int z = blockIdx.y, rho = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = z / g.Hkv, h = z % g.Hkv;
-    const RowMap rm{g.n, g.r, g.R};
+    const RowMap rm{g.n, g.r, g.R, nullptr};
     const int i = rm.pos(rho);
     const int hq = h * g.G + rm.head(rho);
     const float *qrow = (const float *)g.q + b * g.qs[0] + hq * g.qs[1] + (int64_t)i * g.qs[2];

@@ -104,7 +104,8 @@ __device__ __forceinline__ Segment pair_segment(const RowMap &rm, int rows, int 
                                                 int part, int nparts, int seg) {
     const int tA = pair, tB = T - 1 - pair;
     const bool two = tB != tA;
-    const int endA = rm.max_pos(tA * rows, (tA + 1) * rows) + 1;
+    // (chosen accumulator rows - a single tile - may sit anywhere: the whole sequence)
+    const int endA = rm.rows ? rm.n : rm.max_pos(tA * rows, (tA + 1) * rows) + 1;
     const int endB = two ? rm.max_pos(tB * rows, (tB + 1) * rows) + 1 : 0;
     const int sA = (endA + kWgKeys - 1) / kWgKeys, sB = (endB + kWgKeys - 1) / kWgKeys;
     // positions on the line: first tile's steps start at oA, the partner's at oB
@@ -173,7 +174,7 @@ __device__ __forceinline__ float value_prior_of_range(const ScoreGeom &g, int b,
 // ENT: the chunk's mean scaled logit under its own probabilities, E_c[t] = m + u / s, is
 // written to `partial_mean` beside the chunk's log2-sum-exp2; entropy_merge_kernel turns the
 // chunks of a row into its entropy.
-template <int D, int NB, bool ENT>
+template <int D, int NB, bool ENT, bool ROWS = false>
 __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles, int nparts,
                                                             int total_wgs, float *partial,
                                                             float *partial_mean, float *gamma,
@@ -193,7 +194,8 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
     const int part = wg % nparts, pair = (wg / nparts) % npairs, z = wg / (nparts * npairs);
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const RowMap rm{g.n, g.r, g.R};
+    const RowMap rm{g.n, g.r, g.R,
+                    ROWS ? g.rows + ((int64_t)b * g.Hq + (int64_t)h * g.G) * g.r : nullptr};
     const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
 
     for (int seg = 0; seg < 2; ++seg) {
@@ -234,8 +236,8 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
             int tid_s = tid;
             asm volatile("" : "+v"(tid_s));
             QTileRegs<D, NB> qt_regs;
-            q_tile_request<D, NB>(g, b, h, rho0, tid_s, qt_regs);
-            const float lam_req = q_tile_scale<D, NB>(g, rho0, tid_s);
+            q_tile_request<D, NB, ROWS>(g, b, h, rho0, tid_s, qt_regs);
+            const float lam_req = q_tile_scale<D, NB>(g, rm, rho0, tid_s);
             __builtin_amdgcn_sched_barrier(0);  // the key block is requested last
             load_a<D>(kbase, g.ks[2], kb_of(0), key_end, lane, a0);
             q_tile_meta<D, NB>(g, rm, rho0, tid_s, lam_req, sLam, sPos, sBlk);
@@ -256,7 +258,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
             u[ENT ? nb : 0] = 0.f;
         }
 
-        const int tile_min = rm.min_pos(rho0, rho0 + S::ROWS);
+        const int tile_min = ROWS ? tile_min_pos<NB>(sBlk) : rm.min_pos(rho0, rho0 + S::ROWS);
         auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb) {
             if (kb >= key_end) return;  // (a wave past the range's ragged end)
             if (kb + kWaveKeys - 1 <= tile_min) {
@@ -433,7 +435,7 @@ __device__ __forceinline__ void chunk_merge(const float (&e)[BATCH], int count, 
 // step load while the current one multiplies; every score is written exactly once.
 // Otherwise (full accumulation) the grid is (part, tile pair, problem) as in pass 1 and the
 // tiles' contributions meet in the scores through float atomics.
-template <int D, int NB, bool SINGLE>
+template <int D, int NB, bool SINGLE, bool ROWS = false>
 __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_qtiles,
                                                             int total_wgs, int wg_keys, int nchunks,
                                                             const float *partial,
@@ -456,7 +458,8 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     const int z = wg / per_problem, wg_in_z = wg % per_problem;
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const RowMap rm{g.n, g.r, g.R};
+    const RowMap rm{g.n, g.r, g.R,
+                    ROWS ? g.rows + ((int64_t)b * g.Hq + (int64_t)h * g.G) * g.r : nullptr};
     const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
     // SINGLE: the workgroup's key range; otherwise ranges come per tile segment (below)
     int key_begin = wg_in_z * wg_keys;
@@ -476,6 +479,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     static_assert(S::ROWS <= 256, "one thread folds the statistics of one tile row");
     // `first_kb`: the wave's first key block of the tile, requested right behind the tile's
     // own (L2-served) loads so that those are not queued behind the keys coming from HBM
+    int tile_min = 0;  // smallest position among the rows of the tile in LDS
     auto load_tile = [&](int qt, int first_kb) {
         const int rho0 = qt * S::ROWS;
         // Full accumulation sets up a tile per segment: there the thread index and the chunk
@@ -498,9 +502,9 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             // (threads without a row of their own read row 0's statistics and drop them)
             const float *psrc = partial + ((int64_t)(z * n_qtiles + qt) * nchunks_t) * S::ROWS +
                                  (tid < S::ROWS ? tid : 0);
-            q_tile_request<D, NB>(g, b, h, rho0, tid, qt_regs);
+            q_tile_request<D, NB, ROWS>(g, b, h, rho0, tid, qt_regs);
             chunk_request(psrc, S::ROWS, 0, nchunks_t, ch);
-            const float lam_req = q_tile_scale<D, NB>(g, rho0, tid);
+            const float lam_req = q_tile_scale<D, NB>(g, rm, rho0, tid);
             __builtin_amdgcn_sched_barrier(0);  // the key block is requested last
             load_a<D>(kbase, g.ks[2], first_kb, key_end, lane, a0);
             q_tile_meta<D, NB>(g, rm, rho0, tid, lam_req, sLam, sPos, sBlk);
@@ -521,6 +525,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
             q_tile_commit<D, NB>(qt_regs, tid, sQ);
         }
         __syncthreads();
+        tile_min = ROWS ? tile_min_pos<NB>(sBlk) : rm.min_pos(rho0, rho0 + S::ROWS);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             lamr[nb] = sLam[nb * 32 + (tid & 31)];
@@ -530,7 +535,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
     // this wave's 64 keys (A fragments a) against the query tile in LDS
     auto tile_times_keys = [&](const bf16x8 (&a)[kMB][D / 16], int kb, int rho0,
                                f32x16 (&col)[kMB]) {
-        if (kb + kWaveKeys - 1 <= rm.min_pos(rho0, rho0 + S::ROWS)) {
+        if (kb + kWaveKeys - 1 <= tile_min) {
             // all rows of the tile see all 64 keys: no masks, no skipped blocks
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
@@ -703,9 +708,11 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     float *gbm = (float *)(w + pl.off_gblockmax);
     static DeviceOnce once;
     const hipError_t ea = device_once(once, [] {
-        const void *kernels[4] = {(const void *)bf16_pass1_kernel<D, NB, false>,
+        const void *kernels[6] = {(const void *)bf16_pass1_kernel<D, NB, false>,
                                   (const void *)bf16_pass1_kernel<D, NB, true>,
+                                  (const void *)bf16_pass1_kernel<D, NB, false, true>,
                                   (const void *)bf16_pass2_kernel<D, NB, true>,
+                                  (const void *)bf16_pass2_kernel<D, NB, true, true>,
                                   (const void *)bf16_pass2_kernel<D, NB, false>};
         for (const void *kf : kernels) {
             const hipError_t e = hipFuncSetAttribute(
@@ -720,15 +727,25 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     // windowed pass 2: (key range, problem)
     const int64_t wgs2 = (int64_t)((g.n + pl.p2_keys - 1) / pl.p2_keys) * pl.Z;
     // with the caller's row normalisers already in place (one "chunk" per row) pass 1 is skipped
-    if (!have_lse)
-        hipLaunchKernelGGL((bf16_pass1_kernel<D, NB, false>), xcd_grid(wgs1), dim3(256), S::bytes,
-                           st, g, pl.n_qtiles, pl.nchunks, (int)wgs1, partial, (float *)nullptr,
-                           fold_prior ? gamma : nullptr, gbm);
+    if (!have_lse) {
+        if (g.rows)
+            hipLaunchKernelGGL((bf16_pass1_kernel<D, NB, false, true>), xcd_grid(wgs1), dim3(256),
+                               S::bytes, st, g, pl.n_qtiles, pl.nchunks, (int)wgs1, partial,
+                               (float *)nullptr, fold_prior ? gamma : nullptr, gbm);
+        else
+            hipLaunchKernelGGL((bf16_pass1_kernel<D, NB, false>), xcd_grid(wgs1), dim3(256),
+                               S::bytes, st, g, pl.n_qtiles, pl.nchunks, (int)wgs1, partial,
+                               (float *)nullptr, fold_prior ? gamma : nullptr, gbm);
+    }
     const int stat_chunks = have_lse ? 1 : pl.nchunks;
     // the prior's per-range maxima: one per key chunk when pass 1 formed it, else per tile
     const int n_maxima = fold_prior ? pl.nchunks : pl.n_vtiles;
     if (mid) (void)hipEventRecord(mid, st);
-    if (pl.n_qtiles == 1)
+    if (pl.n_qtiles == 1 && g.rows)
+        hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, true, true>), xcd_grid(wgs2), dim3(256),
+                           S::bytes, st, g, pl.n_qtiles, (int)wgs2, pl.p2_keys, stat_chunks,
+                           partial, gamma, gbm, n_maxima, scores);
+    else if (pl.n_qtiles == 1)
         hipLaunchKernelGGL((bf16_pass2_kernel<D, NB, true>), xcd_grid(wgs2), dim3(256), S::bytes,
                            st, g, pl.n_qtiles, (int)wgs2, pl.p2_keys, stat_chunks, partial,
                            gamma, gbm, n_maxima, scores);

@@ -28,7 +28,8 @@ __global__ __launch_bounds__(256) void f32_pass1_kernel(ScoreGeom g, float *rowL
                                                         float *ent_out) {
     const int z = blockIdx.y, rho = blockIdx.x, tid = threadIdx.x;
     const int b = z / g.Hkv, h = z % g.Hkv;
-    const RowMap rm{g.n, g.r, g.R};
+    const RowMap rm{g.n, g.r, g.R,
+                    g.rows ? g.rows + ((int64_t)b * g.Hq + (int64_t)h * g.G) * g.r : nullptr};
     const int i = rm.pos(rho);
     const int hq = h * g.G + rm.head(rho);
     const float *qrow = (const float *)g.q + b * g.qs[0] + hq * g.qs[1] + (int64_t)i * g.qs[2];
@@ -95,7 +96,8 @@ __global__ __launch_bounds__(256) void f32_pass2_kernel(ScoreGeom g, const float
     const int z = blockIdx.y, tid = threadIdx.x;
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int j = blockIdx.x * 256 + tid;
-    const RowMap rm{g.n, g.r, g.R};
+    const RowMap rm{g.n, g.r, g.R,
+                    g.rows ? g.rows + ((int64_t)b * g.Hq + (int64_t)h * g.G) * g.r : nullptr};
     const float *kbase = (const float *)g.k + b * g.ks[0] + h * g.ks[1];
 
     __shared__ float s_q[kF32QRows][D];

@@ -37,7 +37,9 @@ struct QTileRegs {
     unsigned valid;  // bit u: chunk u belongs to a real row (others are stored as zero)
 };
 
-template <int D, int NB>
+// ROWS: the accumulator rows were chosen by the caller (g.rows); a compile-time switch, so
+// that the default kernels carry none of it.
+template <int D, int NB, bool ROWS = false>
 __device__ __forceinline__ void q_tile_request(const ScoreGeom &g, int b, int h, int rho0,
                                                int tid, QTileRegs<D, NB> &t) {
     constexpr int CPR = D / 8;        // 16-byte chunks per row
@@ -54,6 +56,25 @@ __device__ __forceinline__ void q_tile_request(const ScoreGeom &g, int b, int h,
     // row), so the loads need no branches and are all issued back to back
     const int gi0 = rho0 / g.r, ii0 = rho0 - gi0 * g.r;
     t.valid = 0u;
+    if constexpr (ROWS) {
+        // accumulator rows chosen by the caller: the position of every row comes from the list
+        // (one more round trip to memory in the set-up; the default path below has none)
+        const RowMap rm{g.n, g.r, g.R, g.rows + ((int64_t)b * g.Hq + (int64_t)h * g.G) * g.r};
+        const __bf16 *b0 = (const __bf16 *)g.q + b * g.qs[0] + (int64_t)h * g.G * g.qs[1] + c * 8;
+        int pos[QTileRegs<D, NB>::U];
+#pragma unroll
+        for (int u = 0; u < QTileRegs<D, NB>::U; ++u) {
+            const int rr = rho + u * STEP;
+            t.valid |= rr < g.R ? 1u << u : 0u;
+            pos[u] = rm.pos(rr < g.R ? rr : rho0);
+        }
+#pragma unroll
+        for (int u = 0; u < QTileRegs<D, NB>::U; ++u) {
+            const int rr = rho + u * STEP < g.R ? rho + u * STEP : rho0;
+            t.w[u] = *(const u32x4 *)(b0 + (rr / g.r) * g.qs[1] + (int64_t)pos[u] * g.qs[2]);
+        }
+        return;
+    }
 #pragma unroll
     for (int u = 0; u < QTileRegs<D, NB>::U; ++u) {
         const bool ok = rho < g.R;
@@ -85,28 +106,46 @@ __device__ __forceinline__ void q_tile_commit(const QTileRegs<D, NB> &t, int tid
 // The scale of window row ii (token position n - r + ii, c = position + 1 keys) is a
 // logarithm and a square root per row and tile: computed in place, no table.
 template <int D, int NB>
-__device__ __forceinline__ float q_tile_scale(const ScoreGeom &g, int rho0, int tid) {
+__device__ __forceinline__ float q_tile_scale(const ScoreGeom &g, const RowMap &rm, int rho0,
+                                              int tid) {
     static_assert(TileSmem<D, NB>::ROWS <= 256, "one tile row per thread");
     const int rho = rho0 + min(tid, TileSmem<D, NB>::ROWS - 1);
-    const int ii = rho < g.R ? rho % g.r : 0;
-    return row_scale_log2_f32(g.scale_mode, g.fixed_scale, g.lambda_floor, g.n - g.r + ii + 1,
-                              g.budget, g.d);
+    const int i = rm.pos(rho < g.R ? rho : 0);
+    return row_scale_log2_f32(g.scale_mode, g.fixed_scale, g.lambda_floor, i + 1, g.budget, g.d);
 }
 template <int D, int NB>
 __device__ __forceinline__ void q_tile_meta(const ScoreGeom &g, const RowMap &rm, int rho0,
                                             int tid, float lam_requested, float *sLam, int *sPos,
                                             int *sBlk) {
     using S = TileSmem<D, NB>;
+    const int rho = rho0 + tid;
+    const bool ok = tid < S::ROWS && rho < g.R;
+    const int pos = ok ? rm.pos(rho) : -1;
     if (tid < S::ROWS) {
-        const int rho = rho0 + tid;
-        const bool ok = rho < g.R;
-        sPos[tid] = ok ? g.n - g.r + rho % g.r : -1;
+        sPos[tid] = pos;
         sLam[tid] = ok ? lam_requested : 0.f;
     }
-    if (tid < NB) {
+    if (rm.rows) {
+        // chosen rows come in no particular pattern: the 32 rows of a block are 32 adjacent
+        // threads, whose positions are reduced in the vector ALU (every thread takes part)
+        const int mx = reduce_lanes<1, 32>(pos, OpMaxI{});
+        const int mn = reduce_lanes<1, 32>(ok ? pos : g.n, OpMinI{});
+        if ((tid & 31) == 0 && tid < S::ROWS) {
+            sBlk[tid >> 5] = mx;
+            sBlk[NB + (tid >> 5)] = mn;
+        }
+    } else if (tid < NB) {
         sBlk[tid] = rm.max_pos(rho0 + tid * 32, rho0 + tid * 32 + 32);
         sBlk[NB + tid] = rm.min_pos(rho0 + tid * 32, rho0 + tid * 32 + 32);
     }
+}
+// Smallest position of the tile's rows, from the per-block minima (after the tile's barrier).
+template <int NB>
+__device__ __forceinline__ int tile_min_pos(const int *sBlk) {
+    int m = sBlk[NB];
+#pragma unroll
+    for (int nb = 1; nb < NB; ++nb) m = min(m, sBlk[NB + nb]);
+    return m;
 }
 
 // A fragments of a wave's key block: lane holds row kb + mb*32 + lane%32,

@@ -129,6 +129,18 @@ def test_prefill_with_given_normalisers_validates(lib):
                                       big, None) == B.AHA_ERR_INVALID_ARG
 
 
+def test_scores_over_chosen_rows_validate(lib):
+    p = good()
+    cp = p.c()
+    call = lambda rows=DUMMY, pp=cp: lib.aha_prefill_scores_rows(
+        ctypes.byref(pp), DUMMY, DUMMY, DUMMY, rows, DUMMY, DUMMY, 1 << 40, None)
+    assert call(rows=None) == B.AHA_ERR_INVALID_ARG
+    assert b"rows" in lib.aha_last_error()
+    wide = good(window=128).c()                     # 4 query heads x 128 rows: two query tiles
+    assert call(pp=wide) == B.AHA_ERR_UNSUPPORTED
+    assert b"256" in lib.aha_last_error()
+
+
 def test_window_attention_validates(lib):
     p = good()
     cp = p.c()

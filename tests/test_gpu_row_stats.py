@@ -118,3 +118,77 @@ def test_log_sum_exp_hands_over_to_the_single_pass_scores():
     H.assert_scores_close(got, two.scores, w, opts)
     ref = H.run_prefill_oracle(w, opts, (Q, K, V))
     H.assert_scores_close(got, ref.scores, w, opts)
+
+
+# ----------------------------------------- accumulators chosen by a Top-k strategy --
+def run_scores_rows(w, opts, inputs, rows):
+    import torch
+    from paper_2506_03762_amd import binding as B
+    Q, K, V = inputs
+    q, k, v = (H.to_device(a, w.dtype) for a in (Q, K, V))
+    p = H.gpu_params(w, opts).with_strides(q, k, v)
+    ws = B.alloc_workspace(p)
+    ws.fill_(0xA5)
+    scores = torch.full((w.batch, w.n_kv_heads, w.seq_len), float("nan"), dtype=torch.float32,
+                        device="cuda")
+    B.aha_prefill_scores_rows(p, q, k, v, torch.from_numpy(np.ascontiguousarray(rows, np.int32)).cuda(),
+                              scores, ws)
+    torch.cuda.synchronize()
+    return scores.cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("w,opts", [
+    (synth.C1, Opts()),
+    (synth.C1, Opts(scale_mode=SCALE_FIXED, fixed_scale=0.0, value_prior=False)),   # closed form
+    (BF, Opts()),
+    (BF, Opts(value_prior=False, lambda_floor=0.0)),
+    (synth.scaled(BF, name="ragged", seq_len=1573, window=37, n_q_heads=6, n_kv_heads=2, head_dim=64),
+     Opts()),
+    (synth.scaled(BF, name="g8", seq_len=640, window=32, n_q_heads=16, n_kv_heads=2), Opts(pool=3)),
+    (synth.scaled(BF, name="one_row", seq_len=300, window=1, n_q_heads=2, n_kv_heads=2, budget=50,
+                  recent=5), Opts()),
+], ids=lambda x: getattr(x, "name", None))
+def test_scores_over_chosen_rows_match_the_oracle(w, opts):
+    """aha_prefill_scores_rows: random row positions per (batch, query head), anywhere in the
+    sequence (early rows see few keys: masks and skipped blocks everywhere), and the most
+    recent rows, which must reproduce aha_prefill_scores."""
+    print("case", w.name, opts, flush=True)
+    inputs = synth.make_prefill(w)
+    r = opts.window or w.window
+    cfg = H.oracle_cfg(w, opts)
+    rng = np.random.default_rng(w.seq_len + r)
+    rows = np.stack([[np.sort(rng.choice(w.seq_len, r, replace=False)) for _ in range(w.n_q_heads)]
+                     for _ in range(w.batch)]).astype(np.int32)
+    got = run_scores_rows(w, opts, inputs, rows)
+    want = oracle.prefill_scores_rows(*inputs, rows, cfg)
+    H.assert_scores_close(got, want, w, opts)
+    last = np.broadcast_to(np.arange(w.seq_len - r, w.seq_len, dtype=np.int32),
+                           (w.batch, w.n_q_heads, r))
+    plain = H.run_prefill_gpu(w, opts, inputs)
+    H.assert_scores_close(run_scores_rows(w, opts, inputs, last), plain.scores, w, opts)
+    # the order of the list does not matter
+    wild = rows[:, :, ::-1].copy()
+    H.assert_scores_close(run_scores_rows(w, opts, inputs, wild), want, w, opts)
+
+
+def test_lowest_entropy_rows_as_accumulators():
+    """One Top-k strategy for the accumulators, composed from the library's own entry points:
+    the entropy of every row (aha_prefill_row_stats, window = n), the `window` rows of lowest
+    entropy among the later half of each head (picked on the host), and the scores
+    accumulated over those rows - against the oracle fed with the same rows."""
+    w = synth.scaled(BF, name="topk_rows", seq_len=1024, n_q_heads=8, n_kv_heads=2, window=16)
+    inputs = synth.make_prefill(w)
+    n, r = w.seq_len, w.window
+    _, ent = run_row_stats(w, Opts(window=n), inputs[0], inputs[1])
+    cand = ent[:, :, n // 2:]                                   # rows that see at least n/2 keys
+    rows = (np.sort(np.argsort(cand, axis=-1)[:, :, :r], axis=-1) + n // 2).astype(np.int32)
+    got = run_scores_rows(w, Opts(), inputs, rows)
+    want = oracle.prefill_scores_rows(*inputs, rows, H.oracle_cfg(w, Opts()))
+    H.assert_scores_close(got, want, w, Opts())
+    idx_ref = oracle.select_topk(want, w.budget, w.recent)
+    import torch
+    from paper_2506_03762_amd import binding as B
+    p = H.gpu_params(w, Opts())
+    idx = torch.empty((w.batch, w.n_kv_heads, w.budget), dtype=torch.int32, device="cuda")
+    B.aha_select_topk(p, torch.from_numpy(got.astype(np.float32)).cuda(), idx)
+    H.assert_sets_match(idx.cpu().numpy(), idx_ref, want, w)
