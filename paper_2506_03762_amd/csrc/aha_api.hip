@@ -183,7 +183,11 @@ static PrefillPlan plan_prefill(const aha_params *p) {
     pl.off_gblockmax = off;  // per-range maxima of the value prior: per tile, or per key chunk
     const size_t n_maxima = (size_t)(pl.n_vtiles > pl.nchunks ? pl.n_vtiles : pl.nchunks);
     off = align_up(off + sizeof(float) * (size_t)pl.Z * n_maxima, 256);
-    pl.can_fold = p->dtype == AHA_BF16 && pl.n_qtiles == 1;
+    // windowed bf16 scores: pass 1 forms the value prior itself (the pooling halo it gathers
+    // at a range's ends is bounded: pool widths up to 17)
+    pl.can_fold = p->dtype == AHA_BF16 && pl.n_qtiles == 1 && p->pool_kernel <= 17;
+    pl.off_nu = off;  // squared value norms [Z][n], pass 1 -> its own pooling
+    if (pl.can_fold) off = align_up(off + sizeof(float) * (size_t)pl.Z * n, 256);
     pl.bytes = off;
     return pl;
 }
@@ -320,7 +324,7 @@ static int32_t prefill_scores_impl(const aha_params *p, const void *q, const voi
     hipStream_t st = (hipStream_t)stream;
     if ((rc = hip_result(stage(0, st), "stage event"))) return rc;
     // the windowed bf16 scores form the value prior inside their row-statistics launch
-    const bool fold_prior = pl.can_fold && p->value_prior && !with_lse;
+    const bool fold_prior = pl.can_fold && p->value_prior && !with_lse && !rows;
     if ((rc = hip_result(launch_value_prior(g, pl, workspace, scores, lse,
                                             p->value_prior && !fold_prior, st),
                          "value-prior kernel")))

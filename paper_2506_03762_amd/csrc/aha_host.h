@@ -55,7 +55,7 @@ struct PrefillPlan {
     int p2_keys;     // keys per pass-2 workgroup (a multiple of kP2Keys)
     int n_vtiles;    // value-prior tiles per problem (separate launch)
     bool can_fold;   // windowed bf16 scores: pass 1 can form the value prior per key chunk
-    size_t off_rowL, off_partial, off_partial_mean, off_gamma, off_gblockmax;
+    size_t off_rowL, off_partial, off_partial_mean, off_gamma, off_gblockmax, off_nu;
     size_t bytes;
 };
 

@@ -125,16 +125,119 @@ __device__ __forceinline__ Segment pair_segment(const RowMap &rm, int rows, int 
 }
 
 // ---------------------------------------------------------------- pass 1 --
-// Value prior (Sec. 4.3) of the keys [kbeg, kend) of problem z, formed by the workgroup that
-// computes those keys' row statistics: nu = ||V||^2 of the range and its pooling halo into
+// Value prior (Sec. 4.3) inside pass 1.  The value rows of the 64 keys a wave multiplies in a
+// step are loaded with the addressing of the key fragments into the register buffer that is
+// idle in the first half of the step (the next key block is requested at mid-step instead of
+// at the start): a lane then holds one half (the channels of its half-wave) of two value rows.
+
+// nu = ||V_row||^2 of those rows: squares summed in-lane, one exchange between the half-waves.
+template <int D>
+__device__ __forceinline__ void fragment_row_norms(const bf16x8 (&a)[kMB][D / 16],
+                                                   float (&nu)[kMB]) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int mb = 0; mb < kMB; ++mb) {
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {
+            const bf16x8 w = a[mb][ks];
+            const bf16x2 p0 = {w[0], w[1]}, p1 = {w[2], w[3]}, p2 = {w[4], w[5]}, p3 = {w[6], w[7]};
+            s0 = __builtin_amdgcn_fdot2_f32_bf16(p0, p0, s0, false);
+            s1 = __builtin_amdgcn_fdot2_f32_bf16(p1, p1, s1, false);
+            s0 = __builtin_amdgcn_fdot2_f32_bf16(p2, p2, s0, false);
+            s1 = __builtin_amdgcn_fdot2_f32_bf16(p3, p3, s1, false);
+        }
+        const float h = s0 + s1;
+        nu[mb] = combine_lane_xor<32>(h, OpSum{});
+    }
+}
+
+// Pooling halo of a key range [kbeg, kend): the (pool - 1) / 2 value rows below and above it,
+// one per group of d / 8 lanes (at most 256 / (d / 8) rows: the host checks the pool width).
+// Requested right after the main loop, squared when the range is pooled.
+template <int D>
+struct PriorHalo {
+    static constexpr int CPR = D / 8;  // 16-byte chunks per value row
+    u32x4 w;
+    int pos;     // token of this thread's halo row
+    bool valid;  // the row exists (inside the sequence, inside the halo)
+    bool below;
+    __device__ __forceinline__ void request(const ScoreGeom &g, const __bf16 *vbase, int kbeg,
+                                            int kend, int tid) {
+        const int half = (g.pool - 1) / 2, hrow = tid / CPR;
+        below = hrow < half;
+        pos = below ? kbeg - half + hrow : kend + hrow - half;
+        valid = hrow < 2 * half && pos >= 0 && pos < g.n;
+        w = u32x4{0u, 0u, 0u, 0u};
+        if (valid) w = *(const u32x4 *)(vbase + (int64_t)pos * g.vs[2] + (tid % CPR) * 8);
+    }
+    // ||row||^2 in the first lane of the row's group (every lane takes part)
+    __device__ __forceinline__ float norm() const {
+        float hn = 0.f;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float x = bf16_lo(w[c]), y = bf16_hi(w[c]);
+            hn = fmaf(x, x, fmaf(y, y, hn));
+        }
+        return reduce_lanes<1, CPR>(hn, OpSum{});
+    }
+};
+
+// gamma = edge-truncated mean of nu over the pool window for the keys [kbeg, kend) of problem
+// z, written to `gamma`; returns (in every thread) the largest gamma of the range.  The norms
+// of the range's own rows were left by the workgroup's waves in `nu_g` (read past the L1:
+// other waves of this workgroup wrote them); the range is worked through in pieces staged in
+// s_nu.  The caller has passed a barrier since the last norm was written.
+constexpr int kPriorPiece = 512;
+constexpr int kPriorMaxHalo = 32;  // rows on both sides together
+constexpr size_t kPriorSmem = (kPriorPiece + kPriorMaxHalo + 4) * sizeof(float);
+template <int D>
+__device__ __forceinline__ float pool_norms_of_range(const ScoreGeom &g, int z, int kbeg,
+                                                     int kend, const float *nu_g,
+                                                     const PriorHalo<D> &halo, float *s_nu,
+                                                     float *gamma, int tid) {
+    const int half = (g.pool - 1) / 2;
+    float *s_max = s_nu + kPriorPiece + kPriorMaxHalo;
+    const float hn = halo.norm();
+    float gmax = 0.f;
+    for (int t0 = kbeg; t0 < kend; t0 += kPriorPiece) {
+        const int t1 = min(kend, t0 + kPriorPiece);
+        const int lo = max(0, t0 - half), hi = min(g.n, t1 + half);  // hi exclusive
+        for (int t = max(lo, kbeg) + tid; t < min(hi, kend); t += 256)
+            s_nu[t - lo] = __hip_atomic_load(nu_g + (int64_t)z * g.n + t, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+        // the halo rows that touch this piece (the first piece below, the last one above)
+        if (halo.valid && tid % PriorHalo<D>::CPR == 0 && (halo.below ? t0 == kbeg : t1 == kend))
+            s_nu[halo.pos - lo] = hn;
+        __syncthreads();
+        for (int j = t0 + tid; j < t1; j += 256) {
+            const int a = max(0, j - half), e = min(g.n - 1, j + half);
+            float s = 0.f;
+            for (int t = a; t <= e; ++t) s += s_nu[t - lo];
+            const float gam = s / (float)(e - a + 1);
+            gamma[(int64_t)z * g.n + j] = gam;
+            gmax = fmaxf(gmax, gam);
+        }
+        __syncthreads();
+    }
+    gmax = wave_max(gmax);
+    if ((tid & 63) == 0) s_max[tid >> 6] = gmax;
+    __syncthreads();
+    gmax = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+    __syncthreads();
+    return gmax;
+}
+
+// The prior of a key range formed AFTER the main loop, for tiles of fewer than 256 rows (see
+// bf16_pass1_kernel): value rows of the keys [kbeg, kend) of problem z are streamed in a phase
+// of their own: nu = ||V||^2 of the range and its pooling halo into
 // LDS, gamma = edge-truncated mean over the pool window, written to `gamma`; returns (in
 // every thread) the largest gamma of the range.  Works through the range in pieces of
 // kPriorPiece keys so that the LDS it borrows (the query tile's, free at that time) stays
 // small.  Ends with a barrier: the LDS may be reused at once.
-constexpr int kPriorPiece = 512;
 // value rows a lane requests before it uses the first (9 and 33 measured slower here)
 constexpr int kPriorLoads = 17;
-constexpr size_t kPriorSmem = (kPriorPiece + 256 + 4) * sizeof(float);
+constexpr size_t kPriorTailSmem = (kPriorPiece + 256 + 4) * sizeof(float);
 __device__ __forceinline__ float value_prior_of_range(const ScoreGeom &g, int b, int h, int z,
                                                       int kbeg, int kend, float *s_nu,
                                                       float *gamma, int tid) {
@@ -165,27 +268,37 @@ __device__ __forceinline__ float value_prior_of_range(const ScoreGeom &g, int b,
     return gmax;
 }
 
-// `gamma` != null (windowed scores with the value prior): the workgroup also forms the prior
-// of its key range, after its statistics, and leaves the range's maximum in
-// gblockmax[z * nparts + part]: one launch less than a value-prior kernel of its own (a
-// launch costs 4 - 5 us, a third of that kernel's time at 8 heads x 32K).  (Letting half of
-// the workgroups form the prior first, so that value streaming and arithmetic would meet on
-// the chip, measured the same.)
+// PRIOR (windowed scores with the value prior): the workgroup also forms the prior of its key
+// range and leaves the range's maximum in gblockmax[z * nparts + part]: one launch less than
+// a value-prior kernel of its own (a launch costs 4 - 5 us, a third of that kernel's time at
+// 8 heads x 32K).  Where in the kernel depends on the tile:
+//  - a full tile (256 rows, NB = 8): a step's arithmetic takes microseconds, long enough to
+//    hide a load, so the value rows stream in under it.  Per step a wave loads the value rows
+//    of its 64 keys into the idle register buffer, squares them at mid-step into `nu_g`
+//    ([problem][token], workspace) and only then requests the next key block into that
+//    buffer; after the main loop the range's norms are pooled (32K tokens x 8 KV heads:
+//    pass 1 43.6 -> 39.5 us against a phase after the loop).
+//  - smaller tiles: the steps are too short for that (the key prefetch would have half a
+//    step to arrive), and the kernel is bound by the key stream: the value rows are streamed
+//    in a phase of their own after the statistics (16K tokens x 128 heads x 64 rows: 183 us
+//    against 215 us interleaved).
 // ENT: the chunk's mean scaled logit under its own probabilities, E_c[t] = m + u / s, is
 // written to `partial_mean` beside the chunk's log2-sum-exp2; entropy_merge_kernel turns the
 // chunks of a row into its entropy.
-template <int D, int NB, bool ENT, bool ROWS = false>
+template <int D, int NB, bool ENT, bool ROWS = false, bool PRIOR = false>
 __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles, int nparts,
                                                             int total_wgs, float *partial,
                                                             float *partial_mean, float *gamma,
-                                                            float *gblockmax) {
+                                                            float *gblockmax, float *nu_g) {
     using S = TileSmem<D, NB>;
+    constexpr bool kInterleave = PRIOR && NB == 8;  // value rows under the tile arithmetic
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __bf16 *sQ = (__bf16 *)smem;
     float *sLam = (float *)(smem + S::q_bytes);
     int *sPos = (int *)(sLam + S::ROWS);
     int *sBlk = sPos + 2 * S::ROWS;
     float4 *sRed = (float4 *)smem;  // reuses the query tile after the main loop
+    float *sNu = (float *)(smem + S::bytes);  // kInterleave: kPriorSmem bytes behind the tile
 
     // logical workgroup index -> (part, tile pair, problem)
     const int wg = logical_wg_index(total_wgs, n_qtiles > 1);
@@ -211,6 +324,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
                 my_partial[tid] = -INFINITY;
                 if (ENT) partial_mean[my_off + tid] = 0.f;
             }
+            if (PRIOR && tid == 0) gblockmax[z * nparts + part] = 0.f;  // no keys, no prior
             continue;
         }
         if (seg) __syncthreads();  // the previous tile (and its reduction buffer) is done with
@@ -259,12 +373,13 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
         }
 
         const int tile_min = ROWS ? tile_min_pos<NB>(sBlk) : rm.min_pos(rho0, rho0 + S::ROWS);
-        auto step = [&](const bf16x8 (&a)[kMB][D / 16], int kb) {
+        // blocks [nb0, nb1) of the tile against the 64 keys at kb
+        auto blocks = [&](const bf16x8 (&a)[kMB][D / 16], int kb, int nb0, int nb1) {
             if (kb >= key_end) return;  // (a wave past the range's ragged end)
             if (kb + kWaveKeys - 1 <= tile_min) {
                 // every row of the tile sees all 64 keys: no masks, no skipped blocks
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
+                for (int nb = nb0; nb < nb1; ++nb) {
                     f32x16 acc[kMB];
                     mma_block<D, NB>(a, sQ, nb, lane, acc);
                     stats_update<false, ENT>(acc, lam[nb], 0, kb, lane, m[nb], s[nb], u[ENT ? nb : 0]);
@@ -272,7 +387,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
                 return;
             }
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
+            for (int nb = nb0; nb < nb1; ++nb) {
                 if (bmax[nb] < kb) continue;  // nothing of this block sees these keys
                 f32x16 acc[kMB];
                 mma_block<D, NB>(a, sQ, nb, lane, acc);
@@ -282,18 +397,43 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
                     stats_update<false, ENT>(acc, lam[nb], pos[nb], kb, lane, m[nb], s[nb], u[ENT ? nb : 0]);
             }
         };
-        // The prefetch is issued unconditionally (past the range it re-reads clamped rows
-        // that are never used): behind a branch the compiler can no longer tell how many
-        // loads are in flight and would wait for the prefetch itself before the current
-        // step.
+        // One step: the key block in `a` against the whole tile, while `nx` receives the next
+        // key block.  The loads are issued unconditionally (past the range they re-read
+        // clamped rows that are never used): behind a branch the compiler can no longer tell
+        // how many loads are in flight and would wait for the prefetch itself.
+        auto step = [&](const bf16x8 (&a)[kMB][D / 16], bf16x8 (&nx)[kMB][D / 16], int kb,
+                        int kb_next) {
+            if constexpr (!kInterleave) {
+                load_a<D>(kbase, g.ks[2], kb_next, key_end, lane, nx);
+                blocks(a, kb, 0, NB);
+            } else {
+                const __bf16 *vbase = (const __bf16 *)g.v + b * g.vs[0] + h * g.vs[1];
+                load_a<D>(vbase, g.vs[2], kb, key_end, lane, nx);  // the value rows of these keys
+                __builtin_amdgcn_sched_barrier(0);
+                blocks(a, kb, 0, (NB + 1) / 2);
+                __builtin_amdgcn_sched_barrier(0);
+                float nu[kMB];
+                fragment_row_norms<D>(nx, nu);
+#pragma unroll
+                for (int mb = 0; mb < kMB; ++mb) {
+                    const int row = kb + mb * 32 + lane;
+                    if (lane < 32 && row < key_end) nu_g[(int64_t)z * g.n + row] = nu[mb];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                load_a<D>(kbase, g.ks[2], kb_next, key_end, lane, nx);
+                __builtin_amdgcn_sched_barrier(0);
+                blocks(a, kb, (NB + 1) / 2, NB);
+            }
+        };
         for (int i = 0; i < nsteps; i += 2) {
-            load_a<D>(kbase, g.ks[2], kb_of(i + 1), key_end, lane, a1);
-            step(a0, kb_of(i));
+            step(a0, a1, kb_of(i), kb_of(i + 1));
             if (i + 1 >= nsteps) break;
-            load_a<D>(kbase, g.ks[2], kb_of(i + 2), key_end, lane, a0);
-            step(a1, kb_of(i + 1));
+            step(a1, a0, kb_of(i + 1), kb_of(i + 2));
         }
 
+        PriorHalo<D> halo;  // travels while the statistics are reduced
+        if constexpr (kInterleave)
+            halo.request(g, (const __bf16 *)g.v + b * g.vs[0] + h * g.vs[1], key_begin, key_end, tid);
         // fold the two half-waves (same query column, different key rows); a statistic
         // (m, s, u) re-referenced to a maximum M >= m is (M, s f, (u + (m - M) s) f), f = 2^(m - M)
         auto reref = [](float m_, float mref, float &s_, float &u_) {
@@ -338,7 +478,12 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
             my_partial[tid] = M + log2f(sum);  // -inf for a row that saw no key
             if (ENT) partial_mean[my_off + tid] = sum > 0.f ? mref + mom / sum : 0.f;
         }
-        if (gamma) {
+        if constexpr (kInterleave) {
+            // (every wave's norms were written before the barriers of the reduction above)
+            const float gm = pool_norms_of_range<D>(g, z, key_begin, key_end, nu_g, halo, sNu,
+                                                    gamma, tid);
+            if (tid == 0) gblockmax[z * nparts + part] = gm;
+        } else if constexpr (PRIOR) {
             __syncthreads();  // the reduction buffer is done with
             const float gm = value_prior_of_range(g, b, h, z, key_begin, key_end, (float *)smem,
                                                   gamma, tid);
@@ -701,14 +846,17 @@ template <int D, int NB>
 static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, float *scores,
                            hipStream_t st, hipEvent_t mid, bool have_lse, bool fold_prior) {
     using S = TileSmem<D, NB>;
-    static_assert(S::bytes >= kPriorSmem, "the value-prior phase borrows the query tile's LDS");
+    static_assert(2 * (S::bytes + kPriorSmem) <= 160 * 1024, "two workgroups per CU");
+    static_assert(S::bytes >= kPriorTailSmem, "the prior's own phase borrows the query tile's LDS");
     char *w = (char *)ws;
     float *partial = (float *)(w + pl.off_partial);
     float *gamma = (float *)(w + pl.off_gamma);
     float *gbm = (float *)(w + pl.off_gblockmax);
+    float *nu = (float *)(w + pl.off_nu);
     static DeviceOnce once;
     const hipError_t ea = device_once(once, [] {
-        const void *kernels[6] = {(const void *)bf16_pass1_kernel<D, NB, false>,
+        const void *kernels[7] = {(const void *)bf16_pass1_kernel<D, NB, false>,
+                                  (const void *)bf16_pass1_kernel<D, NB, false, false, true>,
                                   (const void *)bf16_pass1_kernel<D, NB, true>,
                                   (const void *)bf16_pass1_kernel<D, NB, false, true>,
                                   (const void *)bf16_pass2_kernel<D, NB, true>,
@@ -716,7 +864,7 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
                                   (const void *)bf16_pass2_kernel<D, NB, false>};
         for (const void *kf : kernels) {
             const hipError_t e = hipFuncSetAttribute(
-                kf, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::bytes);
+                kf, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(S::bytes + kPriorSmem));
             if (e != hipSuccess) return e;
         }
         return hipSuccess;
@@ -731,11 +879,17 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
         if (g.rows)
             hipLaunchKernelGGL((bf16_pass1_kernel<D, NB, false, true>), xcd_grid(wgs1), dim3(256),
                                S::bytes, st, g, pl.n_qtiles, pl.nchunks, (int)wgs1, partial,
-                               (float *)nullptr, fold_prior ? gamma : nullptr, gbm);
+                               (float *)nullptr, (float *)nullptr, (float *)nullptr,
+                               (float *)nullptr);
+        else if (fold_prior)
+            hipLaunchKernelGGL((bf16_pass1_kernel<D, NB, false, false, true>), xcd_grid(wgs1),
+                               dim3(256), S::bytes + kPriorSmem, st, g, pl.n_qtiles, pl.nchunks, (int)wgs1,
+                               partial, (float *)nullptr, gamma, gbm, nu);
         else
             hipLaunchKernelGGL((bf16_pass1_kernel<D, NB, false>), xcd_grid(wgs1), dim3(256),
                                S::bytes, st, g, pl.n_qtiles, pl.nchunks, (int)wgs1, partial,
-                               (float *)nullptr, fold_prior ? gamma : nullptr, gbm);
+                               (float *)nullptr, (float *)nullptr, (float *)nullptr,
+                               (float *)nullptr);
     }
     const int stat_chunks = have_lse ? 1 : pl.nchunks;
     // the prior's per-range maxima: one per key chunk when pass 1 formed it, else per tile
@@ -783,7 +937,7 @@ static hipError_t launch_stats_t(const ScoreGeom &g, const PrefillPlan &pl, void
     const int64_t wgs1 = (int64_t)pl.nchunks * ((pl.n_qtiles + 1) / 2) * pl.Z;
     hipLaunchKernelGGL((bf16_pass1_kernel<D, NB, true>), xcd_grid(wgs1), dim3(256), S::bytes, st,
                        g, pl.n_qtiles, pl.nchunks, (int)wgs1, partial, partial_mean,
-                       (float *)nullptr, (float *)nullptr);
+                       (float *)nullptr, (float *)nullptr, (float *)nullptr);
     const hipError_t e1 = hipGetLastError();
     if (e1 != hipSuccess) return e1;
     hipLaunchKernelGGL(row_stats_merge_kernel, dim3((g.R + 255) / 256, pl.Z), dim3(256), 0, st, g,
