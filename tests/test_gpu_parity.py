@@ -99,6 +99,25 @@ def test_bf16_shapes(kw):
     check_prefill(w, decode_steps=3)
 
 
+@pytest.mark.parametrize("kw,pool", [
+    (dict(seq_len=1573, n_q_heads=8, n_kv_heads=2, window=64, budget=211, recent=19), 7),   # ragged
+    (dict(seq_len=2304, n_q_heads=4, n_kv_heads=1, window=64, budget=300, recent=64), 17),  # widest halo
+    (dict(seq_len=2304, n_q_heads=4, n_kv_heads=1, window=64, budget=300, recent=64), 19),  # own launch
+    (dict(seq_len=257, n_q_heads=8, n_kv_heads=2, window=57, budget=64, recent=8), 3),      # 1 key in step 2
+    (dict(seq_len=100, n_q_heads=4, n_kv_heads=1, window=64, budget=32, recent=4), 1),      # no pooling
+    (dict(seq_len=900, batch=2, head_dim=64, n_q_heads=16, n_kv_heads=2, window=32, budget=128,
+          recent=32), 5),                                                                   # d = 64
+    (dict(seq_len=5000, n_q_heads=12, n_kv_heads=3, window=60, budget=500, recent=60), 9),  # 240 rows
+])
+def test_bf16_full_query_tile_forms_the_value_prior_inside_pass_1(kw, pool):
+    """Tiles of 225 - 256 flattened rows (eight 32-row blocks): pass 1 loads the value rows
+    under its tile arithmetic and pools their norms itself; ragged ends, chunk borders, the
+    widest pooling halo it takes (17) and the width beyond it (a launch of its own)."""
+    w = synth.scaled(BF, name="bf16_full_tile", **kw)
+    assert 224 < (w.n_q_heads // w.n_kv_heads) * w.window <= 256
+    check_prefill(w, Opts(pool=pool), decode_steps=2)
+
+
 def test_c2_llama2_7b_layer():
     gpu, ref, excused = check_prefill(synth.C2, decode_steps=4)
     print("C2 excused near-ties:", excused)
