@@ -246,7 +246,8 @@ static DecodePlan plan_decode(const aha_params *p) {
     } else {
         // one workgroup per head: dots and output probabilities of all live slots in LDS
         const size_t w_floats = (size_t)(G * live > 16 * G * p->head_dim ? G * live : 16 * G * p->head_dim);
-        if ((w_floats + (size_t)G * live) * 4 > kDecodeSingleLds) pl.fits = false;
+        const size_t q_tile = p->dtype == AHA_BF16 && G >= kDecodeMfmaGroup ? kDecodeQTileBytes(p->head_dim) : 0;
+        if ((w_floats + (size_t)G * live) * 4 + q_tile > kDecodeSingleLds) pl.fits = false;
     }
     // value prior inside the loop: the live slots' value norms and their maximum per head
     if (p->decode_value_prior)

@@ -125,6 +125,10 @@ struct DecodeGeom {
 constexpr int kMaxDecodeSplit = 64;  // most workgroups a head's slots are split over
 constexpr size_t kDecodeSplitLds = 64 * 1024;    // dynamic LDS of a split workgroup, at most
 constexpr size_t kDecodeSingleLds = 150 * 1024;  // dynamic LDS of the one-workgroup-per-head kernel, at most
+// bf16 caches with at least this many query heads per KV head: the one-workgroup-per-head
+// kernel forms the dots on the matrix core, from a query tile of 32 padded rows in LDS
+constexpr int kDecodeMfmaGroup = 5;
+constexpr size_t kDecodeQTileBytes(int d) { return (size_t)32 * (d + 8) * 2; }
 
 struct DecodePlan {
     int nsplit;      // 1: single-launch path

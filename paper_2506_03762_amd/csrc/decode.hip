@@ -6,6 +6,8 @@
 // the raw dots of all live slots stay in LDS, from which both the attention
 // output (scale 1/sqrt(d)) and the score update (adaptive scale) are formed.
 // No cross-workgroup exchange is needed: the whole head lives in one CU.
+// With five or more query heads per KV head (bf16) the dots of whole 32-slot
+// blocks come from the matrix core instead of per-query vector-ALU dots.
 #include "aha_dev.h"
 #include "aha_host.h"
 
@@ -72,10 +74,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     constexpr int LPR = D / CH;          // lanes per row
     constexpr int RP = kDecThreads / LPR;  // rows per sweep
     constexpr int ROWB = D * ESIZE;
+    constexpr bool kMfmaDots = ESIZE == 2 && G >= kDecodeMfmaGroup;  // dots on the matrix core
 
     extern __shared__ __attribute__((aligned(16))) float dsm[];
-    float *s_w = dsm;              // [G][live] raw dots; later [waves][G][D] partial outputs
-    float *s_p = dsm + w_floats;   // [G][live] output probabilities
+    // (matrix-core dots: the query tile, 32 padded rows, comes first)
+    float *s_w = dsm + (kMfmaDots ? kDecodeQTileBytes(D) / 4 : 0);  // [G][live] raw dots; later [waves][G][D] partial outputs
+    float *s_p = s_w + w_floats;   // [G][live] output probabilities
     __shared__ float s_red[kDecWaves][2 * G];
     __shared__ unsigned long long s_key[kDecWaves];
     __shared__ int s_victim;
@@ -95,10 +99,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     // waits for the free-slot index.
     const u32x4 knw = *(const u32x4 *)((const char *)g.k_new + (int64_t)z * ROWB + sub * 16);
     const u32x4 vnw = *(const u32x4 *)((const char *)g.v_new + (int64_t)z * ROWB + sub * 16);
-    u32x4 qw[G];
+    u32x4 qw[G];  // (unused where the dots go through the matrix core)
+    if constexpr (!kMfmaDots) {
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi)
-        qw[gi] = *(const u32x4 *)((const char *)g.q + ((int64_t)(b * g.Hq + h * G + gi)) * ROWB + sub * 16);
+        for (int gi = 0; gi < G; ++gi)
+            qw[gi] = *(const u32x4 *)((const char *)g.q + ((int64_t)(b * g.Hq + h * G + gi)) * ROWB + sub * 16);
+    }
 
     // value prior inside the loop (an option): the slots' norms and their maximum come from
     // a launch of their own (decode_value_norms_kernel)
@@ -109,48 +115,125 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     const int p_first = posz[min(tid, live - 1)];
 
     // ---- raw dots over the live slots (the new key stands in for slot fs) ----
-    // cache rows per thread requested before the first is used (fewer for wide groups,
-    // whose queries and outputs fill the 128 registers a thread of this workgroup has)
-    constexpr int PF = G <= 2 ? 8 : G <= 4 ? 4 : 2;
-    u32x4 kpf[PF];
-#pragma unroll
-    for (int u = 0; u < PF; ++u)
-        kpf[u] = *(const u32x4 *)(kcz + (int64_t)min(rg + u * RP, live - 1) * ROWB + sub * 16);
     float mloc[G];
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) mloc[gi] = -INFINITY;
-    auto dots = [&](int s, u32x4 kw) {
+    // dots of the 16-byte chunk `kw` of slot s with the queries' chunks `qw`, summed over the
+    // lanes of the row
+    auto dots = [&](int s, u32x4 kw, const u32x4 (&qc)[G]) {
         if (s == fs) {
             kw = knw;
             *(u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16) = kw;
         }
 #pragma unroll
         for (int gi = 0; gi < G; ++gi) {
-            float w = chunk_dot<ESIZE>(kw, qw[gi]);
+            float w = chunk_dot<ESIZE>(kw, qc[gi]);
             w = reduce_lanes<1, LPR>(w, OpSum{});  // over the lanes of the row
             if (sub == 0) s_w[gi * live + s] = w;
             mloc[gi] = fmaxf(mloc[gi], w);
         }
     };
-#pragma unroll
-    for (int u = 0; u < PF; ++u)
-        if (rg + u * RP < live) dots(rg + u * RP, kpf[u]);
-    // the rest in batches of PF rows per thread, requested together (written out by hand:
-    // a loop with lane exchanges in its body is not unrolled by the compiler).  (A rolling
-    // window - every used row's registers given at once to the row PF sweeps further on -
-    // measured 10 % slower than whole batches.)
-    for (int sb = rg + PF * RP; sb < live; sb += PF * RP) {
+    if constexpr (!kMfmaDots) {
+        // cache rows per thread requested before the first is used
+        constexpr int PF = G <= 2 ? 8 : 4;
+        u32x4 kpf[PF];
 #pragma unroll
         for (int u = 0; u < PF; ++u)
-            kpf[u] = *(const u32x4 *)(kcz + (int64_t)min(sb + u * RP, live - 1) * ROWB + sub * 16);
+            kpf[u] = *(const u32x4 *)(kcz + (int64_t)min(rg + u * RP, live - 1) * ROWB + sub * 16);
 #pragma unroll
         for (int u = 0; u < PF; ++u)
-            if (sb + u * RP < live) dots(sb + u * RP, kpf[u]);
+            if (rg + u * RP < live) dots(rg + u * RP, kpf[u], qw);
+        // the rest in batches of PF rows per thread, requested together (written out by hand:
+        // a loop with lane exchanges in its body is not unrolled by the compiler).  (A rolling
+        // window - every used row's registers given at once to the row PF sweeps further on -
+        // measured 10 % slower than whole batches.)
+        for (int sb = rg + PF * RP; sb < live; sb += PF * RP) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u)
+                kpf[u] = *(const u32x4 *)(kcz + (int64_t)min(sb + u * RP, live - 1) * ROWB + sub * 16);
+#pragma unroll
+            for (int u = 0; u < PF; ++u)
+                if (sb + u * RP < live) dots(sb + u * RP, kpf[u], qw);
+        }
+    } else {
+        // Wide groups (bf16): with G queries per key row the dots are a small matrix product,
+        // S^T = K Q^T, and per-query vector-ALU dots with their lane reductions cost more than
+        // the key stream (and, with the value phase's G x 8 accumulators, more registers than
+        // a thread of this workgroup has).  Blocks of 32 slots go through
+        // v_mfma_f32_32x32x16_bf16 - slots on M, the G queries on N (columns >= G are zero) -
+        // with the key fragments loaded straight into registers, a lane holding one half of a
+        // row, and the queries read from a tile in LDS.  Whole blocks are dealt to the waves
+        // round-robin; the slots past the last whole block and the free slot (whose cache row
+        // is stale: the new key stands in for it) are done by 16-lane groups on the vector ALU
+        // afterwards.
+        constexpr int QLD = D + 8;  // padded row of the query tile: conflict-free b128 reads
+        __bf16 *sQ = (__bf16 *)dsm;
+        for (int i = tid; i < 32 * LPR; i += kDecThreads) {
+            const int n = i / LPR, c = i % LPR;
+            u32x4 w = {0u, 0u, 0u, 0u};
+            if (n < G)
+                w = *(const u32x4 *)((const char *)g.q + ((int64_t)(b * g.Hq + h * G + n)) * ROWB + c * 16);
+            *(u32x4 *)(sQ + n * QLD + c * 8) = w;
+        }
+        // the leftover slots: group rg of 16 lanes takes slot nblk * 32 + rg, the group behind
+        // them the free slot (unless it is one of the leftover slots); requested now, used last
+        const int nblk = live / 32, ntail = live - nblk * 32;
+        const int vrow = rg < ntail ? nblk * 32 + rg : (rg == ntail && fs < nblk * 32 ? fs : -1);
+        u32x4 kv_row = {0u, 0u, 0u, 0u};
+        if (vrow >= 0) kv_row = *(const u32x4 *)(kcz + (int64_t)vrow * ROWB + sub * 16);
+        auto load_block = [&](int blk, bf16x8 (&dst)[D / 16]) {
+            const int row = min(min(blk, nblk - 1) * 32 + (lane & 31), live - 1);
+            const char *pr = kcz + (int64_t)row * ROWB + (lane >> 5) * 16;
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks) dst[ks] = *(const bf16x8 *)(pr + ks * 32);
+        };
+        auto block_dots = [&](int blk, const bf16x8 (&a)[D / 16]) {
+            f32x16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+            const __bf16 *bp = sQ + (lane & 31) * QLD + (lane >> 5) * 8;
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], *(const bf16x8 *)(bp + ks * 16), acc, 0, 0, 0);
+            // lane: query column lane % 32, slots 8 * (v / 4) + 4 * (lane / 32) + v % 4 of the block
+            if ((lane & 31) < G) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    s_w[(lane & 31) * live + blk * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)] = acc[v];
+            }
+        };
+        bf16x8 a0[D / 16], a1[D / 16];
+        if (nblk > 0) load_block(wave, a0);
+        __syncthreads();  // the query tile is in LDS
+        // (the loads are issued unconditionally, clamped to the last whole block: behind a
+        // branch the compiler would wait for a prefetch before the block in hand)
+        for (int blk = wave; blk < nblk; blk += 2 * kDecWaves) {
+            load_block(blk + kDecWaves, a1);
+            block_dots(blk, a0);
+            if (blk + kDecWaves >= nblk) break;
+            load_block(blk + 2 * kDecWaves, a0);
+            block_dots(blk + kDecWaves, a1);
+        }
+        __syncthreads();  // the blocks' dots are written (the free slot's among them: stale)
+        // (the lane reductions inside `dots` stay inside a row's group of lanes, which is
+        // active or idle as a whole)
+        if (vrow >= 0) {
+            u32x4 qc[G];
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi) qc[gi] = *(const u32x4 *)(sQ + gi * QLD + sub * 8);
+            dots(vrow, kv_row, qc);
+        }
+        __syncthreads();
+        // the maxima of the rows' dots, from LDS (the matrix blocks left none in registers)
+        for (int s = tid; s < live; s += kDecThreads) {
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi) mloc[gi] = fmaxf(mloc[gi], s_w[gi * live + s]);
+        }
     }
     // the first value rows travel while the softmax statistics are formed (requesting more
     // of them here, or already behind the last batch of key rows, measured 6 % slower: the
     // key and value streams of the 256 workgroups then mix in memory)
-    constexpr int VPF = PF;
+    constexpr int VPF = G <= 2 ? 8 : G <= 6 ? 4 : 2;  // (wide groups: the G x 8 accumulators leave room for few)
     u32x4 vpf[VPF];
 #pragma unroll
     for (int u = 0; u < VPF; ++u)
@@ -256,7 +339,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
 #pragma unroll
     for (int u = 0; u < VPF; ++u)
         if (rg + u * RP < live) weigh(rg + u * RP, vpf[u]);
-#pragma unroll 8
+    // (rows in flight per thread: as many as the registers beside the G x CH accumulators allow)
+    constexpr int VU = G <= 4 ? 8 : G <= 6 ? 4 : 2;
+#pragma unroll VU
     for (int s = rg + VPF * RP; s < live; s += RP)
         weigh(s, *(const u32x4 *)(vcz + (int64_t)s * ROWB + sub * 16));
     float *s_o = s_w;  // [waves][G][D]
@@ -682,7 +767,8 @@ static hipError_t launch_g(const DecodeGeom &g, const DecodePlan &pl, void *ws, 
         return hipGetLastError();
     }
     const int w_floats = max(g.G * live, kDecWaves * g.G * D);
-    const size_t smem = (size_t)(w_floats + g.G * live) * sizeof(float);
+    const size_t smem = (size_t)(w_floats + g.G * live) * sizeof(float) +
+                        (ESIZE == 2 && g.G >= kDecodeMfmaGroup ? kDecodeQTileBytes(D) : 0);
     dim3 grid(g.batch * g.Hkv);
 #define AHA_DEC(GG)                                                                              \
     {                                                                                            \

@@ -353,6 +353,24 @@ def test_decode_many_heads_single_launch_path():
     check_prefill(w, decode_steps=5)
 
 
+@pytest.mark.parametrize("G,d,budget,recent", [
+    (3, 128, 70, 8),      # two whole 32-slot blocks and seven leftover slots
+    (4, 128, 31, 4),      # live slots = one block exactly: the free slot sits inside it
+    (8, 128, 20, 3),      # fewer live slots than a block: no matrix block at all
+    (8, 128, 160, 16),    # five blocks over sixteen waves, one leftover slot
+    (8, 64, 95, 9),       # d = 64
+    (5, 128, 64, 64),     # every slot protected but the new one's predecessors
+])
+def test_decode_wide_groups_single_launch_path(G, d, budget, recent):
+    """Grouped-query attention with three or more query heads per KV head on the
+    one-workgroup-per-head path (bf16): the dots of whole 32-slot blocks come from the matrix
+    core, the leftover slots and the free slot from the vector ALU.  Many steps, so that the free
+    slot wanders through blocks and leftovers."""
+    w = synth.scaled(BF, name="bf16_decode_wide_gqa", seq_len=200, head_dim=d, n_q_heads=8 * G,
+                     n_kv_heads=8, budget=budget, recent=recent, window=16, batch=16)
+    check_prefill(w, decode_steps=12)
+
+
 def test_decode_fixed_scale_and_no_recent_fp32():
     w = synth.scaled(synth.C1, name="f32_decode", budget=60, recent=0, window=16)
     check_prefill(w, Opts(scale_mode=SCALE_FIXED, fixed_scale=0.125), decode_steps=20)
