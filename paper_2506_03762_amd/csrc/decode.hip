@@ -583,7 +583,8 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
                                                        g.logical_pos, g.budget, D)
                                   : row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor,
                                                    g.logical_pos, g.budget, D);
-    constexpr int NT = kMergeThreads, U = 4, XB = 32;
+    // slots per thread and batch fetched together (fewer for wide groups: G dots per slot)
+    constexpr int NT = kMergeThreads, U = G <= 4 ? 4 : 2, XB = 32;
 
     // Latency-bound like stage 1: every first-use load is requested here, before any result
     // is needed - the free slot, the splits' statistics, the first batch of stored dots with
@@ -618,36 +619,40 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
                 pr[u] = g.logical_pos - 1;
             }
     };
-    const bool output_role = blockIdx.y == 0;  // workgroup-uniform
-    if (!output_role) fetch(0);
-    const int ogi = tid / D, oc = tid % D;  // this thread's output element (tid < G * D)
-    float x[XB];
+    // The splits' statistics go to LDS and every wave folds the maxima by itself (one split
+    // per lane).  (Written out in both roles, so that neither role's registers stay live
+    // through the other's code: together they do not fit a thread of this workgroup.)
+    auto fold_maxima = [&](float (&mx)[G]) {
+        if (tid < nsplit * G) {
+            s_pm[tid / G][tid % G] = my_pm;
+            s_pz[tid / G][tid % G] = my_pz;
+        }
+        __syncthreads();
 #pragma unroll
-    for (int u = 0; u < XB; ++u)
-        x[u] = (output_role && tid < G * D && u < nsplit) ? part[(u * G + ogi) * (D + 2) + oc] : 0.f;
-
-    if (tid < nsplit * G) {
-        s_pm[tid / G][tid % G] = my_pm;
-        s_pz[tid / G][tid % G] = my_pz;
-    }
-    __syncthreads();
-    // every wave folds the splits' maxima by itself (one split per lane)
-    float mx[G];
+        for (int gi = 0; gi < G; ++gi) mx[gi] = wave_max(lane < nsplit ? s_pm[lane][gi] : -INFINITY);
+    };
+    if (blockIdx.y == 0) {  // (workgroup-uniform) the attention output
+        const int ogi = tid / D, oc = tid % D;  // this thread's output element (tid < G * D)
+        float x[XB];
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) mx[gi] = wave_max(lane < nsplit ? s_pm[lane][gi] : -INFINITY);
-
-    if (output_role) {
+        for (int u = 0; u < XB; ++u)
+            x[u] = (tid < G * D && u < nsplit) ? part[(u * G + ogi) * (D + 2) + oc] : 0.f;
+        float mx[G];
+        fold_maxima(mx);
         if (tid >= G * D) return;
+        float mxo = mx[0];  // this thread's head
+#pragma unroll
+        for (int gi = 1; gi < G; ++gi) mxo = ogi == gi ? mx[gi] : mxo;
         float num = 0.f, den = 0.f;
 #pragma unroll
         for (int u = 0; u < XB; ++u)
             if (u < nsplit) {
-                const float sc = exp2f((s_pm[u][ogi] - mx[ogi]) * c_out);
+                const float sc = exp2f((s_pm[u][ogi] - mxo) * c_out);
                 num = fmaf(x[u], sc, num);
                 den = fmaf(s_pz[u][ogi], sc, den);
             }
         for (int sp = XB; sp < nsplit; ++sp) {
-            const float sc = exp2f((s_pm[sp][ogi] - mx[ogi]) * c_out);
+            const float sc = exp2f((s_pm[sp][ogi] - mxo) * c_out);
             num = fmaf(part[(sp * G + ogi) * (D + 2) + oc], sc, num);
             den = fmaf(s_pz[sp][ogi], sc, den);
         }
@@ -659,6 +664,9 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
             ((float *)g.out)[oi] = v;
         return;
     }
+    fetch(0);
+    float mx[G];
+    fold_maxima(mx);
     // score softmax over all live slots, from the stored raw dots; four slots per thread
     // and batch are fetched together so that the loads overlap
     float zs[G];
