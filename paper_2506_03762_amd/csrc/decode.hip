@@ -267,8 +267,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
 #pragma unroll
         for (int gi = 0; gi < G; ++gi) {
             const float d = s_w[gi * live + s] - mx[gi];
-            zo[gi] += exp2f(d * c_out);
-            zs[gi] += exp2f(d * c_sc);
+            zo[gi] += fast_exp2(d * c_out);
+            zs[gi] += fast_exp2(d * c_sc);
         }
     }
 #pragma unroll
@@ -294,8 +294,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
 #pragma unroll
         for (int gi = 0; gi < G; ++gi) {
             const float d = s_w[gi * live + s] - mx[gi];
-            s_p[gi * live + s] = exp2f(d * c_out) / zo[gi];
-            add += exp2f(d * c_sc) / zs[gi];
+            s_p[gi * live + s] = fast_exp2(d * c_out) / zo[gi];
+            add += fast_exp2(d * c_sc) / zs[gi];
         }
         if (g.value_prior) add *= prior_factor(ws_nu[(int64_t)z * live + s], ginv);
         const float f = (s == fs ? 0.f : (s == tid ? f_first : fcz[s])) + add;
@@ -459,7 +459,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
             w = reduce_lanes<1, LPR>(w, OpSum{});  // over the lanes of the row
             if (sub == 0) {
                 s_p[gi * sps + s - s0] = w;
-                ws_w[((int64_t)z * G + gi) * live + s] = w;
+                ws_w[((int64_t)z * live + s) * G + gi] = w;  // [head][slot][query]: a slot's dots together
             }
             mloc[gi] = fmaxf(mloc[gi], w);
         }
@@ -497,7 +497,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
     for (int s = s0 + tid; s < s1; s += 256) {
 #pragma unroll
         for (int gi = 0; gi < G; ++gi) {
-            const float e = exp2f((s_p[gi * sps + s - s0] - mx[gi]) * c_out);
+            const float e = fast_exp2((s_p[gi * sps + s - s0] - mx[gi]) * c_out);
             s_p[gi * sps + s - s0] = e;
             zo[gi] += e;
         }
@@ -584,7 +584,9 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
                                   : row_scale_log2(g.scale_mode, g.fixed_scale, g.lambda_floor,
                                                    g.logical_pos, g.budget, D);
     // slots per thread and batch fetched together (fewer for wide groups: G dots per slot)
-    constexpr int NT = kMergeThreads, U = G <= 4 ? 4 : 2, XB = 32;
+    // slots per thread and batch (score role); splits whose outputs are requested up front
+    // (output role: fewer for wide groups, where every split's address takes registers)
+    constexpr int NT = kMergeThreads, U = 4, XB = G <= 4 ? 32 : 16;
 
     // Latency-bound like stage 1: every first-use load is requested here, before any result
     // is needed - the free slot, the splits' statistics, the first batch of stored dots with
@@ -596,16 +598,38 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
         my_pm = part[tid * (D + 2) + D];  // tid = split * G + head
         my_pz = part[tid * (D + 2) + D + 1];
     }
-    float wr[U][G], fr[U], nur[U];
+    // The score role goes through the query heads in groups of at most four (a slot's dots
+    // lie together in the workspace: one 16-byte load per slot and whole group): with more
+    // heads at once the per-head copies of four slots do not fit a thread of this workgroup.
+    constexpr int GH = G < 4 ? G : 4, NG = (G + GH - 1) / GH;
+    float wr[U][GH], fr[U], nur[U];
     int pr[U];
-    auto fetch = [&](int base) {
+    // dots of head group `grp` (heads grp * GH ..; past G: -inf) of this thread's U slots
+    auto fetch_dots = [&](int base, int grp) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int s = base + tid + u * NT;
             const bool ok = s < live;
+            // (live * G floats of a head start 16-byte aligned when G is a multiple of four:
+            // the workspace is 256-byte aligned)
+            const float *wp = ws_w + ((int64_t)z * live + (ok ? s : 0)) * G + grp * GH;
+            if constexpr (G % 4 == 0) {
+                const f32x4 w4 = *(const f32x4 *)wp;
 #pragma unroll
-            for (int gi = 0; gi < G; ++gi)
-                wr[u][gi] = ok ? ws_w[((int64_t)z * G + gi) * live + s] : -INFINITY;
+                for (int c = 0; c < 4; ++c) wr[u][c] = ok ? w4[c] : -INFINITY;
+            } else {
+#pragma unroll
+                for (int c = 0; c < GH; ++c)
+                    wr[u][c] = ok && grp * GH + c < G ? wp[grp * GH + c < G ? c : 0] : -INFINITY;
+            }
+        }
+    };
+    auto fetch = [&](int base) {  // the first group's dots, the scores, positions, value norms
+        fetch_dots(base, 0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = base + tid + u * NT;
+            const bool ok = s < live;
             fr[u] = ok ? fcz[s] : 0.f;
             pr[u] = ok ? posz[s] : 0x7fffffff;
             nur[u] = (ok && g.value_prior) ? ws_nu[(int64_t)z * live + s] : 0.f;
@@ -647,12 +671,13 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
 #pragma unroll
         for (int u = 0; u < XB; ++u)
             if (u < nsplit) {
-                const float sc = exp2f((s_pm[u][ogi] - mxo) * c_out);
+                const float sc = fast_exp2((s_pm[u][ogi] - mxo) * c_out);
                 num = fmaf(x[u], sc, num);
                 den = fmaf(s_pz[u][ogi], sc, den);
             }
+#pragma unroll 8
         for (int sp = XB; sp < nsplit; ++sp) {
-            const float sc = exp2f((s_pm[sp][ogi] - mxo) * c_out);
+            const float sc = fast_exp2((s_pm[sp][ogi] - mxo) * c_out);
             num = fmaf(part[(sp * G + ogi) * (D + 2) + oc], sc, num);
             den = fmaf(s_pz[sp][ogi], sc, den);
         }
@@ -672,17 +697,23 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
     float zs[G];
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) zs[gi] = 0.f;
-    const bool one_batch = live <= U * NT;  // then the values stay in registers for pass two
+    // one batch and one head group: the values stay in registers for pass two
+    const bool keep = live <= U * NT && NG == 1;
     for (int base = 0; base < live; base += U * NT) {
         if (base) fetch(base);
-
-        // (entries past the last slot are skipped, not fed as -inf: a scale of exactly 0
-        // would turn them into 0 * inf)
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (base + tid + u * NT < live)
+        for (int grp = 0; grp < NG; ++grp) {
+            if (grp) fetch_dots(base, grp);
+            // (entries past the last slot are skipped, not fed as -inf: a scale of exactly 0
+            // would turn them into 0 * inf)
 #pragma unroll
-                for (int gi = 0; gi < G; ++gi) zs[gi] += exp2f((wr[u][gi] - mx[gi]) * c_sc);
+            for (int u = 0; u < U; ++u)
+                if (base + tid + u * NT < live)
+#pragma unroll
+                    for (int c = 0; c < GH; ++c)
+                        if (grp * GH + c < G)
+                            zs[grp * GH + c] += fast_exp2((wr[u][c] - mx[grp * GH + c]) * c_sc);
+        }
     }
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) {
@@ -701,17 +732,27 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(DecodeGeom 
     unsigned long long best = ~0ull;
     int best_slot = -1;
     for (int base = 0; base < live; base += U * NT) {
-        if (!one_batch) fetch(base);
+        if (!keep) fetch(base);
         patch_free_slot(base);
+        float add[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) add[u] = 0.f;
+#pragma unroll
+        for (int grp = 0; grp < NG; ++grp) {
+            if (grp) fetch_dots(base, grp);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int c = 0; c < GH; ++c)
+                    if (grp * GH + c < G)
+                        add[u] += fast_exp2((wr[u][c] - mx[grp * GH + c]) * c_sc) * zs[grp * GH + c];
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int s = base + tid + u * NT;
             if (s >= live) continue;
-            float add = 0.f;
-#pragma unroll
-            for (int gi = 0; gi < G; ++gi) add += exp2f((wr[u][gi] - mx[gi]) * c_sc) * zs[gi];
-            if (g.value_prior) add *= prior_factor(nur[u], ginv);
-            const float f = fr[u] + add;
+            if (g.value_prior) add[u] *= prior_factor(nur[u], ginv);
+            const float f = fr[u] + add[u];
             fcz[s] = f;
             const int ps = pr[u];
             if (s == fs) posz[s] = ps;
