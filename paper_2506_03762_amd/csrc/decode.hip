@@ -282,8 +282,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
         float a = 0.f, c = 0.f;
 #pragma unroll
         for (int w = 0; w < kDecWaves; ++w) { a += s_red[w][2 * gi]; c += s_red[w][2 * gi + 1]; }
-        zo[gi] = a;
-        zs[gi] = c;
+        zo[gi] = 1.f / a;  // (reciprocals: one division per head instead of two per slot)
+        zs[gi] = 1.f / c;
     }
 
     // ---- probabilities, running score, eviction candidate ----
@@ -294,8 +294,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
 #pragma unroll
         for (int gi = 0; gi < G; ++gi) {
             const float d = s_w[gi * live + s] - mx[gi];
-            s_p[gi * live + s] = fast_exp2(d * c_out) / zo[gi];
-            add += fast_exp2(d * c_sc) / zs[gi];
+            s_p[gi * live + s] = fast_exp2(d * c_out) * zo[gi];
+            add += fast_exp2(d * c_sc) * zs[gi];
         }
         if (g.value_prior) add *= prior_factor(ws_nu[(int64_t)z * live + s], ginv);
         const float f = (s == fs ? 0.f : (s == tid ? f_first : fcz[s])) + add;
