@@ -244,11 +244,16 @@ def test_scores_from_lse_follow_the_given_normaliser():
     assert np.max(np.abs(got[:, 0] - oracle.prefill_scores(*inputs, cfg)[:, 0])) > 1e-3
 
 
-def test_strided_inputs_token_major_layout():
+@pytest.mark.parametrize("w", [
+    BF,
+    # a full 256-row tile: pass 1 loads the value rows with the key fragments' addressing
+    synth.scaled(BF, name="bf16_full_tile_strided", seq_len=1100, n_q_heads=8, n_kv_heads=2,
+                 window=64, budget=150, recent=64),
+], ids=lambda w: w.name)
+def test_strided_inputs_token_major_layout(w):
     """Q/K/V stored [b, n, h, d] and passed by strides give the same result."""
     import torch
     from paper_2506_03762_amd import binding as B
-    w = BF
     Q, K, V = synth.make_prefill(w)
     opts = Opts()
     dense = H.run_prefill_gpu(w, opts, (Q, K, V))
