@@ -239,6 +239,7 @@ def main():
 
     if not args.no_extras:
         result["decode_c4"] = bench_decode_c4(torch, B, synth, H, K_STEPS)
+        result["decode_c4_grouped_query"] = bench_decode_gqa(torch, B)
         result["full_accumulation_c2"] = bench_full_c2(torch, B, synth, H, max(5, K_STEPS // 5))
         result["prefill_c5_layer"] = bench_c5_layer(torch, B, synth, H, max(5, K_STEPS // 5))
         result["scores_from_lse_c3"] = bench_lse_c3(torch, B, H, w, p, q, k, v, scores, ws, K_STEPS)
@@ -308,6 +309,53 @@ def bench_decode_c4(torch, B, synth, H, steps):
             "cache_defeated": {"decode_step_us": us_cold, "copies": ncopies,
                                "achieved": alg / (us_cold * 1e-6) / 1e9,
                                "frac": alg / (us_cold * 1e-6) / 1e9 / HBM_PEAK_GBS}}
+
+
+def bench_decode_gqa(torch, B):
+    """The batched decode size (256 KV heads x budget 1024, bf16) with grouped-query attention:
+    4 and 8 query heads per KV head.  Caches filled with random rows (timing only), four in
+    rotation, steps launched back to back."""
+    res = {}
+    bsz, hk, d, budget = 8, 32, 128, 1024
+    g = torch.Generator(device="cuda"); g.manual_seed(99)
+    for G in (4, 8):
+        hq = hk * G
+        p = B.Params(batch=bsz, n_q_heads=hq, n_kv_heads=hk, head_dim=d, seq_len=0, window=0,
+                     budget=budget, recent=64)
+        caches = []
+        for _ in range(4):
+            c = B.CompactCache.empty(p)
+            c.k.copy_(torch.randn(c.k.shape, device="cuda", generator=g)); c.v.copy_(c.k)
+            c.scores.uniform_(); c.free_slot.fill_(budget)
+            c.pos.copy_(torch.arange(budget + 1, dtype=torch.int32, device="cuda")
+                        .expand(bsz, hk, budget + 1))
+            c.pos[:, :, budget] = -1
+            caches.append(c)
+        q = torch.randn((bsz, hq, d), device="cuda", generator=g).to(torch.bfloat16)
+        kv = torch.randn((bsz, hk, d), device="cuda", generator=g).to(torch.bfloat16)
+        out = torch.empty_like(q)
+        ws = torch.empty(max(256, B.workspace_bytes(p)), dtype=torch.uint8, device="cuda")
+        alg = bsz * hk * (2 * (budget + 1) * d * 2 + 8 * (budget + 1) + 2 * d * 2) + 2 * bsz * hq * d * 2
+
+        def run(steps):
+            e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+            for t in range(steps):
+                c = caches[t % 4]
+                if t == 16:
+                    e0.record()
+                B.aha_decode_step(p, q, kv, kv, c.k, c.v, c.scores, c.pos, c.free_slot,
+                                  budget + 100 + t // 4, out, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / (steps - 16)
+
+        run(32)
+        us = run(144)
+        res["group_%d" % G] = {"decode_step_us": us, "alg_bytes": alg,
+                               "hbm_frac": alg / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+    res["note"] = ("random cache contents, four caches in rotation; 8 query heads per KV head: "
+                   "dots on the matrix core")
+    return res
 
 
 def bench_full_c2(torch, B, synth, H, steps):

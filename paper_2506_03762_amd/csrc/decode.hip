@@ -125,13 +125,20 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
             kw = knw;
             *(u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16) = kw;
         }
+        // (all heads' dots and lane reductions first, one guarded block of stores after them:
+        // a store per head in between would fence the independent reduction chains apart,
+        // and each chain alone waits out the data hazards between its lane exchanges)
+        float w[G];
 #pragma unroll
-        for (int gi = 0; gi < G; ++gi) {
-            float w = chunk_dot<ESIZE>(kw, qc[gi]);
-            w = reduce_lanes<1, LPR>(w, OpSum{});  // over the lanes of the row
-            if (sub == 0) s_w[gi * live + s] = w;
-            mloc[gi] = fmaxf(mloc[gi], w);
+        for (int gi = 0; gi < G; ++gi) w[gi] = chunk_dot<ESIZE>(kw, qc[gi]);
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) w[gi] = reduce_lanes<1, LPR>(w[gi], OpSum{});  // over the lanes of the row
+        if (sub == 0) {
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi) s_w[gi * live + s] = w[gi];
         }
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) mloc[gi] = fmaxf(mloc[gi], w[gi]);
     };
     if constexpr (!kMfmaDots) {
         // cache rows per thread requested before the first is used
@@ -453,16 +460,22 @@ __global__ __launch_bounds__(256) void decode_split_kernel(DecodeGeom g, int nsp
             kw = knw;
             *(u32x4 *)(kcz + (int64_t)s * ROWB + sub * 16) = kw;
         }
+        // (dots and lane reductions of all heads first, then one guarded block of stores: the
+        // independent reduction chains interleave instead of waiting out their hazards)
+        float w[G];
 #pragma unroll
-        for (int gi = 0; gi < G; ++gi) {
-            float w = chunk_dot<ESIZE>(kw, qw[gi]);
-            w = reduce_lanes<1, LPR>(w, OpSum{});  // over the lanes of the row
-            if (sub == 0) {
-                s_p[gi * sps + s - s0] = w;
-                ws_w[((int64_t)z * live + s) * G + gi] = w;  // [head][slot][query]: a slot's dots together
+        for (int gi = 0; gi < G; ++gi) w[gi] = chunk_dot<ESIZE>(kw, qw[gi]);
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) w[gi] = reduce_lanes<1, LPR>(w[gi], OpSum{});  // over the lanes of the row
+        if (sub == 0) {
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi) {
+                s_p[gi * sps + s - s0] = w[gi];
+                ws_w[((int64_t)z * live + s) * G + gi] = w[gi];  // [head][slot][query]: a slot's dots together
             }
-            mloc[gi] = fmaxf(mloc[gi], w);
         }
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) mloc[gi] = fmaxf(mloc[gi], w[gi]);
     };
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
