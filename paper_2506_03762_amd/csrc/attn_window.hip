@@ -38,27 +38,25 @@ struct AttnSmem {
 
 // The wave's 64 value rows [kb, kb + 64) -> its private LDS copy, row-major, 16-byte chunks,
 // the lanes of a row adjacent.  Rows at or past `end` re-read row end - 1 (their
-// probabilities are zero).  Two batches of eight loads, so that 32 registers suffice.
+// probabilities are zero).  Request (global memory -> registers) and commit (-> LDS) are
+// apart, so that the logits and the softmax of the step cover the round trip to memory.
 template <int D>
-__device__ __forceinline__ void stage_values(const __bf16 *vbase, int64_t v_tstride, int kb,
-                                             int end, int lane, __bf16 *sV) {
-    constexpr int CPR = D / 8, RPI = 64 / CPR, NI = kWaveKeys / RPI, LDV = AttnSmem<D>::LDV;
-    const int r0 = lane / CPR, c = lane % CPR;
+struct ValueRows {
+    static constexpr int CPR = D / 8, RPI = 64 / CPR, NI = kWaveKeys / RPI, LDV = AttnSmem<D>::LDV;
+    u32x4 w[NI];
+    __device__ __forceinline__ void request(const __bf16 *vbase, int64_t v_tstride, int kb, int end,
+                                            int lane) {
+        const int r0 = lane / CPR, c = lane % CPR;
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        u32x4 w[NI / 2];
-#pragma unroll
-        for (int t = 0; t < NI / 2; ++t) {
-            const int row = (half * (NI / 2) + t) * RPI + r0;
-            w[t] = *(const u32x4 *)(vbase + (int64_t)min(kb + row, end - 1) * v_tstride + c * 8);
-        }
-#pragma unroll
-        for (int t = 0; t < NI / 2; ++t) {
-            const int row = (half * (NI / 2) + t) * RPI + r0;
-            *(u32x4 *)(sV + row * LDV + c * 8) = w[t];
-        }
+        for (int t = 0; t < NI; ++t)
+            w[t] = *(const u32x4 *)(vbase + (int64_t)min(kb + t * RPI + r0, end - 1) * v_tstride + c * 8);
     }
-}
+    __device__ __forceinline__ void commit(int lane, __bf16 *sV) const {
+        const int r0 = lane / CPR, c = lane % CPR;
+#pragma unroll
+        for (int t = 0; t < NI; ++t) *(u32x4 *)(sV + (t * RPI + r0) * LDV + c * 8) = w[t];
+    }
+};
 
 // A fragment of V^T for channel block cb, key block mb, contraction step ks: this lane's
 // channel cb * 32 + lane % 32 of the eight keys that its accumulator elements 8 ks .. 8 ks + 7
@@ -135,14 +133,23 @@ __global__ __launch_bounds__(256, 2) void window_attn_kernel(ScoreGeom g, int n_
         for (int v = 0; v < 16; ++v) O[cb][v] = 0.f;
     float m = -INFINITY, s = 0.f;  // running maximum (log2 domain) and sum of this lane's keys
 
+    // The key fragments of a step are requested during the step before it, right after that
+    // step's logits have consumed the registers; the value rows at the start of their step,
+    // committed to LDS after its softmax.  (All requests are unconditional and clamped to the
+    // key range: behind a branch the compiler would wait for them at once.)
+    bf16x8 a[kMB][D / 16];
+    load_a<D>(kbase, g.ks[2], min(key_begin + wave * kWaveKeys, key_end), key_end, lane, a);
     for (int kb0 = key_begin; kb0 < key_end; kb0 += kWgKeys) {
         const int kb = kb0 + wave * kWaveKeys;
-        if (kb >= key_end || kb > bmax) continue;  // (wave-uniform; no barrier inside the loop)
-        bf16x8 a[kMB][D / 16];
-        load_a<D>(kbase, g.ks[2], kb, key_end, lane, a);
-        stage_values<D>(vbase, g.vs[2], kb, key_end, lane, sV);
+        const bool live = kb < key_end && kb <= bmax;  // (wave-uniform; no barrier inside the loop)
+        ValueRows<D> vr;
+        vr.request(vbase, g.vs[2], min(kb, key_end), key_end, lane);
         f32x16 acc[kMB];
         mma_block<D, 1>(a, sQ, 0, lane, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        load_a<D>(kbase, g.ks[2], min(kb + kWgKeys, key_end), key_end, lane, a);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!live) continue;
         // causal limit and the ragged end of the key range
         if (kb + kWaveKeys - 1 > bmin || kb + kWaveKeys > key_end) {
 #pragma unroll
@@ -177,6 +184,7 @@ __global__ __launch_bounds__(256, 2) void window_attn_kernel(ScoreGeom g, int n_
                 }
         s = s * corr + (sum[0] + sum[1]);
         m = mn;
+        vr.commit(lane, sV);
         if (__builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {  // (rarely after the first blocks)
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
