@@ -108,6 +108,8 @@ def test_bf16_shapes(kw):
     (dict(seq_len=900, batch=2, head_dim=64, n_q_heads=16, n_kv_heads=2, window=32, budget=128,
           recent=32), 5),                                                                   # d = 64
     (dict(seq_len=5000, n_q_heads=12, n_kv_heads=3, window=60, budget=500, recent=60), 9),  # 240 rows
+    # 32 problems: key ranges of 1024 keys, pooled in two pieces with the halo between them
+    (dict(seq_len=13001, batch=4, n_q_heads=32, n_kv_heads=8, window=64, budget=1000, recent=64), 7),
 ])
 def test_bf16_full_query_tile_forms_the_value_prior_inside_pass_1(kw, pool):
     """Tiles of 225 - 256 flattened rows (eight 32-row blocks): pass 1 loads the value rows
