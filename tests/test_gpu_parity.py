@@ -269,6 +269,36 @@ def test_strided_inputs_token_major_layout(w):
     assert np.array_equal(scores.cpu().numpy().astype(np.float64), dense.scores)
 
 
+def test_two_host_threads_on_their_own_streams():
+    """The boundary is called from two host threads at once, each on a stream of its own with
+    its own buffers (the library keeps its last error per thread and its one-time device
+    set-up behind a once-flag): every call gives the single-threaded result."""
+    import threading
+    import torch
+    shapes = [BF, synth.scaled(BF, name="bf16_thread_b", seq_len=1100, n_q_heads=8, n_kv_heads=2,
+                               window=64, budget=150, recent=64)]
+    want = [H.run_prefill_gpu(w) for w in shapes]
+    errors = []
+
+    def worker(i):
+        try:
+            w = shapes[i]
+            with torch.cuda.stream(torch.cuda.Stream()):
+                for _ in range(6):
+                    got = H.run_prefill_gpu(w)
+                    assert np.array_equal(got.scores, want[i].scores)
+                    assert np.array_equal(got.idx, want[i].idx)
+        except BaseException as e:  # noqa: BLE001 - reported by the main thread
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+
+
 def test_repeat_calls_are_bit_identical():
     a = H.run_prefill_gpu(BF)
     b = H.run_prefill_gpu(BF)
