@@ -22,7 +22,8 @@ def check_prefill(w, opts=Opts(), decode_steps=0, layer=0):
     gpu = H.run_prefill_gpu(w, opts, inputs)
     ref = H.run_prefill_oracle(w, opts, inputs)
     H.assert_scores_close(gpu.scores, ref.scores, w, opts)
-    excused = H.assert_sets_match(gpu.idx, ref.idx, ref.extra["rank_scores"], w, sink=opts.sink)
+    excused = H.assert_sets_match(gpu.idx, ref.idx, ref.extra["rank_scores"], w, sink=opts.sink,
+                                  opts=opts)
     H.assert_compact_matches(gpu, w, inputs[1], inputs[2])
     if decode_steps:
         flips = H.run_and_check_decode(w, gpu, ref, decode_steps, opts)
