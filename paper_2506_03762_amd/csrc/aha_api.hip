@@ -200,9 +200,13 @@ static WindowAttnPlan plan_window_attn(const aha_params *p) {
     const int64_t Z = (int64_t)p->batch * p->n_kv_heads;
     pl.n_blocks = (int)((R + 31) / 32);
     pl.nparts = 1;
+    pl.nq = pl.n_blocks >= 2 ? 2 : 1;  // row blocks per workgroup
     if (p->dtype != AHA_BF16) return pl;  // fp32: one workgroup per row, no partials
-    const int64_t steps = (p->seq_len + kP2Keys - 1) / kP2Keys;
-    int64_t want = (512 + Z * pl.n_blocks - 1) / (Z * pl.n_blocks);
+    // (a workgroup step is 128 keys with two row blocks, 256 with one)
+    const int64_t wg_keys = pl.nq == 2 ? kP2Keys / 2 : kP2Keys;
+    const int64_t steps = (p->seq_len + wg_keys - 1) / wg_keys;
+    const int64_t groups = (pl.n_blocks + pl.nq - 1) / pl.nq;
+    int64_t want = (512 + Z * groups - 1) / (Z * groups);
     if (want > steps) want = steps;
     if (want > 64) want = 64;
     pl.nparts = (int)(want < 1 ? 1 : want);

@@ -93,6 +93,7 @@ hipError_t launch_row_stats_f32(const ScoreGeom &g, const PrefillPlan &pl, void 
 struct WindowAttnPlan {
     int n_blocks;   // blocks of 32 flattened query rows per (batch, KV head)
     int nparts;     // key ranges per block (bf16 path; 1 on the fp32 path, which needs no workspace)
+    int nq;         // row blocks per workgroup: 2, or 1 when there is a single block
     size_t off_ms;  // (max, sum) pairs behind the partial outputs
     size_t bytes;
 };

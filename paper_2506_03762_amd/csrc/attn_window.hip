@@ -6,17 +6,19 @@
 // scores with one pass over the keys each.
 //
 // bf16: a flash-style single pass on the matrix cores, in the orientation of the score
-// kernels (keys on M, queries on N).  A workgroup owns one block of 32 flattened query rows
-// of a KV head and a range of keys; each of its four waves takes 64-key blocks:
+// kernels (keys on M, queries on N).  A workgroup owns two blocks of 32 flattened query rows
+// of a KV head (one block if there is only one) and a range of keys; each of its four waves
+// takes 32-key blocks (64 with one row block) and runs, per row block:
 //   S^T = K Q^T            v_mfma_f32_32x32x16_bf16, A = key fragments from global memory
 //   online softmax         per query column = per lane (the two half-waves of a column share
 //                          their running maximum every block)
 //   O^T += V^T P^T         the same MFMA; B = the probabilities, converted to bf16 where they
 //                          sit: accumulator elements 8 ks .. 8 ks + 7 of a lane are exactly the
 //                          eight keys of contraction step ks that the lane supplies; A = V^T,
-//                          gathered from a wave-private copy of the 64 value rows in LDS in
-//                          that same key order (the contraction may run over the keys in any
-//                          order as long as both operands agree).
+//                          gathered from a wave-private copy of the step's value rows in LDS
+//                          in that same key order (the contraction may run over the keys in
+//                          any order as long as both operands agree); a gathered fragment
+//                          serves both row blocks.
 // The waves' partial outputs (each relative to its own maximum) meet in LDS, the key ranges'
 // in the workspace, and a small second launch normalises.
 // fp32 (the small high-accuracy path): plain vector-ALU kernel, one workgroup per row.
@@ -24,25 +26,66 @@
 
 namespace aha {
 
-template <int D>
+// NQ blocks of 32 query rows per workgroup, MB blocks of 32 keys per wave and step.  Two
+// shapes are built: (NQ, MB) = (2, 1) - a wave's key fragments, its value rows in LDS and the
+// V^T fragments gathered from them serve two row blocks, which halves the traffic from the L2
+// and the LDS reads per query-key pair - and (1, 2) for problems with a single block of rows.
+template <int D, int NQ, int MB>
 struct AttnSmem {
-    using T = TileSmem<D, 1>;
-    static constexpr int LDV = D + 8;  // padded value row (elements): 16-byte aligned rows
-    static constexpr size_t v_bytes = (size_t)kWaveKeys * LDV * 2;  // one wave's 64 value rows
+    using T = TileSmem<D, NQ>;
+    static constexpr int WK = 32 * MB;   // keys per wave and step
+    static constexpr int LDV = D + 8;    // padded value row (elements): 16-byte aligned rows
+    static constexpr size_t v_bytes = (size_t)WK * LDV * 2;  // one wave's value rows
     static constexpr size_t off_v = (T::bytes + 15) / 16 * 16;
-    static constexpr size_t bytes = off_v + 4 * v_bytes;
-    static constexpr int LDO = D + 1;  // padded row of a wave's partial output (floats)
-    static_assert((size_t)32 * LDO * 4 <= v_bytes, "a wave's partial output reuses its value rows");
-    static_assert(4 * 32 * sizeof(float2) <= T::q_bytes, "the waves' statistics reuse the query tile");
+    static constexpr int LDO = D + 1;    // padded row of a wave's partial output (floats)
+    // after the main loop: the four waves' partial outputs of ONE row block, and all statistics
+    static constexpr size_t o_bytes = (size_t)4 * 32 * LDO * 4;
+    static constexpr size_t off_ms = o_bytes;
+    static constexpr size_t merge_bytes = off_ms + (size_t)4 * NQ * 32 * sizeof(float2);
+    static constexpr size_t loop_bytes = off_v + 4 * v_bytes;
+    static constexpr size_t bytes = loop_bytes > merge_bytes ? loop_bytes : merge_bytes;
+    static_assert(2 * bytes <= 160 * 1024, "two workgroups per CU");
 };
 
-// The wave's 64 value rows [kb, kb + 64) -> its private LDS copy, row-major, 16-byte chunks,
+// A wave's key fragments of a step: lane holds row kb + mb * 32 + lane % 32, channels
+// ks * 16 + (lane / 32) * 8 .. + 8; rows at or past `end` re-read row end - 1.
+template <int D, int MB>
+__device__ __forceinline__ void load_keys(const __bf16 *kbase, int64_t k_tstride, int kb, int end,
+                                          int lane, bf16x8 (&a)[MB][D / 16]) {
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int row = min(kb + mb * 32 + (lane & 31), end - 1);
+        const __bf16 *p = kbase + (int64_t)row * k_tstride + (lane >> 5) * 8;
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) a[mb][ks] = *(const bf16x8 *)(p + ks * 16);
+    }
+}
+
+// Logits of the wave's keys against one block of 32 query rows (sQb: that block's rows in LDS).
+template <int D, int MB>
+__device__ __forceinline__ void logits(const bf16x8 (&a)[MB][D / 16], const __bf16 *sQb, int lane,
+                                       f32x16 (&acc)[MB]) {
+    const __bf16 *bp = sQb + (lane & 31) * (D + 8) + (lane >> 5) * 8;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+        const bf16x8 bfrag = *(const bf16x8 *)(bp + ks * 16);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb][ks], bfrag, acc[mb], 0, 0, 0);
+    }
+}
+
+// The wave's value rows [kb, kb + 32 MB) -> its private LDS copy, row-major, 16-byte chunks,
 // the lanes of a row adjacent.  Rows at or past `end` re-read row end - 1 (their
 // probabilities are zero).  Request (global memory -> registers) and commit (-> LDS) are
 // apart, so that the logits and the softmax of the step cover the round trip to memory.
-template <int D>
+template <int D, int MB>
 struct ValueRows {
-    static constexpr int CPR = D / 8, RPI = 64 / CPR, NI = kWaveKeys / RPI, LDV = AttnSmem<D>::LDV;
+    static constexpr int CPR = D / 8, RPI = 64 / CPR, NI = 32 * MB / RPI, LDV = D + 8;
     u32x4 w[NI];
     __device__ __forceinline__ void request(const __bf16 *vbase, int64_t v_tstride, int kb, int end,
                                             int lane) {
@@ -64,7 +107,7 @@ struct ValueRows {
 template <int D>
 __device__ __forceinline__ bf16x8 value_fragment(const __bf16 *sV, int mb, int ks, int cb,
                                                  int lane) {
-    constexpr int LDV = AttnSmem<D>::LDV;
+    constexpr int LDV = D + 8;
     const uint16_t *p = (const uint16_t *)sV + (4 * (lane >> 5)) * LDV + (lane & 31);
     u32x4 w;
 #pragma unroll
@@ -78,158 +121,198 @@ __device__ __forceinline__ bf16x8 value_fragment(const __bf16 *sV, int mb, int k
     return f;
 }
 
-template <int D>
+template <int D, int NQ, int MB>
 __global__ __launch_bounds__(256, 2) void window_attn_kernel(ScoreGeom g, int n_blocks, int nparts,
                                                              int units, float *part_o,
                                                              float2 *part_ms) {
-    using S = TileSmem<D, 1>;
-    using A = AttnSmem<D>;
-    constexpr int CB = D / 32;  // 32-channel blocks of the output
+    using S = TileSmem<D, NQ>;
+    using A = AttnSmem<D, NQ, MB>;
+    constexpr int CB = D / 32;          // 32-channel blocks of the output
+    constexpr int WK = A::WK, WGK = 4 * WK;  // keys per wave / per workgroup and step
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __bf16 *sQ = (__bf16 *)smem;
     float *sLam = (float *)(smem + S::q_bytes);
     int *sPos = (int *)(sLam + S::ROWS);
     int *sBlk = sPos + 2 * S::ROWS;
 
-    // The workgroups of one (problem, key range) - one per block of 32 query rows - re-read
+    // The workgroups of one (problem, key range) - one per group of NQ row blocks - re-read
     // the same keys and values: they get indices that are congruent modulo 8, i.e. one XCD
     // and one L2 (workgroups are dealt round-robin to the 8 XCDs).
+    const int n_groups = (n_blocks + NQ - 1) / NQ;
     const int id = (int)blockIdx.x, xcd = id % kXcds, t = id / kXcds;
-    const int nbk = t % n_blocks, u = (t / n_blocks) * kXcds + xcd;
+    const int grp = t % n_groups, u = (t / n_groups) * kXcds + xcd;
     if (u >= units) return;
     const int part = u % nparts, z = u / nparts;
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const RowMap rm{g.n, g.r, g.R, nullptr};
-    const int rho0 = nbk * 32;
-    const int end = rm.max_pos(rho0, rho0 + 32) + 1;  // the keys this block of rows may see
-    const int steps = (end + kWgKeys - 1) / kWgKeys;
-    const int key_begin = (int)((int64_t)part * steps / nparts) * kWgKeys;
-    const int key_end = min(end, (int)((int64_t)(part + 1) * steps / nparts) * kWgKeys);
-    const int64_t pidx = ((int64_t)(z * nparts + part) * n_blocks + nbk) * 32;
-    if (key_begin >= key_end) {  // more ranges than this block has key steps: a neutral partial
-        for (int i = tid; i < 32 * D; i += 256) part_o[pidx * D + i] = 0.f;
-        if (tid < 32) part_ms[pidx + tid] = make_float2(-INFINITY, 0.f);
+    const int rho0 = grp * S::ROWS;
+    const int end = rm.max_pos(rho0, rho0 + S::ROWS) + 1;  // the keys these rows may see
+    const int steps = (end + WGK - 1) / WGK;
+    const int key_begin = (int)((int64_t)part * steps / nparts) * WGK;
+    const int key_end = min(end, (int)((int64_t)(part + 1) * steps / nparts) * WGK);
+    // partials are laid out per block of 32 rows; a group's last block may not exist
+    auto pidx_of = [&](int nq) { return ((int64_t)(z * nparts + part) * n_blocks + grp * NQ + nq) * 32; };
+    if (key_begin >= key_end) {  // more ranges than these rows have key steps: neutral partials
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+            if (grp * NQ + nq >= n_blocks) break;
+            for (int i = tid; i < 32 * D; i += 256) part_o[pidx_of(nq) * D + i] = 0.f;
+            if (tid < 32) part_ms[pidx_of(nq) + tid] = make_float2(-INFINITY, 0.f);
+        }
         return;
     }
     const __bf16 *kbase = (const __bf16 *)g.k + b * g.ks[0] + h * g.ks[1];
     const __bf16 *vbase = (const __bf16 *)g.v + b * g.vs[0] + h * g.vs[1];
     const float c_out = kLog2e * rsqrtf((float)D);
     {
-        QTileRegs<D, 1> qt;
-        q_tile_request<D, 1>(g, b, h, rho0, tid, qt);
-        q_tile_meta<D, 1>(g, rm, rho0, tid, c_out, sLam, sPos, sBlk);
-        q_tile_commit<D, 1>(qt, tid, sQ);
+        QTileRegs<D, NQ> qt;
+        q_tile_request<D, NQ>(g, b, h, rho0, tid, qt);
+        q_tile_meta<D, NQ>(g, rm, rho0, tid, c_out, sLam, sPos, sBlk);
+        q_tile_commit<D, NQ>(qt, tid, sQ);
     }
     __syncthreads();
-    const int pos = sPos[lane & 31];
-    const int bmax = uniform(sBlk[0]), bmin = uniform(sBlk[1]);
+    int pos[NQ], bmin[NQ], bmax_all = -1;
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        pos[nq] = sPos[nq * 32 + (lane & 31)];  // -1 for rows past the last one: every key masked
+        bmin[nq] = uniform(sBlk[NQ + nq]);
+        bmax_all = max(bmax_all, uniform(sBlk[nq]));
+    }
     __bf16 *sV = (__bf16 *)(smem + A::off_v + wave * A::v_bytes);
 
-    f32x16 O[CB];
+    f32x16 O[NQ][CB];
+    float m[NQ], s[NQ];  // running maximum (log2 domain) and sum of this lane's keys, per row block
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
+    for (int nq = 0; nq < NQ; ++nq) {
+        m[nq] = -INFINITY;
+        s[nq] = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) O[cb][v] = 0.f;
-    float m = -INFINITY, s = 0.f;  // running maximum (log2 domain) and sum of this lane's keys
-
-    // The key fragments of a step are requested during the step before it, right after that
-    // step's logits have consumed the registers; the value rows at the start of their step,
-    // committed to LDS after its softmax.  (All requests are unconditional and clamped to the
-    // key range: behind a branch the compiler would wait for them at once.)
-    bf16x8 a[kMB][D / 16];
-    load_a<D>(kbase, g.ks[2], min(key_begin + wave * kWaveKeys, key_end), key_end, lane, a);
-    for (int kb0 = key_begin; kb0 < key_end; kb0 += kWgKeys) {
-        const int kb = kb0 + wave * kWaveKeys;
-        const bool live = kb < key_end && kb <= bmax;  // (wave-uniform; no barrier inside the loop)
-        ValueRows<D> vr;
-        vr.request(vbase, g.vs[2], min(kb, key_end), key_end, lane);
-        f32x16 acc[kMB];
-        mma_block<D, 1>(a, sQ, 0, lane, acc);
-        __builtin_amdgcn_sched_barrier(0);
-        load_a<D>(kbase, g.ks[2], min(kb + kWgKeys, key_end), key_end, lane, a);
-        __builtin_amdgcn_sched_barrier(0);
-        if (!live) continue;
-        // causal limit and the ragged end of the key range
-        if (kb + kWaveKeys - 1 > bmin || kb + kWaveKeys > key_end) {
+        for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-            for (int mb = 0; mb < kMB; ++mb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = acc_key(kb, mb, v, lane);
-                    if (key > pos || key >= key_end) acc[mb][v] = -INFINITY;
-                }
-        }
-        float amax = -INFINITY;
-#pragma unroll
-        for (int mb = 0; mb < kMB; ++mb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) amax = fmaxf(amax, acc[mb][v]);
-        // the two half-waves hold different keys of the same query column: one maximum
-        amax = combine_lane_xor<32>(amax, OpMax{});
-        const float mn = fmaxf(m, amax == -INFINITY ? -INFINITY : amax * c_out);
-        const float mref = mn == -INFINITY ? 0.f : mn;
-        const float corr = fast_exp2(m - mref);  // 0 while the column has seen no key
-        float sum[2] = {0.f, 0.f};
-        bf16x8 pf[kMB][2];  // the probabilities as B fragments of the two contraction steps
-#pragma unroll
-        for (int mb = 0; mb < kMB; ++mb)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float pr = fast_exp2(fmaf(acc[mb][8 * ks + e], c_out, -mref));
-                    sum[e & 1] += pr;
-                    pf[mb][ks][e] = (__bf16)pr;
-                }
-        s = s * corr + (sum[0] + sum[1]);
-        m = mn;
-        vr.commit(lane, sV);
-        if (__builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {  // (rarely after the first blocks)
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) O[cb][v] *= corr;
-        }
-#pragma unroll
-        for (int mb = 0; mb < kMB; ++mb)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-                    O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        value_fragment<D>(sV, mb, ks, cb, lane), pf[mb][ks], O[cb], 0, 0, 0);
+            for (int v = 0; v < 16; ++v) O[nq][cb][v] = 0.f;
     }
 
-    // ---- the four waves' partials (different keys, own maxima) meet in LDS ----
-    s += __shfl_xor(s, 32);  // the column's sum over both half-waves
-    __syncthreads();         // the query tile and the value rows are done with
-    float *sO = (float *)(smem + A::off_v + wave * A::v_bytes);
-    float2 *sMS = (float2 *)smem;
+    // Per step: the value rows are requested at the start and committed to LDS after the
+    // softmax (logits and softmax cover their round trip); the key fragments of the NEXT step
+    // are requested right after that commit, into the registers this step's logits have
+    // consumed, and the gathers and the second product cover theirs.  (Requested any earlier
+    // they are live through the softmax, and the kernel no longer fits 256 registers.)  The
+    // requests are clamped to the key range.
+    bf16x8 a[MB][D / 16];
+    load_keys<D, MB>(kbase, g.ks[2], min(key_begin + wave * WK, key_end), key_end, lane, a);
+    for (int kb0 = key_begin; kb0 < key_end; kb0 += WGK) {
+        const int kb = kb0 + wave * WK;
+        const bool live = kb < key_end && kb <= bmax_all;  // (wave-uniform; no barrier in the loop)
+        ValueRows<D, MB> vr;
+        vr.request(vbase, g.vs[2], min(kb, key_end), key_end, lane);
+        f32x16 acc[NQ][MB];
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-            sO[(lane & 31) * A::LDO + cb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)] = O[cb][v];
-    if (lane < 32) sMS[wave * 32 + lane] = make_float2(m, s);
-    __syncthreads();
-    for (int i = tid; i < 32 * D; i += 256) {
-        const int q = i / D, ch = i % D;
-        float M = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) M = fmaxf(M, sMS[w * 32 + q].x);
-        const float mref = M == -INFINITY ? 0.f : M;
-        float o = 0.f, ssum = 0.f;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float2 ms = sMS[w * 32 + q];
-            const float f = fast_exp2(ms.x - mref);
-            const float *wO = (const float *)(smem + A::off_v + w * A::v_bytes);
-            o = fmaf(f, wO[q * A::LDO + ch], o);
-            ssum = fmaf(f, ms.y, ssum);
+        for (int nq = 0; nq < NQ; ++nq) logits<D, MB>(a, sQ + nq * 32 * S::LD, lane, acc[nq]);
+        if (!live) {
+            load_keys<D, MB>(kbase, g.ks[2], min(kb + WGK, key_end), key_end, lane, a);
+            continue;
         }
-        part_o[(pidx + q) * D + ch] = o;
-        if (ch == 0) part_ms[pidx + q] = make_float2(M, ssum);
+        bf16x8 pf[NQ][MB][2];  // the probabilities as B fragments of the two contraction steps
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+            // causal limit and the ragged end of the key range
+            if (kb + WK - 1 > bmin[nq] || kb + WK > key_end) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int key = acc_key(kb, mb, v, lane);
+                        if (key > pos[nq] || key >= key_end) acc[nq][mb][v] = -INFINITY;
+                    }
+            }
+            float amax = -INFINITY;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) amax = fmaxf(amax, acc[nq][mb][v]);
+            // the two half-waves hold different keys of the same query column: one maximum
+            amax = combine_lane_xor<32>(amax, OpMax{});
+            const float mn = fmaxf(m[nq], amax == -INFINITY ? -INFINITY : amax * c_out);
+            const float mref = mn == -INFINITY ? 0.f : mn;
+            const float corr = fast_exp2(m[nq] - mref);  // 0 while the column has seen no key
+            float sum[2] = {0.f, 0.f};
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float pr = fast_exp2(fmaf(acc[nq][mb][8 * ks + e], c_out, -mref));
+                        sum[e & 1] += pr;
+                        pf[nq][mb][ks][e] = (__bf16)pr;
+                    }
+            s[nq] = s[nq] * corr + (sum[0] + sum[1]);
+            m[nq] = mn;
+            if (__builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {  // (rarely after the first blocks)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) O[nq][cb][v] *= corr;
+            }
+        }
+        vr.commit(lane, sV);
+        __builtin_amdgcn_sched_barrier(0);
+        load_keys<D, MB>(kbase, g.ks[2], min(kb + WGK, key_end), key_end, lane, a);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    const bf16x8 vf = value_fragment<D>(sV, mb, ks, cb, lane);
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq)
+                        O[nq][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nq][mb][ks],
+                                                                            O[nq][cb], 0, 0, 0);
+                }
+    }
+
+    // ---- the four waves' partials (different keys, own maxima) meet in LDS, one row block
+    // at a time ----
+    __syncthreads();  // the query tile and the value rows are done with
+    float2 *sMS = (float2 *)(smem + A::off_ms);
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        const float sc = s[nq] + __shfl_xor(s[nq], 32);  // the column's sum over both half-waves
+        if (lane < 32) sMS[(wave * NQ + nq) * 32 + lane] = make_float2(m[nq], sc);
+    }
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        if (grp * NQ + nq >= n_blocks) break;  // (workgroup-uniform)
+        float *sO = (float *)smem + (size_t)wave * 32 * A::LDO;
+        if (nq) __syncthreads();  // the previous block's partials are read
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                sO[(lane & 31) * A::LDO + cb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)] = O[nq][cb][v];
+        __syncthreads();
+        const int64_t pidx = pidx_of(nq);
+        for (int i = tid; i < 32 * D; i += 256) {
+            const int q = i / D, ch = i % D;
+            float M = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) M = fmaxf(M, sMS[(w * NQ + nq) * 32 + q].x);
+            const float mref = M == -INFINITY ? 0.f : M;
+            float o = 0.f, ssum = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float2 ms = sMS[(w * NQ + nq) * 32 + q];
+                const float f = fast_exp2(ms.x - mref);
+                const float *wO = (const float *)smem + (size_t)w * 32 * A::LDO;
+                o = fmaf(f, wO[q * A::LDO + ch], o);
+                ssum = fmaf(f, ms.y, ssum);
+            }
+            part_o[(pidx + q) * D + ch] = o;
+            if (ch == 0) part_ms[pidx + q] = make_float2(M, ssum);
+        }
     }
 }
 
@@ -330,22 +413,23 @@ __global__ __launch_bounds__(256) void f32_window_attn_kernel(ScoreGeom g, float
 }
 
 // ---------------------------------------------------------------- launch --
-template <int D>
-static hipError_t launch_attn_d(const ScoreGeom &g, const WindowAttnPlan &pl, void *ws, void *out,
+template <int D, int NQ, int MB>
+static hipError_t launch_attn_t(const ScoreGeom &g, const WindowAttnPlan &pl, void *ws, void *out,
                                 float *lse, hipStream_t st) {
-    using A = AttnSmem<D>;
+    using A = AttnSmem<D, NQ, MB>;
     float *part_o = (float *)ws;
     float2 *part_ms = (float2 *)((char *)ws + pl.off_ms);
     static DeviceOnce once;
     const hipError_t ea = device_once(once, [] {
-        return hipFuncSetAttribute((const void *)window_attn_kernel<D>,
+        return hipFuncSetAttribute((const void *)window_attn_kernel<D, NQ, MB>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)A::bytes);
     });
     if (ea != hipSuccess) return ea;
     const int Z = g.batch * g.Hkv, units = Z * pl.nparts;
-    const int64_t wgs = (int64_t)((units + kXcds - 1) / kXcds) * kXcds * pl.n_blocks;
-    hipLaunchKernelGGL(window_attn_kernel<D>, dim3((unsigned)wgs), dim3(256), A::bytes, st, g,
-                       pl.n_blocks, pl.nparts, units, part_o, part_ms);
+    const int n_groups = (pl.n_blocks + NQ - 1) / NQ;
+    const int64_t wgs = (int64_t)((units + kXcds - 1) / kXcds) * kXcds * n_groups;
+    hipLaunchKernelGGL((window_attn_kernel<D, NQ, MB>), dim3((unsigned)wgs), dim3(256), A::bytes, st,
+                       g, pl.n_blocks, pl.nparts, units, part_o, part_ms);
     const hipError_t e1 = hipGetLastError();
     if (e1 != hipSuccess) return e1;
     const int rows_per_wg = 256 / D;
@@ -353,6 +437,13 @@ static hipError_t launch_attn_d(const ScoreGeom &g, const WindowAttnPlan &pl, vo
                        dim3(256), 0, st, g, pl.n_blocks, pl.nparts, part_o, part_ms,
                        (uint16_t *)out, lse);
     return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_attn_d(const ScoreGeom &g, const WindowAttnPlan &pl, void *ws, void *out,
+                                float *lse, hipStream_t st) {
+    return pl.nq == 2 ? launch_attn_t<D, 2, 1>(g, pl, ws, out, lse, st)
+                      : launch_attn_t<D, 1, 2>(g, pl, ws, out, lse, st);
 }
 
 hipError_t launch_window_attention(const ScoreGeom &g, const WindowAttnPlan &pl, void *ws,
