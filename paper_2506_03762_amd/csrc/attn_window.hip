@@ -327,10 +327,13 @@ __global__ __launch_bounds__(256) void window_attn_merge_kernel(ScoreGeom g, int
     if (rho >= g.R) return;
     const int b = z / g.Hkv, h = z % g.Hkv;
     const int nbk = rho / 32, q = rho % 32;
+    // (the loads of several key ranges in flight at once: the launch is bound by their latency)
     float M = -INFINITY;
+#pragma unroll 8
     for (int p = 0; p < nparts; ++p)
         M = fmaxf(M, part_ms[((int64_t)(z * nparts + p) * n_blocks + nbk) * 32 + q].x);
     float o = 0.f, ssum = 0.f;
+#pragma unroll 8
     for (int p = 0; p < nparts; ++p) {
         const int64_t pi = ((int64_t)(z * nparts + p) * n_blocks + nbk) * 32 + q;
         const float2 ms = part_ms[pi];
