@@ -249,8 +249,10 @@ static DecodePlan plan_decode(const aha_params *p) {
         pl.bytes = pl.off_nu;
     } else {
         // one workgroup per head: dots and output probabilities of all live slots in LDS
-        const size_t w_floats = (size_t)(G * live > 16 * G * p->head_dim ? G * live : 16 * G * p->head_dim);
-        const size_t q_tile = p->dtype == AHA_BF16 && G >= kDecodeMfmaGroup ? kDecodeQTileBytes(p->head_dim) : 0;
+        const bool mfma = p->dtype == AHA_BF16 && G >= kDecodeMfmaGroup;
+        const bool mfma_v = p->dtype == AHA_BF16 && G >= kDecodeMfmaValuesGroup;
+        const size_t w_floats = decode_w_floats(G, live, p->head_dim, mfma, mfma_v);
+        const size_t q_tile = mfma ? kDecodeQTileBytes(p->head_dim) : 0;
         if ((w_floats + (size_t)G * live) * 4 + q_tile > kDecodeSingleLds) pl.fits = false;
     }
     // value prior inside the loop: the live slots' value norms and their maximum per head

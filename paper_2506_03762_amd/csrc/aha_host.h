@@ -130,6 +130,22 @@ constexpr size_t kDecodeSingleLds = 150 * 1024;  // dynamic LDS of the one-workg
 // kernel forms the dots on the matrix core, from a query tile of 32 padded rows in LDS
 constexpr int kDecodeMfmaGroup = 5;
 constexpr size_t kDecodeQTileBytes(int d) { return (size_t)32 * (d + 8) * 2; }
+// bf16 caches with at least this many query heads per KV head: the values are weighted on the
+// matrix core as well (16 slots per wave at a time, staged through LDS)
+constexpr int kDecodeMfmaValuesGroup = 5;  // (with 3 or 4 heads the vector-ALU weighting measured the same or faster)
+// Floats of the first region of decode_kernel's dynamic LDS (raw dots of all live slots, later
+// the waves' partial outputs [16][G][d]); with the values on the matrix core every wave also
+// stages 16 value rows over the query tile (if any) and this region.
+// Layout: [query tile][this region][G * live].
+inline size_t decode_w_floats(int G, int live, int d, bool mfma_dots, bool mfma_values) {
+    size_t w = (size_t)G * live > (size_t)16 * G * d ? (size_t)G * live : (size_t)16 * G * d;
+    if (mfma_values) {
+        const size_t staging = (size_t)16 * 16 * (d + 8) * 2, tile = mfma_dots ? kDecodeQTileBytes(d) : 0;
+        const size_t need = staging > tile ? (staging - tile + 3) / 4 : 0;
+        if (need > w) w = need;
+    }
+    return w;
+}
 
 struct DecodePlan {
     int nsplit;      // 1: single-launch path

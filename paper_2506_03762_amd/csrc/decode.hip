@@ -75,12 +75,14 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     constexpr int RP = kDecThreads / LPR;  // rows per sweep
     constexpr int ROWB = D * ESIZE;
     constexpr bool kMfmaDots = ESIZE == 2 && G >= kDecodeMfmaGroup;  // dots on the matrix core
+    constexpr bool kMfmaValues = ESIZE == 2 && G >= kDecodeMfmaValuesGroup;  // values too
 
     extern __shared__ __attribute__((aligned(16))) float dsm[];
     // (matrix-core dots: the query tile, 32 padded rows, comes first)
     float *s_w = dsm + (kMfmaDots ? kDecodeQTileBytes(D) / 4 : 0);  // [G][live] raw dots; later [waves][G][D] partial outputs
     float *s_p = s_w + w_floats;   // [G][live] output probabilities
     __shared__ float s_red[kDecWaves][2 * G];
+    __shared__ float s_tot[2 * G];
     __shared__ unsigned long long s_key[kDecWaves];
     __shared__ int s_victim;
 
@@ -240,24 +242,55 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     // the first value rows travel while the softmax statistics are formed (requesting more
     // of them here, or already behind the last batch of key rows, measured 6 % slower: the
     // key and value streams of the 256 workgroups then mix in memory)
-    constexpr int VPF = G <= 2 ? 8 : G <= 6 ? 4 : 2;  // (wide groups: the G x 8 accumulators leave room for few)
+    constexpr int VPF = kMfmaValues ? 1 : G <= 2 ? 8 : 4;
     u32x4 vpf[VPF];
+    // (wide groups: the values go through the matrix core too, in blocks of 16 slots per wave:
+    // block b of wave w is slots 16 (w + 16 b) ..; a lane holds the 16-byte chunk lane % LPR
+    // of rows lane / LPR + t * (64 / LPR) of a block)
+    constexpr int VB = 16, VRPI = 64 / LPR, VNI = VB / VRPI;
+    u32x4 vblk[kMfmaValues ? VNI : 1];
+    auto request_block = [&](int blk) {
 #pragma unroll
-    for (int u = 0; u < VPF; ++u)
-        vpf[u] = *(const u32x4 *)(vcz + (int64_t)min(rg + u * RP, live - 1) * ROWB + sub * 16);
+        for (int t = 0; t < VNI; ++t)
+            vblk[kMfmaValues ? t : 0] =
+                *(const u32x4 *)(vcz + (int64_t)min(blk * VB + t * VRPI + lane / LPR, live - 1) * ROWB + sub * 16);
+    };
+    if constexpr (kMfmaValues) {
+        request_block(wave);
+    } else {
+#pragma unroll
+        for (int u = 0; u < VPF; ++u)
+            vpf[u] = *(const u32x4 *)(vcz + (int64_t)min(rg + u * RP, live - 1) * ROWB + sub * 16);
+    }
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) {
         const float m = wave_max(mloc[gi]);
         if (lane == 0) s_red[wave][gi] = m;
     }
     __syncthreads();
+    // the waves' statistics are folded by every thread for itself with one or two heads (16
+    // LDS reads per value); with more heads one thread per value folds and publishes (the
+    // reads, G x 48 per thread, would otherwise outweigh the extra barrier)
+    constexpr bool kFoldOnce = G >= 3;
     float mx[G];
+    if constexpr (kFoldOnce) {
+        if (tid < G) {
+            float m = s_red[0][tid];
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) {
-        float m = s_red[0][gi];
+            for (int w = 1; w < kDecWaves; ++w) m = fmaxf(m, s_red[w][tid]);
+            s_tot[tid] = m;
+        }
+        __syncthreads();
 #pragma unroll
-        for (int w = 1; w < kDecWaves; ++w) m = fmaxf(m, s_red[w][gi]);
-        mx[gi] = m;
+        for (int gi = 0; gi < G; ++gi) mx[gi] = s_tot[gi];
+    } else {
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            float m = s_red[0][gi];
+#pragma unroll
+            for (int w = 1; w < kDecWaves; ++w) m = fmaxf(m, s_red[w][gi]);
+            mx[gi] = m;
+        }
     }
     __syncthreads();
 
@@ -284,13 +317,28 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
         if (lane == 0) { s_red[wave][2 * gi] = a; s_red[wave][2 * gi + 1] = c; }
     }
     __syncthreads();
+    if constexpr (kFoldOnce) {
+        if (tid < 2 * G) {
+            float a = 0.f;
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) {
-        float a = 0.f, c = 0.f;
+            for (int w = 0; w < kDecWaves; ++w) a += s_red[w][tid];
+            s_tot[tid] = 1.f / a;  // (reciprocals: one division per head instead of two per slot)
+        }
+        __syncthreads();
 #pragma unroll
-        for (int w = 0; w < kDecWaves; ++w) { a += s_red[w][2 * gi]; c += s_red[w][2 * gi + 1]; }
-        zo[gi] = 1.f / a;  // (reciprocals: one division per head instead of two per slot)
-        zs[gi] = 1.f / c;
+        for (int gi = 0; gi < G; ++gi) {
+            zo[gi] = s_tot[2 * gi];
+            zs[gi] = s_tot[2 * gi + 1];
+        }
+    } else {
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            float a = 0.f, c = 0.f;
+#pragma unroll
+            for (int w = 0; w < kDecWaves; ++w) { a += s_red[w][2 * gi]; c += s_red[w][2 * gi + 1]; }
+            zo[gi] = 1.f / a;  // (reciprocals: one division per head instead of two per slot)
+            zs[gi] = 1.f / c;
+        }
     }
 
     // ---- probabilities, running score, eviction candidate ----
@@ -324,6 +372,64 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     if (best_slot >= 0 && best == gbest) s_victim = best_slot;
 
     // ---- attention output: sum_s p_s V_s ----
+    float *s_o = s_w;  // [waves][G][D]
+    if constexpr (kMfmaValues) {
+        // O^T += V^T P^T on the matrix core, 16 slots at a time: A = V^T (channels on M, a
+        // lane gathers its channel of eight slots from the wave's copy of the block's rows in
+        // LDS), B = the probabilities of those slots (query heads on N, columns >= G zero).
+        // The wave's copy lies over the query tile (if any) and the dots, which are done with.
+        constexpr int LDVS = D + 8, CB = D / 32;
+        __bf16 *sVw = (__bf16 *)dsm + wave * VB * LDVS;
+        f32x16 O[CB];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) O[cb][v] = 0.f;
+        const int nvb = (live + VB - 1) / VB, qn = lane & 31, hf = lane >> 5;
+        for (int blk = wave; blk < nvb; blk += kDecWaves) {
+            // this block's rows -> LDS (the new value row stands in for the free slot's and
+            // goes to the cache), the next block's are requested (clamped: never past the last)
+#pragma unroll
+            for (int t = 0; t < VNI; ++t) {
+                const int rin = t * VRPI + lane / LPR;
+                u32x4 w = vblk[t];
+                if (blk * VB + rin == fs) {
+                    w = vnw;
+                    *(u32x4 *)(vcz + (int64_t)fs * ROWB + sub * 16) = w;
+                }
+                *(u32x4 *)(sVw + rin * LDVS + sub * 8) = w;
+            }
+            request_block(min(blk + kDecWaves, nvb - 1));
+            // probabilities of slots 8 hf .. 8 hf + 7 of the block for query head qn
+            bf16x8 pfrag;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int sl = blk * VB + 8 * hf + e;
+                pfrag[e] = (__bf16)((qn < G && sl < live) ? s_p[min(qn, G - 1) * live + min(sl, live - 1)] : 0.f);
+            }
+            const uint16_t *p16 = (const uint16_t *)sVw + (8 * hf) * LDVS + qn;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                u32x4 w;
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const uint32_t lo = p16[e * LDVS + cb * 32], hi = p16[(e + 1) * LDVS + cb * 32];
+                    w[e / 2] = lo | (hi << 16);
+                }
+                bf16x8 vfrag;
+                __builtin_memcpy(&vfrag, &w, 16);
+                O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pfrag, O[cb], 0, 0, 0);
+            }
+        }
+        __syncthreads();  // every wave is done with its rows: the partial outputs go on top
+        if (qn < G) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    s_o[(wave * G + qn) * D + cb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3)] = O[cb][v];
+        }
+    } else {
     float o[G][CH];
 #pragma unroll
     for (int gi = 0; gi < G; ++gi)
@@ -346,12 +452,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
 #pragma unroll
     for (int u = 0; u < VPF; ++u)
         if (rg + u * RP < live) weigh(rg + u * RP, vpf[u]);
-    // (rows in flight per thread: as many as the registers beside the G x CH accumulators allow)
-    constexpr int VU = G <= 4 ? 8 : G <= 6 ? 4 : 2;
-#pragma unroll VU
+#pragma unroll 8
     for (int s = rg + VPF * RP; s < live; s += RP)
         weigh(s, *(const u32x4 *)(vcz + (int64_t)s * ROWB + sub * 16));
-    float *s_o = s_w;  // [waves][G][D]
 #pragma unroll
     for (int gi = 0; gi < G; ++gi)
 #pragma unroll
@@ -360,6 +463,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
             v = reduce_lanes<LPR, 64>(v, OpSum{});  // over the rows of the wave
             if (lane < LPR) s_o[(wave * G + gi) * D + sub * CH + c] = v;
         }
+    }
     __syncthreads();
     for (int t = tid; t < G * D; t += kDecThreads) {
         const int gi = t / D, c = t % D;
@@ -828,9 +932,11 @@ static hipError_t launch_g(const DecodeGeom &g, const DecodePlan &pl, void *ws, 
 #undef AHA_DECS
         return hipGetLastError();
     }
-    const int w_floats = max(g.G * live, kDecWaves * g.G * D);
+    const bool mfma = ESIZE == 2 && g.G >= kDecodeMfmaGroup;
+    const bool mfma_v = ESIZE == 2 && g.G >= kDecodeMfmaValuesGroup;
+    const int w_floats = (int)decode_w_floats(g.G, live, D, mfma, mfma_v);
     const size_t smem = (size_t)(w_floats + g.G * live) * sizeof(float) +
-                        (ESIZE == 2 && g.G >= kDecodeMfmaGroup ? kDecodeQTileBytes(D) : 0);
+                        (mfma ? kDecodeQTileBytes(D) : 0);
     dim3 grid(g.batch * g.Hkv);
 #define AHA_DEC(GG)                                                                              \
     {                                                                                            \
