@@ -82,9 +82,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     float *s_w = dsm + (kMfmaDots ? kDecodeQTileBytes(D) / 4 : 0);  // [G][live] raw dots; later [waves][G][D] partial outputs
     float *s_p = s_w + w_floats;   // [G][live] output probabilities
     __shared__ float s_red[kDecWaves][2 * G];
-    __shared__ float s_tot[2 * G];
+    __shared__ float s_tot[3 * G];  // folded maxima [G], then reciprocal sums [2 G]
     __shared__ unsigned long long s_key[kDecWaves];
-    __shared__ int s_victim;
 
     const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = z / g.Hkv, h = z % g.Hkv;
@@ -268,31 +267,19 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
         if (lane == 0) s_red[wave][gi] = m;
     }
     __syncthreads();
-    // the waves' statistics are folded by every thread for itself with one or two heads (16
-    // LDS reads per value); with more heads one thread per value folds and publishes (the
-    // reads, G x 48 per thread, would otherwise outweigh the extra barrier)
-    constexpr bool kFoldOnce = G >= 3;
+    // the waves' statistics are folded by one thread per value and published (every thread
+    // folding for itself costs 48 LDS reads per head and thread: C4 decode 28.7 -> 28.4 us)
     float mx[G];
-    if constexpr (kFoldOnce) {
-        if (tid < G) {
-            float m = s_red[0][tid];
+    if (tid < G) {
+        float m = s_red[0][tid];
 #pragma unroll
-            for (int w = 1; w < kDecWaves; ++w) m = fmaxf(m, s_red[w][tid]);
-            s_tot[tid] = m;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int gi = 0; gi < G; ++gi) mx[gi] = s_tot[gi];
-    } else {
-#pragma unroll
-        for (int gi = 0; gi < G; ++gi) {
-            float m = s_red[0][gi];
-#pragma unroll
-            for (int w = 1; w < kDecWaves; ++w) m = fmaxf(m, s_red[w][gi]);
-            mx[gi] = m;
-        }
+        for (int w = 1; w < kDecWaves; ++w) m = fmaxf(m, s_red[w][tid]);
+        s_tot[tid] = m;
     }
     __syncthreads();
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) mx[gi] = s_tot[gi];
+    // (no barrier: s_red and s_tot are next written behind the barrier that follows the sums)
 
     // ---- the two softmax denominators ----
     const float c_out = kLog2e * rsqrtf((float)D);
@@ -317,28 +304,17 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
         if (lane == 0) { s_red[wave][2 * gi] = a; s_red[wave][2 * gi + 1] = c; }
     }
     __syncthreads();
-    if constexpr (kFoldOnce) {
-        if (tid < 2 * G) {
-            float a = 0.f;
+    if (tid < 2 * G) {
+        float a = 0.f;
 #pragma unroll
-            for (int w = 0; w < kDecWaves; ++w) a += s_red[w][tid];
-            s_tot[tid] = 1.f / a;  // (reciprocals: one division per head instead of two per slot)
-        }
-        __syncthreads();
+        for (int w = 0; w < kDecWaves; ++w) a += s_red[w][tid];
+        s_tot[G + tid] = 1.f / a;  // (reciprocals: one division per head instead of two per slot)
+    }
+    __syncthreads();
 #pragma unroll
-        for (int gi = 0; gi < G; ++gi) {
-            zo[gi] = s_tot[2 * gi];
-            zs[gi] = s_tot[2 * gi + 1];
-        }
-    } else {
-#pragma unroll
-        for (int gi = 0; gi < G; ++gi) {
-            float a = 0.f, c = 0.f;
-#pragma unroll
-            for (int w = 0; w < kDecWaves; ++w) { a += s_red[w][2 * gi]; c += s_red[w][2 * gi + 1]; }
-            zo[gi] = 1.f / a;  // (reciprocals: one division per head instead of two per slot)
-            zs[gi] = 1.f / c;
-        }
+    for (int gi = 0; gi < G; ++gi) {
+        zo[gi] = s_tot[G + 2 * gi];
+        zs[gi] = s_tot[G + 2 * gi + 1];
     }
 
     // ---- probabilities, running score, eviction candidate ----
@@ -366,10 +342,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     const unsigned long long wbest = wave_min_key(best);  // every lane takes part
     if (lane == 0) s_key[wave] = wbest;
     __syncthreads();  // also: s_w is free from here on
-    unsigned long long gbest = s_key[0];
-#pragma unroll
-    for (int w = 1; w < kDecWaves; ++w) gbest = s_key[w] < gbest ? s_key[w] : gbest;
-    if (best_slot >= 0 && best == gbest) s_victim = best_slot;
+    // (the waves' candidates are compared at the very end, off the path to the values)
 
     // ---- attention output: sum_s p_s V_s ----
     float *s_o = s_w;  // [waves][G][D]
@@ -476,10 +449,16 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
         else
             ((float *)g.out)[oi] = v;
     }
-    if (tid == 0) {
-        const int victim = s_victim;
-        posz[victim] = -1;
-        g.free_slot[z] = victim;
+    // positions are unique, so exactly one thread holds the victim: it retires the slot (only
+    // the waves' own candidates look at the other waves' keys)
+    if (best_slot >= 0 && best == wbest) {
+        unsigned long long gbest = s_key[0];
+#pragma unroll
+        for (int w = 1; w < kDecWaves; ++w) gbest = s_key[w] < gbest ? s_key[w] : gbest;
+        if (best == gbest) {
+            posz[best_slot] = -1;
+            g.free_slot[z] = best_slot;
+        }
     }
 }
 
