@@ -114,6 +114,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
     // them would otherwise wait a full round trip to memory in the middle of the kernel)
     const float f_first = fcz[min(tid, live - 1)];
     const int p_first = posz[min(tid, live - 1)];
+    const float f_second = fcz[min(tid + kDecThreads, live - 1)];
+    const int p_second = posz[min(tid + kDecThreads, live - 1)];
 
     // ---- raw dots over the live slots (the new key stands in for slot fs) ----
     float mloc[G];
@@ -329,10 +331,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
             add += fast_exp2(d * c_sc) * zs[gi];
         }
         if (g.value_prior) add *= prior_factor(ws_nu[(int64_t)z * live + s], ginv);
-        const float f = (s == fs ? 0.f : (s == tid ? f_first : fcz[s])) + add;
+        const float f = (s == fs ? 0.f : s == tid ? f_first : s == tid + kDecThreads ? f_second : fcz[s]) + add;
         fcz[s] = f;
         int ps;
-        if (s == fs) { ps = g.logical_pos - 1; posz[s] = ps; } else { ps = s == tid ? p_first : posz[s]; }
+        if (s == fs) { ps = g.logical_pos - 1; posz[s] = ps; } else { ps = s == tid ? p_first : s == tid + kDecThreads ? p_second : posz[s]; }
         if (ps < g.logical_pos - g.recent && ps >= g.sink) {
             const unsigned long long key =
                 ((unsigned long long)__float_as_uint(f) << 32) | (uint32_t)(~ps);
