@@ -57,7 +57,7 @@ def main():
                     help="skip the oracle timing (used under rocprofv3)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the C4 decode and C2 full-accumulation side measurements")
-    ap.add_argument("--only", choices=["decode_c4", "full_c2", "full_c3", "c5_layer"], default=None,
+    ap.add_argument("--only", choices=["decode_c4", "full_c2", "full_c3", "c5_layer", "window_attn"], default=None,
                     help="run one side measurement alone and print it (for profiling that kernel)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB elementwise kernel (calibrates the rocprofv3 "
@@ -88,7 +88,8 @@ def main():
         fn = {"decode_c4": lambda: bench_decode_c4(torch, B, synth, H, K_STEPS),
               "full_c2": lambda: bench_full_c2(torch, B, synth, H, max(5, K_STEPS // 5)),
               "full_c3": lambda: bench_full_c3_alone(torch, B, synth, H),
-              "c5_layer": lambda: bench_c5_layer(torch, B, synth, H, max(5, K_STEPS // 5))}[args.only]
+              "c5_layer": lambda: bench_c5_layer(torch, B, synth, H, max(5, K_STEPS // 5)),
+              "window_attn": lambda: bench_window_attn_alone(torch, B, synth, H, K_STEPS)}[args.only]
         print(json.dumps({"only": args.only, args.only: fn()}))
         return
 
@@ -500,6 +501,17 @@ def bench_window_attn_c3(torch, B, w, p, q, k, v, scores, ws, steps):
             "mfma_frac": flops / (attn * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
             "attention_plus_scores_us": timed(both),
             "two_pass_scores_alone_us": timed(lambda: B.aha_prefill_scores(pf, q, k, v, scores, ws))}
+
+
+def bench_window_attn_alone(torch, B, synth, H, steps):
+    """bench_window_attn_c3 with inputs of its own (for profiling that measurement alone)."""
+    w = synth.C3
+    log("generating", w.name)
+    q, k, v = (H.to_device(a, w.dtype) for a in synth.make_prefill(w, threads=16))
+    p = H.params_for(w).with_strides(q, k, v)
+    ws = B.alloc_workspace(p)
+    scores = torch.empty((w.batch, w.n_kv_heads, w.seq_len), dtype=torch.float32, device="cuda")
+    return bench_window_attn_c3(torch, B, w, p, q, k, v, scores, ws, steps)
 
 
 def bench_c5_layer(torch, B, synth, H, steps):

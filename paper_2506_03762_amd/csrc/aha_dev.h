@@ -16,6 +16,28 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kWave = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 
+// A^T fragment of v_mfma_f32_32x32x16_bf16 from a row-major bf16 matrix in LDS (the value rows
+// [slot][channel], wanted as V^T with the channels on M): the lane's channel
+// col0 + lane % 32 of the eight rows row0 + 4 (lane / 32) + {0..3} and row0 + gap + 4 (lane / 32) +
+// {0..3}, ld elements per row.  A lane wants a COLUMN of four elements at a time:
+// ds_read_b64_tr_b16 reads, per group of 16 lanes, a tile of 4 rows x 16 elements - lane s of
+// the group supplies the address of row s / 4, elements 4 (s % 4) .. + 3 - and hands lane j of
+// the group column j of that tile (its elements of rows 0 .. 3, in order).  Two such reads
+// make a fragment, with no repacking in the vector ALU.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8 lds_transposed_fragment(const __bf16 *base, int ld, int row0,
+                                                          int gap, int col0, int lane) {
+    using lds_ptr = s16x4 __attribute__((address_space(3))) *;
+    const __bf16 *p = base + (row0 + 4 * (lane >> 5) + ((lane >> 2) & 3)) * ld + col0 + (lane & 16) +
+                      4 * (lane & 3);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + gap * ld));
+    bf16x8 f;
+    __builtin_memcpy(&f, &lo, 8);
+    __builtin_memcpy((char *)&f + 8, &hi, 8);
+    return f;
+}
+
 // bf16 <-> fp32 on raw bits (bf16 is the upper half of an fp32).
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }

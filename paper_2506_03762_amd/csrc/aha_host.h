@@ -132,7 +132,7 @@ constexpr int kDecodeMfmaGroup = 5;
 constexpr size_t kDecodeQTileBytes(int d) { return (size_t)32 * (d + 8) * 2; }
 // bf16 caches with at least this many query heads per KV head: the values are weighted on the
 // matrix core as well (16 slots per wave at a time, staged through LDS)
-constexpr int kDecodeMfmaValuesGroup = 5;  // (with 3 or 4 heads the vector-ALU weighting measured the same or faster)
+constexpr int kDecodeMfmaValuesGroup = 4;  // (with 4 heads the dots stay in the vector ALU, with 3 the values too: measured faster)
 // Floats of the first region of decode_kernel's dynamic LDS (raw dots of all live slots, later
 // the waves' partial outputs [16][G][d]); with the values on the matrix core every wave also
 // stages 16 value rows over the query tile (if any) and this region.

@@ -30,11 +30,18 @@ namespace aha {
 // shapes are built: (NQ, MB) = (2, 1) - a wave's key fragments, its value rows in LDS and the
 // V^T fragments gathered from them serve two row blocks, which halves the traffic from the L2
 // and the LDS reads per query-key pair - and (1, 2) for problems with a single block of rows.
+// Padded value row in LDS (elements): rows 16-byte aligned.  With 32 keys per wave the four
+// rows of a transposing read lie 16 banks apart (80 resp. 48 dwords per row), so that the
+// 4 x 32 elements that a half-wave reads fall into 64 different banks; with 64 keys per wave
+// (the single-row-block shape) only the smallest padding fits two workgroups per CU.
+template <int D, int MB>
+struct AttnLdv { static constexpr int value = MB == 1 ? D + 32 : D + 8; };
+
 template <int D, int NQ, int MB>
 struct AttnSmem {
     using T = TileSmem<D, NQ>;
     static constexpr int WK = 32 * MB;   // keys per wave and step
-    static constexpr int LDV = D + 8;    // padded value row (elements): 16-byte aligned rows
+    static constexpr int LDV = AttnLdv<D, MB>::value;
     static constexpr size_t v_bytes = (size_t)WK * LDV * 2;  // one wave's value rows
     static constexpr size_t off_v = (T::bytes + 15) / 16 * 16;
     static constexpr int LDO = D + 1;    // padded row of a wave's partial output (floats)
@@ -85,7 +92,7 @@ __device__ __forceinline__ void logits(const bf16x8 (&a)[MB][D / 16], const __bf
 // apart, so that the logits and the softmax of the step cover the round trip to memory.
 template <int D, int MB>
 struct ValueRows {
-    static constexpr int CPR = D / 8, RPI = 64 / CPR, NI = 32 * MB / RPI, LDV = D + 8;
+    static constexpr int CPR = D / 8, RPI = 64 / CPR, NI = 32 * MB / RPI, LDV = AttnLdv<D, MB>::value;
     u32x4 w[NI];
     __device__ __forceinline__ void request(const __bf16 *vbase, int64_t v_tstride, int kb, int end,
                                             int lane) {
@@ -103,22 +110,12 @@ struct ValueRows {
 
 // A fragment of V^T for channel block cb, key block mb, contraction step ks: this lane's
 // channel cb * 32 + lane % 32 of the eight keys that its accumulator elements 8 ks .. 8 ks + 7
-// of key block mb stand for (rows mb * 32 + 16 ks + 8 (e / 4) + e % 4 + 4 (lane / 32)).
-template <int D>
+// of key block mb stand for (rows mb * 32 + 16 ks + 8 (e / 4) + e % 4 + 4 (lane / 32)): two
+// runs of four consecutive keys, eight rows apart, read with the transposing LDS load.
+template <int LDV>
 __device__ __forceinline__ bf16x8 value_fragment(const __bf16 *sV, int mb, int ks, int cb,
                                                  int lane) {
-    constexpr int LDV = D + 8;
-    const uint16_t *p = (const uint16_t *)sV + (4 * (lane >> 5)) * LDV + (lane & 31);
-    u32x4 w;
-#pragma unroll
-    for (int e = 0; e < 8; e += 2) {
-        const int r0 = mb * 32 + 16 * ks + 8 * (e >> 2) + (e & 3);
-        const uint32_t lo = p[r0 * LDV + cb * 32], hi = p[(r0 + 1) * LDV + cb * 32];
-        w[e / 2] = lo | (hi << 16);
-    }
-    bf16x8 f;
-    __builtin_memcpy(&f, &w, 16);
-    return f;
+    return lds_transposed_fragment(sV, LDV, mb * 32 + 16 * ks, 8, cb * 32, lane);
 }
 
 template <int D, int NQ, int MB>
@@ -266,7 +263,7 @@ __global__ __launch_bounds__(256, 2) void window_attn_kernel(ScoreGeom g, int n_
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) {
-                    const bf16x8 vf = value_fragment<D>(sV, mb, ks, cb, lane);
+                    const bf16x8 vf = value_fragment<A::LDV>(sV, mb, ks, cb, lane);
 #pragma unroll
                     for (int nq = 0; nq < NQ; ++nq)
                         O[nq][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nq][mb][ks],

@@ -382,17 +382,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
                 const int sl = blk * VB + 8 * hf + e;
                 pfrag[e] = (__bf16)((qn < G && sl < live) ? s_p[min(qn, G - 1) * live + min(sl, live - 1)] : 0.f);
             }
-            const uint16_t *p16 = (const uint16_t *)sVw + (8 * hf) * LDVS + qn;
+            // V^T fragments (slots 8 hf .. 8 hf + 7 of the block) by transposing LDS reads
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
-                u32x4 w;
-#pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    const uint32_t lo = p16[e * LDVS + cb * 32], hi = p16[(e + 1) * LDVS + cb * 32];
-                    w[e / 2] = lo | (hi << 16);
-                }
-                bf16x8 vfrag;
-                __builtin_memcpy(&vfrag, &w, 16);
+                const bf16x8 vfrag = lds_transposed_fragment(sVw, LDVS, 4 * hf, 4, cb * 32, lane);
                 O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pfrag, O[cb], 0, 0, 0);
             }
         }
