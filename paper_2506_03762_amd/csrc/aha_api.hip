@@ -202,8 +202,7 @@ static WindowAttnPlan plan_window_attn(const aha_params *p) {
     pl.nparts = 1;
     pl.nq = pl.n_blocks >= 2 ? 2 : 1;  // row blocks per workgroup
     if (p->dtype != AHA_BF16) return pl;  // fp32: one workgroup per row, no partials
-    // (a workgroup step is 128 keys with two row blocks, 256 with one)
-    const int64_t wg_keys = pl.nq == 2 ? kP2Keys / 2 : kP2Keys;
+    const int64_t wg_keys = kP2Keys / 2;  // a workgroup step: four waves of 32 keys
     const int64_t steps = (p->seq_len + wg_keys - 1) / wg_keys;
     const int64_t groups = (pl.n_blocks + pl.nq - 1) / pl.nq;
     int64_t want = (512 + Z * groups - 1) / (Z * groups);

@@ -15,10 +15,14 @@ BF = synth.scaled(synth.C3, name="bf16_small", seq_len=1536, n_q_heads=8, n_kv_h
                   budget=192, recent=32, window=32)
 
 
-def run_window_attention(w, window, Q, K, V):
+def run_window_attention(w, window, Q, K, V, token_major=False):
     import torch
     from paper_2506_03762_amd import binding as B
-    q, k, v = (H.to_device(a, w.dtype) for a in (Q, K, V))
+    if token_major:  # stored [b, n, h, d], passed by strides
+        q, k, v = (H.to_device(np.ascontiguousarray(a.transpose(0, 2, 1, 3)), w.dtype).permute(0, 2, 1, 3)
+                   for a in (Q, K, V))
+    else:
+        q, k, v = (H.to_device(a, w.dtype) for a in (Q, K, V))
     p = H.gpu_params(w, Opts(window=window)).with_strides(q, k, v)
     ws = torch.empty(max(B.window_attention_workspace_bytes(p), 256), dtype=torch.uint8, device="cuda")
     ws.fill_(0xA5)
@@ -62,9 +66,41 @@ def check(w, window, inputs=None):
     (synth.scaled(BF, name="short", seq_len=31, n_q_heads=2, n_kv_heads=2, budget=8, recent=8), 31),
     (synth.scaled(BF, name="batch3", seq_len=300, batch=3, n_q_heads=2, n_kv_heads=1, budget=50,
                   recent=5), 300),
+    # a single block of rows (its own kernel shape) with 64 channels, ragged key ranges
+    (synth.scaled(BF, name="one_block_d64", seq_len=2077, n_q_heads=4, n_kv_heads=2, head_dim=64), 9),
+    (synth.scaled(BF, name="one_block_d128", seq_len=777, n_q_heads=2, n_kv_heads=2), 32),
 ], ids=lambda x: getattr(x, "name", x))
 def test_window_attention_matches_the_oracle(w, window):
     check(w, window)
+
+
+@pytest.mark.parametrize("head_dim", [64, 128])
+def test_window_attention_with_logits_that_keep_rising(head_dim):
+    """Keys whose size grows with the position, aligned with the queries' mean direction: the
+    rows' maxima rise all along the sequence, by more than the kernel's slack between its
+    softmax reference and the running maximum many times over, and by less than it in
+    between (both branches of the lazy reference)."""
+    # (128 problems x row-block pairs: four key ranges of eight 128-key steps each)
+    w = synth.scaled(BF, name="rising", batch=4, n_q_heads=32, n_kv_heads=16, seq_len=4096,
+                     head_dim=head_dim, window=64)
+    Q, K, V = synth.make_prefill(w)
+    n = w.seq_len
+    u = np.random.default_rng(7).standard_normal(head_dim)
+    u /= np.linalg.norm(u)
+    # logit ~ 3 * ramp / sqrt(d): about 3 (log2 units) more per 128-key step
+    ramp = np.linspace(0.0, 20.0 * np.sqrt(head_dim), n)[None, None, :, None]
+    Q = synth.store_round((Q * 0.3 + 3.0 * u).astype(np.float32), w.dtype)   # all queries lean on u
+    K = synth.store_round((K * 0.5 + ramp * u).astype(np.float32), w.dtype)
+    check(w, w.window, (Q, K, V))
+
+
+def test_window_attention_token_major_layout():
+    """Q/K/V stored [b, n, h, d] and passed by strides give the same output, bit for bit."""
+    w = synth.scaled(BF, name="token_major", seq_len=1100, n_q_heads=8, n_kv_heads=2, window=64)
+    Q, K, V = synth.make_prefill(w)
+    dense = run_window_attention(w, w.window, Q, K, V)
+    strided = run_window_attention(w, w.window, Q, K, V, token_major=True)
+    assert np.array_equal(dense[0], strided[0]) and np.array_equal(dense[1], strided[1])
 
 
 def test_c3_window_attention_and_scores_from_its_log_sum_exp():
