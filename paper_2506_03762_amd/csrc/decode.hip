@@ -192,7 +192,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
         u32x4 kv_row = {0u, 0u, 0u, 0u};
         if (vrow >= 0) kv_row = *(const u32x4 *)(kcz + (int64_t)vrow * ROWB + sub * 16);
         auto load_block = [&](int blk, bf16x8 (&dst)[D / 16]) {
-            const int row = min(min(blk, nblk - 1) * 32 + (lane & 31), live - 1);
+            const int row = min(max(min(blk, nblk - 1), 0) * 32 + (lane & 31), live - 1);  // (any blk, any nblk)
             const char *pr = kcz + (int64_t)row * ROWB + (lane >> 5) * 16;
 #pragma unroll
             for (int ks = 0; ks < D / 16; ++ks) dst[ks] = *(const bf16x8 *)(pr + ks * 32);
@@ -212,17 +212,27 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeGeom g, int w
                     s_w[(lane & 31) * live + blk * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)] = acc[v];
             }
         };
+        // (The loads are issued unconditionally, clamped to the last whole block: behind a
+        // branch the compiler would wait for a prefetch before the block in hand.)
         bf16x8 a0[D / 16], a1[D / 16];
-        if (nblk > 0) load_block(wave, a0);
-        __syncthreads();  // the query tile is in LDS
-        // (the loads are issued unconditionally, clamped to the last whole block: behind a
-        // branch the compiler would wait for a prefetch before the block in hand)
-        for (int blk = wave; blk < nblk; blk += 2 * kDecWaves) {
-            load_block(blk + kDecWaves, a1);
-            block_dots(blk, a0);
-            if (blk + kDecWaves >= nblk) break;
-            load_block(blk + 2 * kDecWaves, a0);
-            block_dots(blk + kDecWaves, a1);
+        if (nblk <= 2 * kDecWaves) {
+            // at most two blocks per wave (budgets up to 1024): both travel while the query
+            // tile is set up, and nothing is requested that is not used
+            load_block(wave, a0);
+            load_block(wave + kDecWaves, a1);
+            __syncthreads();  // the query tile is in LDS
+            if (wave < nblk) block_dots(wave, a0);
+            if (wave + kDecWaves < nblk) block_dots(wave + kDecWaves, a1);
+        } else {
+            load_block(wave, a0);
+            __syncthreads();  // the query tile is in LDS
+            for (int blk = wave; blk < nblk; blk += 2 * kDecWaves) {
+                load_block(blk + kDecWaves, a1);
+                block_dots(blk, a0);
+                if (blk + kDecWaves >= nblk) break;
+                load_block(blk + 2 * kDecWaves, a0);
+                block_dots(blk + kDecWaves, a1);
+            }
         }
         __syncthreads();  // the blocks' dots are written (the free slot's among them: stale)
         // (the lane reductions inside `dots` stay inside a row's group of lanes, which is

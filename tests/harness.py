@@ -173,13 +173,20 @@ def assert_sets_match(idx_gpu, idx_ref, scores_ref, w, max_excused_frac=0.01, si
     the oracle's threshold (the B_s-th largest candidate score).  `scores_ref` are the
     oracle's float64 scores that ranked the candidates (the pooled ones when the selection
     ranks pooled scores).  Returns the number of excused indices."""
+    # Pooled scores around one dominant token form a plateau: its pool-width neighbours hold
+    # the same large term and differ by terms below fp32 resolution, so the kernel (fp32) sees
+    # exact ties, broken by position, where float64 sees an order.  Every swapped index must
+    # still be a near-tie; with pooling one swap per problem is allowed on top of the 1 %.
+    pooled = opts is not None and opts.score_pool > 1
     return sets_match(idx_gpu, idx_ref, scores_ref, w.seq_len, w.budget, w.recent,
-                      rtol_of(w, opts), max_excused_frac, sink)
+                      rtol_of(w, opts), max_excused_frac, sink, swaps_per_problem=1 if pooled else 0)
 
 
-def sets_match(idx_gpu, idx_ref, scores_ref, n, B, Br, rtol, max_excused_frac=0.01, sink=0):
+def sets_match(idx_gpu, idx_ref, scores_ref, n, B, Br, rtol, max_excused_frac=0.01, sink=0,
+               swaps_per_problem=0):
     assert idx_gpu.shape == idx_ref.shape
     excused = 0
+    problems = int(np.prod(idx_ref.shape[:-1]))
     for p in np.ndindex(idx_ref.shape[:-1]):
         g, r = idx_gpu[p], idx_ref[p]
         assert np.all(np.diff(g) > 0), "GPU indices not strictly ascending at %s" % (p,)
@@ -196,7 +203,8 @@ def sets_match(idx_gpu, idx_ref, scores_ref, n, B, Br, rtol, max_excused_frac=0.
             assert abs(s - thr) <= rtol * abs(thr), \
                 "index %d at %s differs and is not a near-tie: score %.9g threshold %.9g" % (j, p, s, thr)
         excused += diff.size
-    assert excused <= max_excused_frac * idx_ref.size + 2, "too many near-tie flips: %d" % excused
+    assert excused <= max_excused_frac * idx_ref.size + 2 + 2 * swaps_per_problem * problems, \
+        "too many near-tie flips: %d" % excused
     return excused
 
 
