@@ -57,7 +57,7 @@ def main():
                     help="skip the oracle timing (used under rocprofv3)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the C4 decode and C2 full-accumulation side measurements")
-    ap.add_argument("--only", choices=["decode_c4", "full_c2", "full_c3", "c5_layer", "window_attn"], default=None,
+    ap.add_argument("--only", choices=["decode_c4", "full_c2", "full_c3", "c5_layer", "c2_layer", "window_attn"], default=None,
                     help="run one side measurement alone and print it (for profiling that kernel)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB elementwise kernel (calibrates the rocprofv3 "
@@ -89,6 +89,7 @@ def main():
               "full_c2": lambda: bench_full_c2(torch, B, synth, H, max(5, K_STEPS // 5)),
               "full_c3": lambda: bench_full_c3_alone(torch, B, synth, H),
               "c5_layer": lambda: bench_c5_layer(torch, B, synth, H, max(5, K_STEPS // 5)),
+              "c2_layer": lambda: bench_windowed_layer(torch, B, synth, H, synth.C2, K_STEPS),
               "window_attn": lambda: bench_window_attn_alone(torch, B, synth, H, K_STEPS)}[args.only]
         print(json.dumps({"only": args.only, args.only: fn()}))
         return
@@ -243,6 +244,7 @@ def main():
         result["decode_c4_grouped_query"] = bench_decode_gqa(torch, B)
         result["full_accumulation_c2"] = bench_full_c2(torch, B, synth, H, max(5, K_STEPS // 5))
         result["prefill_c5_layer"] = bench_c5_layer(torch, B, synth, H, max(5, K_STEPS // 5))
+        result["prefill_c2_layer"] = bench_windowed_layer(torch, B, synth, H, synth.C2, K_STEPS)
         result["scores_from_lse_c3"] = bench_lse_c3(torch, B, H, w, p, q, k, v, scores, ws, K_STEPS)
         result["window_attention_c3"] = bench_window_attn_c3(torch, B, w, p, q, k, v, scores, ws, K_STEPS)
         result["full_accumulation_c3"] = bench_full_c3(torch, B, w, p, q, k, v, scores)
@@ -517,10 +519,16 @@ def bench_window_attn_alone(torch, B, synth, H, steps):
 def bench_c5_layer(torch, B, synth, H, steps):
     """One layer of the full-depth sweep (batch 4 x 32 heads x 16384, budget 3276): the
     shape at which the windowed score, the value prior and the compaction are bound by HBM
-    bandwidth.  Timing only: seeded Gaussian Q/K/V drawn on the device."""
-    w = synth.C5
+    bandwidth."""
+    return bench_windowed_layer(torch, B, synth, H, synth.C5, steps)
+
+
+def bench_windowed_layer(torch, B, synth, H, w, steps):
+    """The prefill step (scores, top-k, compaction) of one layer of workload `w`, per kernel
+    between events and as a whole back to back.  Timing only: seeded Gaussian Q/K/V drawn on
+    the device."""
     b, hq, hk, n, d = w.batch, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
-    g = torch.Generator(device="cuda"); g.manual_seed(synth.BASE_SEED + 5000)
+    g = torch.Generator(device="cuda"); g.manual_seed(synth.BASE_SEED + 1000 * w.cfg_id)
     q, k, v = (torch.randn((b, hh, n, d), device="cuda", generator=g).to(torch.bfloat16)
                for hh in (hq, hk, hk))
     p = H.params_for(w).with_strides(q, k, v)
@@ -555,7 +563,19 @@ def bench_c5_layer(torch, B, synth, H, steps):
            "score_pass2": kb + b * hq * w.window * d * 2 + b * hk * n * 4,
            "topk": b * hk * (n + w.budget) * 4,
            "compact": 4 * b * hk * w.budget * d * 2 + b * hk * w.budget * 12}
+    def step():
+        B.aha_prefill_scores(p, q, k, v, scores, ws)
+        B.aha_select_topk(p, scores, idx, ws)
+        B.aha_compact_kv(p, k, v, scores, idx, cache.k, cache.v, cache.scores, cache.pos,
+                         cache.free_slot)
+
+    e0 = ev()
+    for _ in range(4 * steps):
+        step()
+    e1 = ev()
+    torch.cuda.synchronize()
     out = {"workload": w.name + " (one layer)", "us_per_layer": sum(t.values()) * 1e3,
+           "back_to_back_us": e0.elapsed_time(e1) * 1e3 / (4 * steps),
            "tokens_per_s": b * n / (sum(t.values()) * 1e-3), "kernels": {}}
     for name in t:
         gbs = alg[name] / (t[name] * 1e-3) / 1e9
