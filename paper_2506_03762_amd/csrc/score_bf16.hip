@@ -75,6 +75,27 @@ __device__ __forceinline__ void colsum_update(const f32x16 (&acc)[kMB], float la
     // The empty asm keeps the masked and the unmasked instantiation apart: without it the
     // compiler merges the two branches and every block pays the per-element compare/select.
     if (MASK) asm volatile("" ::: "memory");
+    if constexpr (!MASK) {
+        // Four elements at a time - their scaled logits, their exponentials, their sums - and
+        // the instructions kept in that order: scheduled by register pressure alone, every
+        // exponential is followed at once by the addition that needs it, with a wait state
+        // (an issue slot of the wave) in between.
+#pragma unroll
+        for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+            for (int v0 = 0; v0 < 16; v0 += 4) {
+                float t[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) t[i] = fmaf(acc[mb][v0 + i], lam, -L);
+                asm volatile("" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) t[i] = fast_exp2(t[i]);
+                asm volatile("" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) col[mb][v0 + i] += t[i];
+            }
+        return;
+    }
 #pragma unroll
     for (int mb = 0; mb < kMB; ++mb)
 #pragma unroll
@@ -378,10 +399,11 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
             if (kb >= key_end) return;  // (a wave past the range's ragged end)
             if (kb + kWaveKeys - 1 <= tile_min) {
                 // every row of the tile sees all 64 keys: no masks, no skipped blocks
+                bf16x8 qf = query_fragment<D, NB>(sQ, nb0, 0, lane);
 #pragma unroll
                 for (int nb = nb0; nb < nb1; ++nb) {
                     f32x16 acc[kMB];
-                    mma_block<D, NB>(a, sQ, nb, lane, acc);
+                    mma_block_stream<D, NB>(a, sQ, nb, nb + 1 < nb1 ? nb + 1 : nb0, lane, qf, acc);
                     stats_update<false, ENT>(acc, lam[nb], 0, kb, lane, m[nb], s[nb], u[ENT ? nb : 0]);
                 }
                 return;
@@ -682,10 +704,11 @@ __global__ __launch_bounds__(256, 2) void bf16_pass2_kernel(ScoreGeom g, int n_q
                                f32x16 (&col)[kMB]) {
         if (kb + kWaveKeys - 1 <= tile_min) {
             // all rows of the tile see all 64 keys: no masks, no skipped blocks
+            bf16x8 qf = query_fragment<D, NB>(sQ, 0, 0, lane);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 f32x16 acc[kMB];
-                mma_block<D, NB>(a, sQ, nb, lane, acc);
+                mma_block_stream<D, NB>(a, sQ, nb, nb + 1 < NB ? nb + 1 : 0, lane, qf, acc);
                 colsum_update<false>(acc, lamr[nb], Lr[nb], 0, kb, lane, col);
             }
             return;

@@ -183,6 +183,40 @@ __device__ __forceinline__ void mma_block(const bf16x8 (&a)[kMB][D / 16], const 
     }
 }
 
+// The same product with the query fragments read AHEAD of their use: each fragment one
+// contraction step before its products, and fragment 0 of block `nb_next` behind the last
+// products of this block, so that it travels under the block's vector work (`first`: fragment
+// 0 of this block on entry, of block nb_next on exit).  A fragment read right before its
+// products exposes the LDS latency to the wave eight times per block; the scheduling barriers
+// keep the reads where they are written (the compiler would otherwise move each read back to
+// its use to save its four registers).
+template <int D, int NB>
+__device__ __forceinline__ bf16x8 query_fragment(const __bf16 *sQ, int nb, int ks, int lane) {
+    using S = TileSmem<D, NB>;
+    return *(const bf16x8 *)(sQ + (nb * 32 + (lane & 31)) * S::LD + (lane >> 5) * 8 + ks * 16);
+}
+template <int D, int NB>
+__device__ __forceinline__ void mma_block_stream(const bf16x8 (&a)[kMB][D / 16], const __bf16 *sQ,
+                                                 int nb, int nb_next, int lane, bf16x8 &first,
+                                                 f32x16 (&acc)[kMB]) {
+#pragma unroll
+    for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+    bf16x8 cur = first;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+        const bf16x8 nxt = ks + 1 < D / 16 ? query_fragment<D, NB>(sQ, nb, ks + 1, lane)
+                                           : query_fragment<D, NB>(sQ, nb_next, 0, lane);
+#pragma unroll
+        for (int mb = 0; mb < kMB; ++mb)
+            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb][ks], cur, acc[mb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        cur = nxt;
+    }
+    first = cur;
+}
+
 // Key row of accumulator element v of M block mb, for this lane.
 __device__ __forceinline__ int acc_key(int kb, int mb, int v, int lane) {
     return kb + mb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
