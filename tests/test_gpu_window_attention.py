@@ -94,6 +94,29 @@ def test_window_attention_with_logits_that_keep_rising(head_dim):
     check(w, w.window, (Q, K, V))
 
 
+def random_attention_case(seed):
+    rng = np.random.default_rng(seed)
+    d = int(rng.choice([64, 128])); G = int(rng.choice([1, 1, 2, 3, 4, 8]))
+    hk = int(rng.integers(1, 4)); b = int(rng.integers(1, 3))
+    n = int(rng.choice([rng.integers(1, 200), rng.integers(200, 1500), rng.integers(1500, 5000)]))
+    window = int(min(n, rng.choice([1, rng.integers(1, 40), rng.integers(40, 300)])))
+    dtype = "bf16" if rng.random() < 0.85 else "f32"
+    if dtype == "f32":
+        n = min(n, 600); window = min(window, n, 64)
+    w = synth.scaled(synth.C3, name="attn_%d" % seed, batch=b, n_q_heads=hk * G, n_kv_heads=hk,
+                     head_dim=d, seq_len=n, window=window, budget=max(1, n // 4),
+                     recent=min(window, max(1, n // 8)), dtype=dtype)
+    return w, window
+
+
+def test_window_attention_random_shapes():
+    """Seeded random shapes: sequence lengths 1 .. 5000, 1 .. 8 query heads per KV head, windows
+    of 1 .. 300 rows, both head sizes, both dtypes (single and paired row blocks, ragged key
+    ranges, more key ranges than steps)."""
+    for seed in range(40):
+        check(*random_attention_case(seed))
+
+
 def test_window_attention_token_major_layout():
     """Q/K/V stored [b, n, h, d] and passed by strides give the same output, bit for bit."""
     w = synth.scaled(BF, name="token_major", seq_len=1100, n_q_heads=8, n_kv_heads=2, window=64)
