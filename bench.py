@@ -134,6 +134,27 @@ def main():
     torch.cuda.synchronize()
     step_us = us_stats(step_evs)
 
+    # the same layer with the configuration's other budget (1024): selection and compaction change
+    import dataclasses
+    p_small = dataclasses.replace(p, budget=w.budget // 2)
+    idx_small = torch.empty((b, hk, w.budget // 2), dtype=torch.int32, device="cuda")
+    cache_small = B.CompactCache.empty(p_small)
+
+    def step_small():
+        B.aha_prefill_scores(p_small, q, k, v, scores, ws)
+        B.aha_select_topk(p_small, scores, idx_small, ws)
+        B.aha_compact_kv(p_small, k, v, scores, idx_small, cache_small.k, cache_small.v,
+                         cache_small.scores, cache_small.pos, cache_small.free_slot)
+
+    for _ in range(W_STEPS):
+        step_small()
+    e0 = ev()
+    for _ in range(K_STEPS):
+        step_small()
+    e1 = ev()
+    torch.cuda.synchronize()
+    step_small_us = e0.elapsed_time(e1) * 1e3 / K_STEPS
+
     # ------------------------------------------- per-kernel times (events) --
     # Events on the launch stream bracket every launch; between two launches that were
     # enqueued back to back they measure the kernel plus the dispatch gap before it (2-3 us
@@ -225,6 +246,7 @@ def main():
         "tokens_per_s": b * n / (ms_per_step * 1e-3),
         "step_us": {"mean_wall_clock": ms_per_step * 1e3, "median_events": step_us["median"],
                     "min_events": step_us["min"]},
+        "step_us_budget_1024": step_small_us,
         "decode_step_c3": {"back_to_back_us": decode_b2b_us,
                            "median_us": kstats["decode_step"]["median"],
                            "min_us": kstats["decode_step"]["min"],
