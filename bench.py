@@ -264,6 +264,7 @@ def main():
         "step_us": {"mean_wall_clock": ms_per_step * 1e3, "median_events": step_us["median"],
                     "min_events": step_us["min"]},
         "step_us_budget_1024": step_small_us,
+        "device_settle_ms": SETTLE_MS,  # untimed busy period before the warm-up steps (see settle)
         "decode_step_c3": {"back_to_back_us": decode_b2b_us,
                            "median_us": kstats["decode_step"]["median"],
                            "min_us": kstats["decode_step"]["min"],
