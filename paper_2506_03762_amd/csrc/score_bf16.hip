@@ -30,10 +30,40 @@ namespace aha {
 // times the maximum raw dot.
 // With ENT the first moment u = sum of exp2(t - m) * (t - m) is kept beside the sum: the
 // row's entropy is ln 2 * (log2 s - u / s) (Sec. 4.2, entropy of a softmax row).
-template <bool MASK, bool ENT>
+template <bool MASK, bool ENT, bool LAZY = false>
 __device__ __forceinline__ void stats_update(const f32x16 (&acc)[kMB], float lam, int pos, int kb,
                                              int lane, float &m, float &s, float &u) {
     if (MASK) asm volatile("" ::: "memory");
+    if constexpr (!MASK && LAZY) {
+        // (LAZY: full accumulation, where this loop is the kernel; in the windowed kernel the
+        // second code path costs registers that spill.)
+        // Unmasked blocks: `m` is a REFERENCE that sum and moment are relative to, not
+        // necessarily the running maximum (the final statistics m + log2 s and u / s do not
+        // depend on it).  As long as every lane has one, the block is summed against it as it
+        // stands - no maximum over the block's 32 elements - and the reference is only moved
+        // (by the exact update below, which also redoes this block) when a block's sum says
+        // that it has fallen more than 40 binades behind: fp32 has room for that, and a
+        // reference never lies above the largest logit seen, so nothing underflows that the
+        // exact update would have kept.
+        if (__builtin_amdgcn_ballot_w64(m == -INFINITY) == 0) {
+            float sum[4] = {0.f, 0.f, 0.f, 0.f}, mom[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float x = fmaf(acc[mb][v], lam, -m);
+                    const float e = fast_exp2(x);
+                    sum[v & 3] += e;
+                    if (ENT) mom[v & 3] = fmaf(e, x, mom[v & 3]);
+                }
+            const float bs = (sum[0] + sum[1]) + (sum[2] + sum[3]);
+            if (__builtin_amdgcn_ballot_w64(!(bs < 0x1p40f)) == 0) {  // (also: not a NaN)
+                s += bs;
+                if (ENT) u += (mom[0] + mom[1]) + (mom[2] + mom[3]);
+                return;
+            }
+        }
+    }
     float amax = -INFINITY;
 #pragma unroll
     for (int mb = 0; mb < kMB; ++mb)
@@ -306,7 +336,7 @@ __device__ __forceinline__ float value_prior_of_range(const ScoreGeom &g, int b,
 // ENT: the chunk's mean scaled logit under its own probabilities, E_c[t] = m + u / s, is
 // written to `partial_mean` beside the chunk's log2-sum-exp2; entropy_merge_kernel turns the
 // chunks of a row into its entropy.
-template <int D, int NB, bool ENT, bool ROWS = false, bool PRIOR = false>
+template <int D, int NB, bool ENT, bool ROWS = false, bool PRIOR = false, bool LAZY = false>
 __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_qtiles, int nparts,
                                                             int total_wgs, float *partial,
                                                             float *partial_mean, float *gamma,
@@ -404,7 +434,7 @@ __global__ __launch_bounds__(256, 2) void bf16_pass1_kernel(ScoreGeom g, int n_q
                 for (int nb = nb0; nb < nb1; ++nb) {
                     f32x16 acc[kMB];
                     mma_block_stream<D, NB>(a, sQ, nb, nb + 1 < nb1 ? nb + 1 : nb0, lane, qf, acc);
-                    stats_update<false, ENT>(acc, lam[nb], 0, kb, lane, m[nb], s[nb], u[ENT ? nb : 0]);
+                    stats_update<false, ENT, LAZY>(acc, lam[nb], 0, kb, lane, m[nb], s[nb], u[ENT ? nb : 0]);
                 }
                 return;
             }
@@ -878,7 +908,8 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
     float *nu = (float *)(w + pl.off_nu);
     static DeviceOnce once;
     const hipError_t ea = device_once(once, [] {
-        const void *kernels[7] = {(const void *)bf16_pass1_kernel<D, NB, false>,
+        const void *kernels[8] = {(const void *)bf16_pass1_kernel<D, NB, false>,
+                                  (const void *)bf16_pass1_kernel<D, NB, false, false, false, true>,
                                   (const void *)bf16_pass1_kernel<D, NB, false, false, true>,
                                   (const void *)bf16_pass1_kernel<D, NB, true>,
                                   (const void *)bf16_pass1_kernel<D, NB, false, true>,
@@ -908,6 +939,11 @@ static hipError_t launch_t(const ScoreGeom &g, const PrefillPlan &pl, void *ws, 
             hipLaunchKernelGGL((bf16_pass1_kernel<D, NB, false, false, true>), xcd_grid(wgs1),
                                dim3(256), S::bytes + kPriorSmem, st, g, pl.n_qtiles, pl.nchunks, (int)wgs1,
                                partial, (float *)nullptr, gamma, gbm, nu);
+        else if (pl.n_qtiles > 1)  // full accumulation: block sums against a lazy reference
+            hipLaunchKernelGGL((bf16_pass1_kernel<D, NB, false, false, false, true>), xcd_grid(wgs1),
+                               dim3(256), S::bytes, st, g, pl.n_qtiles, pl.nchunks, (int)wgs1,
+                               partial, (float *)nullptr, (float *)nullptr, (float *)nullptr,
+                               (float *)nullptr);
         else
             hipLaunchKernelGGL((bf16_pass1_kernel<D, NB, false>), xcd_grid(wgs1), dim3(256),
                                S::bytes, st, g, pl.n_qtiles, pl.nchunks, (int)wgs1, partial,
